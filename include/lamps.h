@@ -1,0 +1,184 @@
+/*
+ * liblamps -- the GPU work of one serving iteration under LAMPS
+ * (arXiv 2410.18248), for one AMD MI355X (gfx950).
+ *
+ * The paper's scheduler (Algorithm 1) forms a running batch every iteration
+ * and executes it; requests that reach an API call leave the batch and their
+ * KV cache is handled by one of three strategies (Section 1, Section 4.2):
+ *   Preserve -- the cache stays in GPU memory, the request is simply not run;
+ *   Discard  -- the cache is dropped (blocks freed) and recomputed later;
+ *   Swap     -- the cache is offloaded to CPU memory and reloaded on return.
+ * This library is what sits under "Execute runningBatch": single-query
+ * attention over a paged KV cache for the running requests (Section 2.2
+ * equation; paging as in Section 7's description of paged attention), the
+ * block copies that implement Swap, and the block free list.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every call returns a lamps_status (0 = ok, negative =
+ *     error) unless stated otherwise.  On error nothing has been enqueued and
+ *     no library state has changed; lamps_last_error() describes it.
+ *   - The CALLER owns all data memory: both KV pools, the workspace, q / out /
+ *     block tables / context lengths / masks (device memory) and the swap
+ *     buffers (pinned host memory), and both HIP streams.  The library owns
+ *     only the lamps_ctx (free list, ticket table, events, a small pinned
+ *     ring for block-id lists).
+ *   - "device" pointers are HIP device memory of the current device; "host"
+ *     pointers are ordinary process memory unless marked pinned.
+ *   - Arguments that live in device memory (block_table, ctx_lens,
+ *     running_mask) are NOT validated: no call synchronises with the device.
+ *   - A context is not thread-safe; calls on it must be serialised.
+ *
+ * KV pool layout (part of the ABI, so swap images can be checked byte by byte)
+ *   Keys and values live in two pools of identical shape
+ *       pool[num_blocks][num_layers][num_kv_heads][block_size][head_dim]
+ *   of `dtype` elements, C order.  Cached position t of a request is slot
+ *   t % block_size of physical block block_table[request][t / block_size].
+ *   A block id names that block in every layer, keys and values.
+ *   Host image of one swapped block = its key-pool bytes (all layers)
+ *   followed by its value-pool bytes; images follow each other in the order
+ *   of the id list.
+ */
+#ifndef LAMPS_H
+#define LAMPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lamps_ctx lamps_ctx; /* opaque, library-owned */
+
+typedef enum { LAMPS_F32 = 0, LAMPS_BF16 = 1 } lamps_dtype;
+
+typedef enum {
+    LAMPS_OK = 0,
+    LAMPS_ERR_INVALID = -1,     /* null pointer, bad size, unsupported geometry      */
+    LAMPS_ERR_RANGE = -2,       /* block id / layer / batch / ticket out of range    */
+    LAMPS_ERR_DUP = -3,         /* the same block id twice in one list               */
+    LAMPS_ERR_DOUBLE_FREE = -4, /* id is not allocated (free, swap of a free block)  */
+    LAMPS_ERR_BUSY = -5,        /* ticket not complete yet (lamps_ticket_query)      */
+    LAMPS_ERR_NOMEM = -6,       /* not enough free blocks / host allocation failed   */
+    LAMPS_ERR_HIP = -7          /* a HIP runtime call failed                         */
+} lamps_status;
+
+typedef struct {
+    int32_t num_layers;         /* L >= 1                                            */
+    int32_t num_q_heads;        /* H, a multiple of num_kv_heads                     */
+    int32_t num_kv_heads;       /* H_kv; query head h reads kv head h / (H / H_kv)   */
+    int32_t head_dim;           /* d_h: bf16 {64,128,256}, f32 {32,64,128}           */
+    int32_t block_size;         /* tokens per block, a power of two >= 16            */
+    int32_t num_blocks;         /* physical blocks in each pool                      */
+    int32_t max_blocks_per_req; /* row length of the block table                     */
+    int32_t max_batch;          /* largest `batch` passed to lamps_decode_attn       */
+    int32_t dtype;              /* lamps_dtype of q, the pools and out               */
+    float softmax_scale;        /* 0 => 1/sqrt(head_dim), the Section 2.2 equation   */
+    int32_t part_tokens;        /* tokens per split partition, multiple of
+                                   block_size; 0 => library default                  */
+    int64_t staging_bytes;      /* device staging per swap direction; 0 => default   */
+} lamps_config;
+
+/* ---- sizes (pure functions of the config; return 0 on an invalid config) ---- */
+
+/* M of equations (1)-(3): bytes of KV cache per token over all layers,
+ * 2 * L * H_kv * d_h * sizeof(dtype) (Section 2.2.1). */
+size_t lamps_kv_bytes_per_token(const lamps_config *cfg);
+/* Bytes of one block's host image: keys + values, all layers. */
+size_t lamps_block_bytes(const lamps_config *cfg);
+/* Bytes the caller must allocate for EACH of the two pools. */
+size_t lamps_pool_bytes(const lamps_config *cfg);
+/* Bytes of device workspace the caller must allocate (256-byte aligned):
+ * split partition partials and the two swap staging areas. */
+size_t lamps_workspace_bytes(const lamps_config *cfg);
+
+/* ---- life cycle ---- */
+
+/* Creates a context over caller-owned device memory and streams (hipStream_t
+ * passed as void*; NULL = the default stream).  swap_out_stream and
+ * swap_in_stream may be the same stream, and may equal compute_stream (then
+ * nothing overlaps).  All blocks start free; a fresh pool hands out ids
+ * 0, 1, 2, ...  Makes no HIP call. */
+int lamps_create(const lamps_config *cfg, void *k_pool, void *v_pool, void *workspace,
+                 void *compute_stream, void *swap_out_stream, void *swap_in_stream,
+                 lamps_ctx **out);
+/* Waits for the library's outstanding stream work, releases events and the
+ * pinned id ring.  Caller memory is not touched. */
+int lamps_destroy(lamps_ctx *ctx);
+
+/* ---- decode attention: Section 2.2 equation over the paged cache ---- */
+
+/* One layer of one iteration, enqueued on the compute stream; returns at once.
+ * For every request r < batch with running_mask[r] != 0 and every query head h:
+ *   out[r][h][:] = softmax(q[r][h] . K_r^T * scale) . V_r
+ * over exactly the first ctx_lens[r] cached positions of r (kv head h / G).
+ * Rows of requests with running_mask[r] == 0 (Preserve / Swap / Discard while
+ * the API call lasts; not in Algorithm 1's running batch) are not written and
+ * their blocks are not read.  ctx_lens[r] == 0 gives a zero row.  Table
+ * entries at or beyond ceil(ctx_lens[r] / block_size) are never read, nor are
+ * slots at or beyond ctx_lens[r].  Accumulation is fp32; bf16 output is
+ * rounded to nearest even.  Results are bit-reproducible for fixed arguments
+ * and do not depend on which physical blocks hold the data.
+ *   q, out        device, [batch][H][d_h] dtype
+ *   block_table   device, int32 [batch][max_blocks_per_req]
+ *   ctx_lens      device, int32 [batch], each <= max_blocks_per_req*block_size
+ *   running_mask  device, uint8 [batch]
+ * Errors: INVALID (null), RANGE (layer, batch). */
+int lamps_decode_attn(lamps_ctx *ctx, int32_t layer, int32_t batch, const void *q,
+                      const int32_t *block_table, const int32_t *ctx_lens,
+                      const uint8_t *running_mask, void *out);
+
+/* ---- Swap handling strategy (Section 1; Section 4.2) ---- */
+
+/* Copies the n listed blocks (all layers, keys and values) into host_buf
+ * (PINNED host memory, n * lamps_block_bytes bytes, alive until the ticket
+ * completes) on the swap-out stream: blocks are gathered into contiguous
+ * device staging, then moved by hipMemcpyAsync.  The copy is ordered after all
+ * compute-stream work enqueued before this call and after earlier swap-ins
+ * into the same blocks.  The pool is not modified and the blocks stay
+ * allocated; the caller frees them afterwards with lamps_free_blocks, and
+ * their reuse is held back on the device until the copy has finished (the
+ * delay before the memory is fully released, Section 4.2).
+ * block_ids is a HOST array, copied inside the call.  *ticket identifies the
+ * copy.  n == 0 is allowed.
+ * Errors: INVALID, RANGE, DUP, DOUBLE_FREE (a listed block is not allocated),
+ * NOMEM, HIP. */
+int lamps_swap_out(lamps_ctx *ctx, const int32_t *block_ids, int32_t n, void *host_buf,
+                   uint64_t *ticket);
+/* Mirror image: writes image i of host_buf into block block_ids[i] on the
+ * swap-in stream (hipMemcpyAsync into staging, then scatter).  The listed
+ * blocks must be allocated (typically just obtained from lamps_alloc_blocks;
+ * they need not be the blocks the images came from).  No other block changes.
+ * A request may run again only in steps enqueued after
+ * lamps_compute_wait(ticket). */
+int lamps_swap_in(lamps_ctx *ctx, const void *host_buf, const int32_t *block_ids, int32_t n,
+                  uint64_t *ticket);
+
+/* LAMPS_OK if the ticket's copy has finished, LAMPS_ERR_BUSY if not. */
+int lamps_ticket_query(lamps_ctx *ctx, uint64_t ticket);
+/* Blocks the calling host thread until the ticket's copy has finished. */
+int lamps_ticket_wait(lamps_ctx *ctx, uint64_t ticket);
+/* Makes the compute stream wait (on the device) for the ticket's copy. */
+int lamps_compute_wait(lamps_ctx *ctx, uint64_t ticket);
+
+/* ---- block free list (Discard; and the release half of Swap) ---- */
+
+/* Pops n ids (LIFO: the most recently freed id first; a fresh pool yields
+ * 0, 1, 2, ...).  If a popped block still has an unfinished swap-out, the
+ * compute and swap-in streams are made to wait for it before any later work.
+ * Errors: INVALID, NOMEM (fewer than n free; nothing is popped). */
+int lamps_alloc_blocks(lamps_ctx *ctx, int32_t n, int32_t *block_ids_out);
+/* Pushes the listed ids, in the order given; their contents become undefined.
+ * Errors: INVALID, RANGE, DUP, DOUBLE_FREE; on error nothing is freed. */
+int lamps_free_blocks(lamps_ctx *ctx, const int32_t *block_ids, int32_t n);
+/* Number of free blocks, or a negative status. */
+int lamps_num_free(lamps_ctx *ctx);
+
+/* Text of the last error on this context ("" if none).  With ctx == NULL,
+ * the last error of a failed lamps_create on this thread. */
+const char *lamps_last_error(lamps_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAMPS_H */

@@ -1,0 +1,181 @@
+"""ctypes binding of liblamps.so -- argument marshalling only.
+
+Pointers may be given as ints, ctypes pointers, or objects with ``data_ptr()``
+(torch tensors).  Nothing here computes: every step of the path runs in the
+library's kernels, and there is no fallback if the library is missing.
+"""
+import ctypes
+import os
+
+LAMPS_F32, LAMPS_BF16 = 0, 1
+
+STATUS = {0: "LAMPS_OK", -1: "LAMPS_ERR_INVALID", -2: "LAMPS_ERR_RANGE", -3: "LAMPS_ERR_DUP",
+          -4: "LAMPS_ERR_DOUBLE_FREE", -5: "LAMPS_ERR_BUSY", -6: "LAMPS_ERR_NOMEM",
+          -7: "LAMPS_ERR_HIP"}
+LAMPS_ERR_BUSY = -5
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_lib = None
+
+
+class LampsError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("%s: %s" % (STATUS.get(status, status), text))
+        self.status = status
+
+
+class LampsConfig(ctypes.Structure):
+    """Mirror of ``lamps_config``."""
+    _fields_ = [("num_layers", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+                ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("block_size", ctypes.c_int32), ("num_blocks", ctypes.c_int32),
+                ("max_blocks_per_req", ctypes.c_int32), ("max_batch", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("part_tokens", ctypes.c_int32), ("staging_bytes", ctypes.c_int64)]
+
+
+def lib_path():
+    return os.path.join(_HERE, "liblamps.so")
+
+
+def load_library():
+    """Loads liblamps.so; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError("liblamps.so is not built: run `python -m paper_2410_18248_amd.build`")
+    lib = ctypes.CDLL(path)
+    vp, i32, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64
+    cfgp = ctypes.POINTER(LampsConfig)
+    for name in ("lamps_kv_bytes_per_token", "lamps_block_bytes", "lamps_pool_bytes",
+                 "lamps_workspace_bytes"):
+        getattr(lib, name).restype = ctypes.c_size_t
+        getattr(lib, name).argtypes = [cfgp]
+    sig = {
+        "lamps_create": [cfgp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)],
+        "lamps_destroy": [vp],
+        "lamps_decode_attn": [vp, i32, i32, vp, vp, vp, vp, vp],
+        "lamps_swap_out": [vp, vp, i32, vp, ctypes.POINTER(u64)],
+        "lamps_swap_in": [vp, vp, vp, i32, ctypes.POINTER(u64)],
+        "lamps_ticket_query": [vp, u64],
+        "lamps_ticket_wait": [vp, u64],
+        "lamps_compute_wait": [vp, u64],
+        "lamps_alloc_blocks": [vp, i32, vp],
+        "lamps_free_blocks": [vp, vp, i32],
+        "lamps_num_free": [vp],
+    }
+    for name, args in sig.items():
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = args
+    lib.lamps_last_error.restype = ctypes.c_char_p
+    lib.lamps_last_error.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if hasattr(x, "ctypes"):            # numpy array
+        return x.ctypes.data
+    return ctypes.cast(x, ctypes.c_void_p).value
+
+
+def _ids(block_ids):
+    ids = list(block_ids)
+    return (ctypes.c_int32 * max(len(ids), 1))(*ids), len(ids)
+
+
+def lamps_kv_bytes_per_token(cfg):
+    return load_library().lamps_kv_bytes_per_token(ctypes.byref(cfg))
+
+
+def lamps_block_bytes(cfg):
+    return load_library().lamps_block_bytes(ctypes.byref(cfg))
+
+
+def lamps_pool_bytes(cfg):
+    return load_library().lamps_pool_bytes(ctypes.byref(cfg))
+
+
+def lamps_workspace_bytes(cfg):
+    return load_library().lamps_workspace_bytes(ctypes.byref(cfg))
+
+
+class Lamps:
+    """One ``lamps_ctx``.  Methods carry the C names without the prefix."""
+
+    def __init__(self, cfg, k_pool, v_pool, workspace, compute_stream=0, swap_out_stream=0,
+                 swap_in_stream=0):
+        self.lib = load_library()
+        self.cfg = cfg
+        self._keep = (k_pool, v_pool, workspace)     # the caller's memory must outlive the context
+        h = ctypes.c_void_p()
+        rc = self.lib.lamps_create(ctypes.byref(cfg), _ptr(k_pool), _ptr(v_pool), _ptr(workspace),
+                                   compute_stream or None, swap_out_stream or None,
+                                   swap_in_stream or None, ctypes.byref(h))
+        if rc != 0:
+            raise LampsError(rc, self.lib.lamps_last_error(None).decode())
+        self.h = h
+
+    def _check(self, rc):
+        if rc < 0:
+            raise LampsError(rc, self.lib.lamps_last_error(self.h).decode())
+        return rc
+
+    def destroy(self):
+        if self.h:
+            rc = self.lib.lamps_destroy(self.h)
+            self.h = None
+            if rc < 0:
+                raise LampsError(rc, "lamps_destroy")
+
+    def decode_attn(self, layer, batch, q, block_table, ctx_lens, running_mask, out):
+        self._check(self.lib.lamps_decode_attn(self.h, layer, batch, _ptr(q), _ptr(block_table),
+                                               _ptr(ctx_lens), _ptr(running_mask), _ptr(out)))
+
+    def swap_out(self, block_ids, host_buf):
+        arr, n = _ids(block_ids)
+        t = ctypes.c_uint64()
+        self._check(self.lib.lamps_swap_out(self.h, arr, n, _ptr(host_buf), ctypes.byref(t)))
+        return t.value
+
+    def swap_in(self, host_buf, block_ids):
+        arr, n = _ids(block_ids)
+        t = ctypes.c_uint64()
+        self._check(self.lib.lamps_swap_in(self.h, _ptr(host_buf), arr, n, ctypes.byref(t)))
+        return t.value
+
+    def ticket_query(self, ticket):
+        rc = self.lib.lamps_ticket_query(self.h, ticket)
+        if rc == LAMPS_ERR_BUSY:
+            return False
+        self._check(rc)
+        return True
+
+    def ticket_wait(self, ticket):
+        self._check(self.lib.lamps_ticket_wait(self.h, ticket))
+
+    def compute_wait(self, ticket):
+        self._check(self.lib.lamps_compute_wait(self.h, ticket))
+
+    def alloc_blocks(self, n):
+        arr = (ctypes.c_int32 * max(n, 1))()
+        self._check(self.lib.lamps_alloc_blocks(self.h, n, arr))
+        return list(arr[:n])
+
+    def free_blocks(self, block_ids):
+        arr, n = _ids(block_ids)
+        self._check(self.lib.lamps_free_blocks(self.h, arr, n))
+
+    def num_free(self):
+        return self._check(self.lib.lamps_num_free(self.h))
+
+    def last_error(self):
+        return self.lib.lamps_last_error(self.h).decode()

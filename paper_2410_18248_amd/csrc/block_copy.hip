@@ -1,0 +1,70 @@
+// KV block gather / scatter for the Swap handling strategy (arXiv 2410.18248,
+// Section 1 and Section 4.2): the blocks of a request that enters an API call
+// are scattered over the pool; they are packed into one contiguous staging
+// area so that a single DMA moves them to pinned host memory, and unpacked the
+// other way when the API returns.
+//
+// Staging image i = key-pool bytes of block ids[i] (all layers) followed by its
+// value-pool bytes.  Pure 16-byte copies, bit-exact; grid.y walks (block, pool)
+// pairs, grid.x and a stride loop walk the bytes of one such half.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+
+namespace lamps {
+namespace {
+
+constexpr int kCopyThreads = 256;
+
+template <bool GATHER>
+__global__ __launch_bounds__(kCopyThreads) void block_copy(uint4 *k_pool, uint4 *v_pool,
+                                                           const int32_t *ids, size_t half_vecs,
+                                                           uint4 *staging)
+{
+    const int i = blockIdx.y >> 1, which = blockIdx.y & 1;
+    const size_t b = (size_t)ids[i];
+    uint4 *pool = (which ? v_pool : k_pool) + b * half_vecs;
+    uint4 *img = staging + ((size_t)i * 2 + which) * half_vecs;
+    for (size_t x = (size_t)blockIdx.x * kCopyThreads + threadIdx.x; x < half_vecs;
+         x += (size_t)gridDim.x * kCopyThreads) {
+        if (GATHER)
+            img[x] = pool[x];
+        else
+            pool[x] = img[x];
+    }
+}
+
+template <bool GATHER>
+hipError_t launch(void *k_pool, void *v_pool, const int32_t *ids, int32_t n, size_t half_bytes,
+                  void *staging, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    if (n < 0 || 2 * (int64_t)n > 65535 || half_bytes % 16 != 0) return hipErrorInvalidValue;
+    const size_t half_vecs = half_bytes / 16;
+    // four 16-byte copies per thread per pass keeps loads in flight without a huge grid
+    size_t gx = (half_vecs + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
+    if (gx < 1) gx = 1;
+    if (gx > 256) gx = 256;
+    dim3 grid((unsigned)gx, (unsigned)(2 * n));
+    hipLaunchKernelGGL(block_copy<GATHER>, grid, dim3(kCopyThreads), 0, stream,
+                       static_cast<uint4 *>(k_pool), static_cast<uint4 *>(v_pool), ids, half_vecs,
+                       static_cast<uint4 *>(staging));
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gather(const void *k_pool, const void *v_pool, const int32_t *ids, int32_t n,
+                         size_t half_bytes, void *staging, hipStream_t stream)
+{
+    return launch<true>(const_cast<void *>(k_pool), const_cast<void *>(v_pool), ids, n, half_bytes,
+                        staging, stream);
+}
+
+hipError_t launch_scatter(void *k_pool, void *v_pool, const int32_t *ids, int32_t n,
+                          size_t half_bytes, const void *staging, hipStream_t stream)
+{
+    return launch<false>(k_pool, v_pool, ids, n, half_bytes, const_cast<void *>(staging), stream);
+}
+
+}  // namespace lamps

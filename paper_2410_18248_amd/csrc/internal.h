@@ -1,0 +1,39 @@
+// Internal launcher interface between the host half of liblamps (lamps.cpp)
+// and its kernels.  Not part of the ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lamps {
+
+struct DecodeArgs {
+    const void *q;            // [batch][H][D]
+    const void *k_pool;       // pool[block][layer][kv_head][slot][d]
+    const void *v_pool;
+    const int32_t *block_table;  // [batch][max_blocks]
+    const int32_t *ctx_lens;     // [batch]
+    const uint8_t *running;      // [batch]
+    float *partials;          // [batch][H][max_parts][D + 2]
+    void *out;                // [batch][H][D]
+    int32_t batch, layer, num_layers, num_q_heads, num_kv_heads, head_dim;
+    int32_t block_size, log2_block_size, max_blocks, part_tokens, max_parts;
+    int32_t bf16;             // 0: fp32 storage, 1: bf16 storage
+    float scale_log2e;        // softmax scale * log2(e)
+};
+
+// Heads of one kv group handled by one workgroup for this geometry
+// (0 if the geometry is not supported).
+int decode_heads_per_group(int bf16, int head_dim, int group);
+
+// Enqueues the split partial kernel and the merge kernel.
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
+
+// Gather: staging image i (key bytes then value bytes of block ids[i]) <- pools.
+// Scatter: the reverse.  `half_bytes` = bytes of one block in one pool, a
+// multiple of 16.  `ids` must be readable by the device.
+hipError_t launch_gather(const void *k_pool, const void *v_pool, const int32_t *ids, int32_t n,
+                         size_t half_bytes, void *staging, hipStream_t stream);
+hipError_t launch_scatter(void *k_pool, void *v_pool, const int32_t *ids, int32_t n,
+                          size_t half_bytes, const void *staging, hipStream_t stream);
+
+}  // namespace lamps

@@ -1,0 +1,528 @@
+// Host half of liblamps: the C ABI of include/lamps.h.
+//
+// Owns what the paper's engine keeps per model replica around "Execute
+// runningBatch" (arXiv 2410.18248, Algorithm 1): the free list of KV blocks
+// (Discard frees, Swap frees after its copy, an API return allocates), and the
+// ordering between the swap copies and the decode steps.  All data memory and
+// the streams belong to the caller; kernels are in decode_attn.hip and
+// block_copy.hip.
+#include "lamps.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "internal.h"
+
+namespace {
+
+thread_local std::string g_create_error;
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Derived {
+    size_t elem = 0, half_bytes = 0, block_bytes = 0, pool_bytes = 0;
+    size_t partial_bytes = 0, staging_bytes = 0, workspace_bytes = 0;
+    int part_tokens = 0, max_parts = 0, log2_bs = 0, blocks_per_chunk = 0;
+    float scale_log2e = 0.f;
+};
+
+// Validates a config and derives the sizes; returns an error text or nullptr.
+const char *derive(const lamps_config *c, Derived *d)
+{
+    if (!c) return "config is null";
+    if (c->dtype != LAMPS_F32 && c->dtype != LAMPS_BF16) return "dtype must be LAMPS_F32 or LAMPS_BF16";
+    if (c->num_layers < 1 || c->num_q_heads < 1 || c->num_kv_heads < 1 || c->head_dim < 1 ||
+        c->num_blocks < 1 || c->max_blocks_per_req < 1 || c->max_batch < 1)
+        return "sizes must be positive";
+    if (c->num_q_heads % c->num_kv_heads != 0) return "num_q_heads must be a multiple of num_kv_heads";
+    const int bf16 = c->dtype == LAMPS_BF16;
+    if (lamps::decode_heads_per_group(bf16, c->head_dim, c->num_q_heads / c->num_kv_heads) == 0)
+        return "unsupported head_dim for this dtype (bf16: 64/128/256, f32: 32/64/128)";
+    if (c->block_size < 16 || (c->block_size & (c->block_size - 1)) != 0)
+        return "block_size must be a power of two >= 16";
+    if ((int64_t)c->max_blocks_per_req * c->block_size > (int64_t)1 << 30) return "context too long";
+    d->elem = bf16 ? 2 : 4;
+    d->log2_bs = 0;
+    while ((1 << d->log2_bs) < c->block_size) ++d->log2_bs;
+    d->half_bytes = (size_t)c->num_layers * c->num_kv_heads * c->block_size * c->head_dim * d->elem;
+    d->block_bytes = 2 * d->half_bytes;
+    d->pool_bytes = d->half_bytes * (size_t)c->num_blocks;
+    d->part_tokens = c->part_tokens;
+    if (d->part_tokens == 0) d->part_tokens = c->block_size > 256 ? c->block_size : 256;
+    if (d->part_tokens < 0 || d->part_tokens % c->block_size != 0)
+        return "part_tokens must be a positive multiple of block_size";
+    const int64_t max_ctx = (int64_t)c->max_blocks_per_req * c->block_size;
+    d->max_parts = (int)((max_ctx + d->part_tokens - 1) / d->part_tokens);
+    if (d->max_parts > 65535) return "too many partitions per request; raise part_tokens";
+    d->partial_bytes = (size_t)c->max_batch * c->num_q_heads * d->max_parts * (c->head_dim + 2) * 4;
+    if (c->staging_bytes < 0) return "staging_bytes is negative";
+    size_t st = c->staging_bytes ? (size_t)c->staging_bytes : (size_t)64 << 20;
+    if (c->staging_bytes == 0 && st < d->block_bytes) st = d->block_bytes;
+    if (st < d->block_bytes) return "staging_bytes is smaller than one block image";
+    size_t bpc = st / d->block_bytes;
+    if (bpc > 16384) bpc = 16384;               // keeps the copy grid's y dimension legal
+    if (bpc > (size_t)c->num_blocks) bpc = c->num_blocks;
+    d->blocks_per_chunk = (int)bpc;
+    d->staging_bytes = bpc * d->block_bytes;
+    d->workspace_bytes = align256(d->partial_bytes) + 2 * align256(d->staging_bytes);
+    const float scale = c->softmax_scale != 0.f ? c->softmax_scale : 1.0f / std::sqrt((float)c->head_dim);
+    d->scale_log2e = scale * 1.4426950408889634f;
+    return nullptr;
+}
+
+struct Ticket {
+    hipEvent_t ev;
+    size_t ring_slots;
+};
+
+}  // namespace
+
+struct lamps_ctx {
+    lamps_config cfg;
+    Derived d;
+    char *k_pool, *v_pool;
+    float *partials;
+    char *stage_out, *stage_in;
+    hipStream_t cs, os, is;
+
+    std::vector<int32_t> free_stack;
+    std::vector<uint8_t> allocated;
+    std::vector<uint64_t> out_guard, in_guard;  // last swap-out / swap-in ticket per block, 0 = none
+    std::vector<uint32_t> mark;                 // duplicate detection, by epoch
+    uint32_t epoch = 0;
+
+    std::deque<Ticket> tickets;                 // tickets[i] has id base_ticket + i
+    uint64_t base_ticket = 1;
+    std::vector<hipEvent_t> spare_events;
+    hipEvent_t fence = nullptr;
+    int32_t *ring = nullptr;                    // pinned; id lists read by the copy kernels
+    size_t ring_cap = 0;
+    uint64_t ring_head = 0, ring_tail = 0;      // monotonic slot counters
+    std::string err;
+};
+
+namespace {
+
+int fail(lamps_ctx *c, int code, const std::string &msg)
+{
+    if (c) c->err = msg;
+    return code;
+}
+
+int hip_fail(lamps_ctx *c, const char *what, hipError_t e)
+{
+    return fail(c, LAMPS_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define LAMPS_HIP(call)                                        \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return hip_fail(c, #call, e_);   \
+    } while (0)
+
+// Retires finished tickets from the front; releases their events and ring slots.
+void retire_finished(lamps_ctx *c)
+{
+    while (!c->tickets.empty() && hipEventQuery(c->tickets.front().ev) == hipSuccess) {
+        c->spare_events.push_back(c->tickets.front().ev);
+        c->ring_tail += c->tickets.front().ring_slots;
+        c->tickets.pop_front();
+        ++c->base_ticket;
+    }
+}
+
+// Blocks until the oldest ticket has finished, then retires it.
+int retire_oldest(lamps_ctx *c)
+{
+    LAMPS_HIP(hipEventSynchronize(c->tickets.front().ev));
+    retire_finished(c);
+    return LAMPS_OK;
+}
+
+bool ticket_known(const lamps_ctx *c, uint64_t t)
+{
+    return t >= 1 && t < c->base_ticket + c->tickets.size();
+}
+
+bool ticket_done(lamps_ctx *c, uint64_t t)
+{
+    if (t < c->base_ticket) return true;
+    retire_finished(c);
+    if (t < c->base_ticket) return true;
+    return hipEventQuery(c->tickets[t - c->base_ticket].ev) == hipSuccess;
+}
+
+hipEvent_t ticket_event(lamps_ctx *c, uint64_t t) { return c->tickets[t - c->base_ticket].ev; }
+
+int ensure_runtime(lamps_ctx *c)
+{
+    if (!c->fence) LAMPS_HIP(hipEventCreateWithFlags(&c->fence, hipEventDisableTiming));
+    if (!c->ring) {
+        c->ring_cap = (size_t)c->cfg.num_blocks * 2;
+        if (c->ring_cap < 1024) c->ring_cap = 1024;
+        void *p = nullptr;
+        LAMPS_HIP(hipHostMalloc(&p, c->ring_cap * sizeof(int32_t), hipHostMallocDefault));
+        c->ring = static_cast<int32_t *>(p);
+    }
+    return LAMPS_OK;
+}
+
+int new_event(lamps_ctx *c, hipEvent_t *ev)
+{
+    if (!c->spare_events.empty()) {
+        *ev = c->spare_events.back();
+        c->spare_events.pop_back();
+        return LAMPS_OK;
+    }
+    LAMPS_HIP(hipEventCreateWithFlags(ev, hipEventDisableTiming));
+    return LAMPS_OK;
+}
+
+// Reserves n contiguous ring slots; *slots is what the ticket must give back.
+int ring_reserve(lamps_ctx *c, int32_t n, int32_t **where, size_t *slots)
+{
+    for (;;) {
+        size_t pos = (size_t)(c->ring_head % c->ring_cap);
+        size_t pad = pos + (size_t)n > c->ring_cap ? c->ring_cap - pos : 0;
+        if (c->ring_head + pad + n - c->ring_tail <= c->ring_cap) {
+            c->ring_head += pad;
+            *where = c->ring + (size_t)(c->ring_head % c->ring_cap);
+            c->ring_head += n;
+            *slots = pad + n;
+            return LAMPS_OK;
+        }
+        if (c->tickets.empty()) return fail(c, LAMPS_ERR_NOMEM, "id ring too small for this list");
+        int rc = retire_oldest(c);
+        if (rc != LAMPS_OK) return rc;
+    }
+}
+
+// Checks an id list: range, duplicates, and (if want_allocated) that every block is allocated.
+int check_ids(lamps_ctx *c, const int32_t *ids, int32_t n, const char *who)
+{
+    if (n < 0) return fail(c, LAMPS_ERR_INVALID, std::string(who) + ": n is negative");
+    if (n > 0 && !ids) return fail(c, LAMPS_ERR_INVALID, std::string(who) + ": block_ids is null");
+    if (++c->epoch == 0) {
+        std::fill(c->mark.begin(), c->mark.end(), 0u);
+        c->epoch = 1;
+    }
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t b = ids[i];
+        if (b < 0 || b >= c->cfg.num_blocks)
+            return fail(c, LAMPS_ERR_RANGE, std::string(who) + ": block id out of range");
+        if (c->mark[b] == c->epoch)
+            return fail(c, LAMPS_ERR_DUP, std::string(who) + ": duplicate block id");
+        c->mark[b] = c->epoch;
+    }
+    for (int32_t i = 0; i < n; ++i)
+        if (!c->allocated[ids[i]])
+            return fail(c, LAMPS_ERR_DOUBLE_FREE, std::string(who) + ": block is not allocated");
+    return LAMPS_OK;
+}
+
+// Makes `stream` wait for every unfinished ticket named in guard[ids[*]].
+int wait_guards(lamps_ctx *c, hipStream_t stream, const std::vector<uint64_t> &guard,
+                const int32_t *ids, int32_t n)
+{
+    uint64_t last = 0;
+    std::vector<uint64_t> seen;
+    for (int32_t i = 0; i < n; ++i) {
+        const uint64_t t = guard[ids[i]];
+        if (t == 0 || t == last || t < c->base_ticket) continue;
+        last = t;
+        bool dup = false;
+        for (uint64_t s : seen) dup |= (s == t);
+        if (dup) continue;
+        seen.push_back(t);
+        if (!ticket_done(c, t)) LAMPS_HIP(hipStreamWaitEvent(stream, ticket_event(c, t), 0));
+    }
+    return LAMPS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lamps_kv_bytes_per_token(const lamps_config *cfg)
+{
+    Derived d;
+    if (derive(cfg, &d)) return 0;
+    return 2 * (size_t)cfg->num_layers * cfg->num_kv_heads * cfg->head_dim * d.elem;
+}
+
+size_t lamps_block_bytes(const lamps_config *cfg)
+{
+    Derived d;
+    return derive(cfg, &d) ? 0 : d.block_bytes;
+}
+
+size_t lamps_pool_bytes(const lamps_config *cfg)
+{
+    Derived d;
+    return derive(cfg, &d) ? 0 : d.pool_bytes;
+}
+
+size_t lamps_workspace_bytes(const lamps_config *cfg)
+{
+    Derived d;
+    return derive(cfg, &d) ? 0 : d.workspace_bytes;
+}
+
+int lamps_create(const lamps_config *cfg, void *k_pool, void *v_pool, void *workspace,
+                 void *compute_stream, void *swap_out_stream, void *swap_in_stream, lamps_ctx **out)
+{
+    Derived d;
+    if (!out) {
+        g_create_error = "lamps_create: out is null";
+        return LAMPS_ERR_INVALID;
+    }
+    *out = nullptr;
+    if (const char *why = derive(cfg, &d)) {
+        g_create_error = std::string("lamps_create: ") + why;
+        return LAMPS_ERR_INVALID;
+    }
+    if (!k_pool || !v_pool || !workspace) {
+        g_create_error = "lamps_create: k_pool, v_pool and workspace must be non-null";
+        return LAMPS_ERR_INVALID;
+    }
+    if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)workspace) & 15) {
+        g_create_error = "lamps_create: pools and workspace must be 16-byte aligned";
+        return LAMPS_ERR_INVALID;
+    }
+    lamps_ctx *c = new (std::nothrow) lamps_ctx();
+    if (!c) {
+        g_create_error = "lamps_create: out of host memory";
+        return LAMPS_ERR_NOMEM;
+    }
+    c->cfg = *cfg;
+    c->d = d;
+    c->k_pool = static_cast<char *>(k_pool);
+    c->v_pool = static_cast<char *>(v_pool);
+    char *ws = static_cast<char *>(workspace);
+    c->partials = reinterpret_cast<float *>(ws);
+    c->stage_out = ws + align256(d.partial_bytes);
+    c->stage_in = c->stage_out + align256(d.staging_bytes);
+    c->cs = static_cast<hipStream_t>(compute_stream);
+    c->os = static_cast<hipStream_t>(swap_out_stream);
+    c->is = static_cast<hipStream_t>(swap_in_stream);
+    const int nb = cfg->num_blocks;
+    c->free_stack.resize(nb);
+    for (int i = 0; i < nb; ++i) c->free_stack[i] = nb - 1 - i;   // top of stack = id 0
+    c->allocated.assign(nb, 0);
+    c->out_guard.assign(nb, 0);
+    c->in_guard.assign(nb, 0);
+    c->mark.assign(nb, 0);
+    *out = c;
+    g_create_error.clear();
+    return LAMPS_OK;
+}
+
+int lamps_destroy(lamps_ctx *c)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    int rc = LAMPS_OK;
+    while (!c->tickets.empty()) {
+        if (hipEventSynchronize(c->tickets.front().ev) != hipSuccess) rc = LAMPS_ERR_HIP;
+        (void)hipEventDestroy(c->tickets.front().ev);
+        c->tickets.pop_front();
+    }
+    for (hipEvent_t e : c->spare_events) (void)hipEventDestroy(e);
+    if (c->fence) (void)hipEventDestroy(c->fence);
+    if (c->ring) (void)hipHostFree(c->ring);
+    delete c;
+    return rc;
+}
+
+int lamps_decode_attn(lamps_ctx *c, int32_t layer, int32_t batch, const void *q,
+                      const int32_t *block_table, const int32_t *ctx_lens,
+                      const uint8_t *running_mask, void *out)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!q || !block_table || !ctx_lens || !running_mask || !out)
+        return fail(c, LAMPS_ERR_INVALID, "lamps_decode_attn: null argument");
+    if (layer < 0 || layer >= c->cfg.num_layers)
+        return fail(c, LAMPS_ERR_RANGE, "lamps_decode_attn: layer out of range");
+    if (batch < 0 || batch > c->cfg.max_batch)
+        return fail(c, LAMPS_ERR_RANGE, "lamps_decode_attn: batch out of range");
+    if (batch == 0) return LAMPS_OK;
+    lamps::DecodeArgs a;
+    a.q = q;
+    a.k_pool = c->k_pool;
+    a.v_pool = c->v_pool;
+    a.block_table = block_table;
+    a.ctx_lens = ctx_lens;
+    a.running = running_mask;
+    a.partials = c->partials;
+    a.out = out;
+    a.batch = batch;
+    a.layer = layer;
+    a.num_layers = c->cfg.num_layers;
+    a.num_q_heads = c->cfg.num_q_heads;
+    a.num_kv_heads = c->cfg.num_kv_heads;
+    a.head_dim = c->cfg.head_dim;
+    a.block_size = c->cfg.block_size;
+    a.log2_block_size = c->d.log2_bs;
+    a.max_blocks = c->cfg.max_blocks_per_req;
+    a.part_tokens = c->d.part_tokens;
+    a.max_parts = c->d.max_parts;
+    a.bf16 = c->cfg.dtype == LAMPS_BF16;
+    a.scale_log2e = c->d.scale_log2e;
+    LAMPS_HIP(lamps::launch_decode(a, c->cs));
+    return LAMPS_OK;
+}
+
+int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host_buf,
+                   uint64_t *ticket)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!ticket || (n > 0 && !host_buf))
+        return fail(c, LAMPS_ERR_INVALID, "lamps_swap_out: null argument");
+    int rc = check_ids(c, block_ids, n, "lamps_swap_out");
+    if (rc != LAMPS_OK) return rc;
+    if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
+    retire_finished(c);
+    int32_t *ids = nullptr;
+    size_t slots = 0;
+    if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
+    if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
+    hipEvent_t ev;
+    if ((rc = new_event(c, &ev)) != LAMPS_OK) return rc;
+
+    // the copy reads what the compute stream (and any earlier swap-in) wrote
+    LAMPS_HIP(hipEventRecord(c->fence, c->cs));
+    LAMPS_HIP(hipStreamWaitEvent(c->os, c->fence, 0));
+    if ((rc = wait_guards(c, c->os, c->in_guard, block_ids, n)) != LAMPS_OK) return rc;
+
+    char *host = static_cast<char *>(host_buf);
+    for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
+        const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
+        LAMPS_HIP(lamps::launch_gather(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                       c->stage_out, c->os));
+        LAMPS_HIP(hipMemcpyAsync(host + (size_t)done * c->d.block_bytes, c->stage_out,
+                                 (size_t)cnt * c->d.block_bytes, hipMemcpyDeviceToHost, c->os));
+    }
+    LAMPS_HIP(hipEventRecord(ev, c->os));
+    c->tickets.push_back(Ticket{ev, slots});
+    const uint64_t id = c->base_ticket + c->tickets.size() - 1;
+    for (int32_t i = 0; i < n; ++i) c->out_guard[block_ids[i]] = id;
+    *ticket = id;
+    return LAMPS_OK;
+}
+
+int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, int32_t n,
+                  uint64_t *ticket)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!ticket || (n > 0 && !host_buf))
+        return fail(c, LAMPS_ERR_INVALID, "lamps_swap_in: null argument");
+    int rc = check_ids(c, block_ids, n, "lamps_swap_in");
+    if (rc != LAMPS_OK) return rc;
+    if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
+    retire_finished(c);
+    int32_t *ids = nullptr;
+    size_t slots = 0;
+    if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
+    if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
+    hipEvent_t ev;
+    if ((rc = new_event(c, &ev)) != LAMPS_OK) return rc;
+
+    // the scatter overwrites blocks: earlier compute-stream readers and an
+    // unfinished swap-out of the same blocks go first
+    LAMPS_HIP(hipEventRecord(c->fence, c->cs));
+    LAMPS_HIP(hipStreamWaitEvent(c->is, c->fence, 0));
+    if ((rc = wait_guards(c, c->is, c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
+
+    const char *host = static_cast<const char *>(host_buf);
+    for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
+        const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
+        LAMPS_HIP(hipMemcpyAsync(c->stage_in, host + (size_t)done * c->d.block_bytes,
+                                 (size_t)cnt * c->d.block_bytes, hipMemcpyHostToDevice, c->is));
+        LAMPS_HIP(lamps::launch_scatter(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                        c->stage_in, c->is));
+    }
+    LAMPS_HIP(hipEventRecord(ev, c->is));
+    c->tickets.push_back(Ticket{ev, slots});
+    const uint64_t id = c->base_ticket + c->tickets.size() - 1;
+    for (int32_t i = 0; i < n; ++i) c->in_guard[block_ids[i]] = id;
+    *ticket = id;
+    return LAMPS_OK;
+}
+
+int lamps_ticket_query(lamps_ctx *c, uint64_t ticket)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_ticket_query: unknown ticket");
+    return ticket_done(c, ticket) ? LAMPS_OK : LAMPS_ERR_BUSY;
+}
+
+int lamps_ticket_wait(lamps_ctx *c, uint64_t ticket)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_ticket_wait: unknown ticket");
+    if (ticket >= c->base_ticket) LAMPS_HIP(hipEventSynchronize(ticket_event(c, ticket)));
+    retire_finished(c);
+    return LAMPS_OK;
+}
+
+int lamps_compute_wait(lamps_ctx *c, uint64_t ticket)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_compute_wait: unknown ticket");
+    if (!ticket_done(c, ticket)) LAMPS_HIP(hipStreamWaitEvent(c->cs, ticket_event(c, ticket), 0));
+    return LAMPS_OK;
+}
+
+int lamps_alloc_blocks(lamps_ctx *c, int32_t n, int32_t *block_ids_out)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (n < 0 || (n > 0 && !block_ids_out))
+        return fail(c, LAMPS_ERR_INVALID, "lamps_alloc_blocks: bad argument");
+    if ((size_t)n > c->free_stack.size())
+        return fail(c, LAMPS_ERR_NOMEM, "lamps_alloc_blocks: not enough free blocks");
+    for (int32_t i = 0; i < n; ++i) {
+        block_ids_out[i] = c->free_stack.back();
+        c->free_stack.pop_back();
+        c->allocated[block_ids_out[i]] = 1;
+    }
+    // a popped block may still be the source of an unfinished swap-out (or the
+    // target of an unfinished swap-in): later writers wait for it on the device
+    int rc;
+    if ((rc = wait_guards(c, c->cs, c->out_guard, block_ids_out, n)) != LAMPS_OK) return rc;
+    if (c->is != c->cs && (rc = wait_guards(c, c->is, c->out_guard, block_ids_out, n)) != LAMPS_OK)
+        return rc;
+    if ((rc = wait_guards(c, c->cs, c->in_guard, block_ids_out, n)) != LAMPS_OK) return rc;
+    for (int32_t i = 0; i < n; ++i) {
+        c->out_guard[block_ids_out[i]] = 0;
+        c->in_guard[block_ids_out[i]] = 0;
+    }
+    return LAMPS_OK;
+}
+
+int lamps_free_blocks(lamps_ctx *c, const int32_t *block_ids, int32_t n)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    int rc = check_ids(c, block_ids, n, "lamps_free_blocks");
+    if (rc != LAMPS_OK) return rc;
+    for (int32_t i = 0; i < n; ++i) {
+        c->allocated[block_ids[i]] = 0;
+        c->free_stack.push_back(block_ids[i]);
+    }
+    return LAMPS_OK;
+}
+
+int lamps_num_free(lamps_ctx *c)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    return (int)c->free_stack.size();
+}
+
+const char *lamps_last_error(lamps_ctx *c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,217 @@
+"""Parity of lamps_decode_attn (through the C ABI) with the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import lamps_workloads as W
+import oracle
+from rig import Rig, n2t, t2n, to_f64, tol
+
+pytestmark = pytest.mark.gpu
+
+
+def _logical(seed, geom, ctx):
+    K, V = [], []
+    for r, c in enumerate(ctx):
+        k, v = W.logical_kv(seed + 31 * (r + 1), geom, c)
+        K.append(k)
+        V.append(v)
+    return K, V
+
+
+def _setup(seed, geom, ctx, part_tokens=0):
+    """Logical-first inputs paged through a seeded random block table."""
+    B = len(ctx)
+    rig = Rig(geom, max_batch=B, part_tokens=part_tokens)
+    perm = W.permutation(seed, geom.num_blocks)
+    table, _ = W.deal_block_table(perm, ctx, geom)
+    K, V = _logical(seed, geom, ctx)
+    q = W.queries(seed, geom, B)
+    for layer in range(geom.num_layers):
+        rig.page_requests(layer, table, K, V)
+    return rig, table, q, K, V
+
+
+CASES = [
+    # dtype  H  Hkv  D   bs  part  contexts
+    ("f32", 8, 8, 64, 16, 0, [17, 64, 130, 200]),
+    ("f32", 8, 8, 64, 16, 32, [17, 64, 130, 200, 1, 0, 33]),
+    ("f32", 4, 2, 128, 16, 64, [5, 100, 16, 129]),
+    ("f32", 6, 2, 32, 32, 32, [31, 32, 33, 97]),
+    ("bf16", 8, 8, 128, 16, 0, [1, 15, 16, 17, 300, 513]),
+    ("bf16", 8, 2, 128, 16, 64, [2, 63, 64, 65, 200, 0]),
+    ("bf16", 16, 2, 128, 32, 64, [40, 129, 7]),
+    ("bf16", 4, 4, 64, 16, 32, [3, 50, 96]),
+    ("bf16", 6, 3, 256, 16, 48, [20, 77]),
+    ("bf16", 10, 2, 128, 16, 32, [90, 11]),
+]
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,D,bs,part,ctx", CASES)
+def test_small_parity(dtype, H, Hkv, D, bs, part, ctx):
+    mb = max(1, max((c + bs - 1) // bs for c in ctx))
+    nb = sum((c + bs - 1) // bs for c in ctx) + 5
+    geom = W.Geometry(2, H, Hkv, D, bs, nb, mb, dtype)
+    rig, table, q, K, V = _setup(4242 + D + H, geom, ctx, part)
+    B = len(ctx)
+    running = np.ones(B, dtype=np.uint8)
+    if B > 2:
+        running[1] = 0                                   # one paused request
+    for layer in (0, 1):
+        out = rig.decode(layer, q, table, ctx, running, sentinel=7.0)
+        ref = oracle.decode_attn(q, K, V, ctx, running)
+        got = to_f64(out)
+        for r in range(B):
+            if running[r]:
+                err = np.abs(got[r] - ref[r]).max()
+                assert err <= tol(geom), (layer, r, ctx[r], err)
+            else:
+                assert (got[r] == 7.0).all()             # paused row untouched
+    rig.close()
+
+
+def test_cfg0_swap_scenario():
+    """Tiny fp32 step with request 2 in Swap state: (i) swapped out, freed,
+    blocks poisoned, step with it paused; (ii) swapped back into different
+    blocks, all four running."""
+    wl = W.workload(0)
+    geom = wl.geom
+    ctx = wl.ctx_lens.tolist()
+    seed = W.config_seed(0)
+    rig = Rig(geom, max_batch=4)
+    lam = rig.lamps
+    perm = W.permutation(seed, geom.num_blocks)
+    # the library hands out 0,1,2,...; take all 64 and keep the first 28 of the permutation
+    all_ids = lam.alloc_blocks(geom.num_blocks)
+    assert all_ids == list(range(geom.num_blocks))
+    table, used = W.deal_block_table(perm, ctx, geom)
+    assert used == 28
+    lam.free_blocks([int(b) for b in perm[used:]])
+    K, V = _logical(seed, geom, ctx)
+    q = W.queries(seed, geom, 4)
+    rig.page_requests(0, table, K, V)
+
+    ref = oracle.decode_attn(q, K, V, ctx, [1, 1, 1, 1])
+    base = rig.decode(0, q, table, ctx, [1, 1, 1, 1])
+    assert np.abs(to_f64(base) - ref).max() <= 1e-5
+
+    # (i) request 2 enters its API call under Swap
+    ids2 = [int(b) for b in table[2, :geom.blocks_for(ctx[2])]]
+    host = torch.empty(len(ids2) * 2 * geom.block_half_bytes, dtype=torch.uint8).pin_memory()
+    t_out = lam.swap_out(ids2, host)
+    free_before = lam.num_free()
+    lam.free_blocks(ids2)
+    assert lam.num_free() == free_before + len(ids2)
+    lam.ticket_wait(t_out)
+    rig.k_pool[torch.as_tensor(ids2, device=rig.dev)] = float("nan")   # freed blocks are undefined
+    rig.v_pool[torch.as_tensor(ids2, device=rig.dev)] = float("nan")
+    torch.cuda.synchronize()
+    out = rig.decode(0, q, table, ctx, [1, 1, 0, 1], sentinel=-5.0)
+    got = to_f64(out)
+    assert (got[2] == -5.0).all()
+    for r in (0, 1, 3):
+        assert np.abs(got[r] - ref[r]).max() <= 1e-5
+        assert torch.equal(out[r], base[r])
+
+    # (ii) the API returns: different physical blocks, then all four run
+    pad = lam.alloc_blocks(len(ids2))                   # LIFO would return the same ids: hold them
+    new_ids = lam.alloc_blocks(len(ids2))
+    assert not set(new_ids) & set(ids2)
+    lam.free_blocks(pad)
+    t_in = lam.swap_in(host, new_ids)
+    lam.compute_wait(t_in)
+    table2 = table.copy()
+    table2[2, :len(new_ids)] = new_ids
+    out2 = rig.decode(0, q, table2, ctx, [1, 1, 1, 1])
+    assert np.abs(to_f64(out2) - ref).max() <= 1e-5
+    assert torch.equal(out2, base)                       # bit-identical to the pre-swap result
+    rig.close()
+
+
+def test_permuted_placement_is_bit_identical():
+    geom = W.Geometry(1, 8, 2, 128, 16, 80, 24, "bf16")
+    ctx = [333, 17, 129]
+    outs = []
+    for seed in (1, 2):
+        rig = Rig(geom, max_batch=3, part_tokens=64)
+        perm = W.permutation(seed, geom.num_blocks)
+        table, _ = W.deal_block_table(perm, ctx, geom)
+        K, V = _logical(77, geom, ctx)
+        q = W.queries(77, geom, 3)
+        rig.page_requests(0, table, K, V)
+        a = rig.decode(0, q, table, ctx, [1, 1, 1])
+        b = rig.decode(0, q, table, ctx, [1, 1, 1])
+        assert torch.equal(a, b)                         # run-to-run reproducible
+        outs.append(a.cpu())
+        rig.close()
+    assert torch.equal(outs[0], outs[1])
+
+
+def test_unused_table_entries_and_blocks_are_never_read():
+    geom = W.Geometry(1, 4, 4, 128, 16, 40, 8, "bf16")
+    ctx = [50, 9]
+    rig, table, q, K, V = _setup(5, geom, ctx, 32)
+    ref = oracle.decode_attn(q, K, V, ctx, [1, 1])
+    table = table.copy()
+    table[table < 0] = 2 ** 30                           # garbage far outside the pool
+    out = rig.decode(0, q, table, ctx, [1, 1])
+    assert np.abs(to_f64(out) - ref).max() <= 2e-2
+    rig.close()
+
+
+def test_scale_override():
+    geom = W.Geometry(1, 4, 4, 64, 16, 10, 4, "f32")
+    ctx = [40]
+    B = 1
+    rig = Rig(geom, max_batch=B, scale=0.3)
+    perm = W.permutation(9, geom.num_blocks)
+    table, _ = W.deal_block_table(perm, ctx, geom)
+    K, V = _logical(9, geom, ctx)
+    q = W.queries(9, geom, B)
+    rig.page_requests(0, table, K, V)
+    out = rig.decode(0, q, table, ctx, [1])
+    ref = oracle.decode_attn(q, K, V, ctx, [1], scale=0.3)
+    assert np.abs(to_f64(out) - ref).max() <= 1e-5
+    rig.close()
+
+
+def _full_size(cfg, sample_requests, rep=0):
+    """Physical-first: pools filled iid on the device, block table random over
+    the pool; a seeded sample of running requests is un-paged for the oracle."""
+    wl = W.workload(cfg, rep)
+    geom = wl.geom
+    seed = W.config_seed(cfg, rep)
+    rig = Rig(geom, max_batch=wl.batch, part_tokens=wl.part_tokens, poison=False)
+    gen = torch.Generator(device=rig.dev).manual_seed(seed)
+    rig.k_pool.normal_(generator=gen)
+    rig.v_pool.normal_(generator=gen)
+    perm = W.permutation(seed + 3, geom.num_blocks)
+    table, _ = W.deal_block_table(perm, wl.ctx_lens, geom)
+    q = torch.empty((wl.batch, geom.num_q_heads, geom.head_dim), dtype=rig.tdtype,
+                    device=rig.dev).normal_(generator=gen)
+    running = (wl.state == W.RUNNING).astype(np.uint8)
+    out = rig.decode(0, q, table, wl.ctx_lens, running, sentinel=3.0)
+    got = to_f64(out)
+    qn = t2n(q)
+    run_idx = np.flatnonzero(running)
+    pick = run_idx[W.permutation(seed + 4, len(run_idx))[:sample_requests]]
+    # always include the shortest and the longest running request
+    pick = set(pick.tolist()) | {int(run_idx[np.argmin(wl.ctx_lens[run_idx])]),
+                                 int(run_idx[np.argmax(wl.ctx_lens[run_idx])])}
+    worst = 0.0
+    for r in sorted(pick):
+        C = int(wl.ctx_lens[r])
+        k, v = rig.unpage_request(0, table[r], C)
+        ref = oracle.decode_attn(qn[r:r + 1], [k], [v], [C], [1], threads=8)
+        worst = max(worst, np.abs(got[r] - ref[0]).max())
+    paused = np.flatnonzero(running == 0)
+    assert (got[paused] == 3.0).all()
+    assert not np.isnan(got[run_idx]).any()
+    rig.close()
+    return worst
+
+
+@pytest.mark.parametrize("cfg,sample", [(1, 6), (2, 8), (3, 2)])
+def test_full_size_sampled_parity(cfg, sample):
+    worst = _full_size(cfg, sample)
+    assert worst <= 2e-2, worst
