@@ -1,0 +1,306 @@
+#!/usr/bin/env python3
+"""Benchmark of the LAMPS decode hot path on one MI355X.
+
+A "step" is one pass of the hot path over one synthetic batch: paged decode
+attention for the running requests of the batch (one call per layer through
+the C ABI), while the batch's Swap-state requests have their blocks swapped
+out to pinned host memory, freed, re-allocated and swapped back in on side
+streams, Preserve-state requests stay masked, and Discard-state requests'
+blocks are freed.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: tokens/s of the whole job (running requests x steps /
+wall time, device fully drained at both ends), the HBM roofline of the decode
+kernel, and the CPU oracle timed on the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="0 = enough steps for ~50 ms of decode")
+    ap.add_argument("--warmup", type=int, default=-1)
+    ap.add_argument("--config", type=int, default=1, help="workload 1..3 (1 is the headline)")
+    ap.add_argument("--rotations", type=int, default=0, help="disjoint KV regions cycled over")
+    ap.add_argument("--part-tokens", type=int, default=-1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-swap", action="store_true", help="decode only (for profiling)")
+    ap.add_argument("--table", choices=["random", "sequential"], default="random",
+                    help="physical placement of the blocks (sequential is a diagnostic)")
+    return ap.parse_args()
+
+
+class Job:
+    """Device-resident state of one benchmark workload."""
+
+    def __init__(self, cfg_id, rotations, part_tokens, table_kind="random"):
+        import torch
+
+        import lamps_workloads as W
+        import paper_2410_18248_amd as P
+        self.torch, self.W, self.P = torch, W, P
+        wl = W.workload(cfg_id)
+        g = wl.geom
+        self.wl, self.g = wl, g
+        dev = torch.device("cuda:0")
+        self.dev = dev
+        need = sum(g.blocks_for(c) for c in wl.ctx_lens)
+        if rotations <= 0:
+            rotations = 8
+        rotations = max(1, min(rotations, (g.num_blocks - need // 4) // need))
+        self.R = rotations
+        if part_tokens < 0:
+            part_tokens = wl.part_tokens
+        self.cfg = P.LampsConfig(g.num_layers, g.num_q_heads, g.num_kv_heads, g.head_dim,
+                                 g.block_size, g.num_blocks, g.max_blocks_per_req, wl.batch,
+                                 P.LAMPS_BF16 if g.dtype == "bf16" else P.LAMPS_F32, 0.0,
+                                 part_tokens, 0)
+        tdt = torch.bfloat16 if g.dtype == "bf16" else torch.float32
+        seed = W.config_seed(cfg_id)
+        gen = torch.Generator(device=dev).manual_seed(seed)
+        self.k_pool = torch.empty(g.pool_shape, dtype=tdt, device=dev).normal_(generator=gen)
+        self.v_pool = torch.empty(g.pool_shape, dtype=tdt, device=dev).normal_(generator=gen)
+        self.ws = torch.empty(P.lamps_workspace_bytes(self.cfg), dtype=torch.uint8, device=dev)
+        self.compute = torch.cuda.Stream(dev)
+        self.s_out = torch.cuda.Stream(dev)
+        self.s_in = torch.cuda.Stream(dev)
+        torch.cuda.synchronize()
+        self.lam = P.Lamps(self.cfg, self.k_pool, self.v_pool, self.ws, self.compute.cuda_stream,
+                           self.s_out.cuda_stream, self.s_in.cuda_stream)
+        # every block starts allocated to the harness; what no batch uses goes back
+        self.lam.alloc_blocks(g.num_blocks)
+        perm = W.permutation(seed + 3, g.num_blocks)
+        if table_kind == "sequential":
+            perm = np.arange(g.num_blocks, dtype=np.int64)
+        self.running = (wl.state == W.RUNNING).astype(np.uint8)
+        self.n_running = int(self.running.sum())
+        self.tables, self.q, self.out, self.tab_d = [], [], [], []
+        pos = 0
+        for b in range(self.R):
+            table, used = W.deal_block_table(perm, wl.ctx_lens, g, start=pos)
+            pos += used
+            self.tables.append(table)
+            self.tab_d.append(torch.as_tensor(table, device=dev))
+            self.q.append(torch.empty((wl.batch, g.num_q_heads, g.head_dim), dtype=tdt,
+                                      device=dev).normal_(generator=gen))
+            self.out.append(torch.zeros((wl.batch, g.num_q_heads, g.head_dim), dtype=tdt,
+                                        device=dev))
+        self.lam.free_blocks([int(x) for x in perm[pos:]])
+        self.ctx_d = torch.as_tensor(wl.ctx_lens.astype(np.int32), device=dev)
+        self.mask_d = torch.as_tensor(self.running, device=dev)
+        # Swap-state requests of each rotation batch: their block ids and a pinned buffer
+        self.block_bytes = P.lamps_block_bytes(self.cfg)
+        self.swap_ids, self.host = [], []
+        for b in range(self.R):
+            ids = []
+            for r in np.flatnonzero(wl.state == W.SWAP):
+                ids += [int(x) for x in self.tables[b][r, :g.blocks_for(wl.ctx_lens[r])]]
+            self.swap_ids.append(ids)
+            self.host.append(torch.empty(max(1, len(ids) * self.block_bytes),
+                                         dtype=torch.uint8).pin_memory())
+        # Discard-state requests: their blocks are simply freed (and re-allocated next train)
+        self.discard_ids = []
+        for b in range(self.R):
+            ids = []
+            for r in np.flatnonzero(wl.state == W.DISCARD):
+                ids += [int(x) for x in self.tables[b][r, :g.blocks_for(wl.ctx_lens[r])]]
+            self.discard_ids.append(ids)
+        self.swap_bytes = sum(len(i) for i in self.swap_ids) * self.block_bytes
+        torch.cuda.synchronize()
+        # algorithmic bytes of one decode launch: K and V of the running requests' tokens,
+        # q in, out, and the block-table entries walked
+        tok = int(wl.ctx_lens[self.running == 1].sum())
+        self.run_tokens = tok
+        self.algo_bytes = (tok * g.token_bytes_per_layer
+                           + 2 * self.n_running * g.num_q_heads * g.head_dim * g.elem_bytes
+                           + 4 * sum(g.blocks_for(c) for c in wl.ctx_lens[self.running == 1]))
+
+    def enqueue_swaps(self):
+        """Swap-state requests of every rotation batch: out, free, allocate, in."""
+        lam = self.lam
+        for b in range(self.R):
+            old = self.swap_ids[b]
+            if old:
+                new = lam.alloc_blocks(len(old))            # different physical blocks
+                lam.swap_out(old, self.host[b])
+                lam.free_blocks(old)
+                lam.swap_in(self.host[b], new)
+                self.swap_ids[b] = new
+            if self.discard_ids[b]:
+                lam.free_blocks(self.discard_ids[b])
+                self.discard_ids[b] = lam.alloc_blocks(len(self.discard_ids[b]))
+
+    def decode_steps(self, k):
+        lam, L, B = self.lam, self.g.num_layers, self.wl.batch
+        for i in range(k):
+            b = i % self.R
+            for layer in range(L):
+                lam.decode_attn(layer, B, self.q[b], self.tab_d[b], self.ctx_d, self.mask_d,
+                                self.out[b])
+
+    def train(self, k, with_swap):
+        """k steps; returns (wall seconds with the device drained, decode-stream
+        seconds by HIP events on the compute stream)."""
+        torch = self.torch
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if with_swap:
+            self.enqueue_swaps()
+        e0.record(self.compute)
+        self.decode_steps(k)
+        e1.record(self.compute)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return t1 - t0, e0.elapsed_time(e1) * 1e-3
+
+    def swap_alone(self):
+        """GB/s of one batch's swap-out and swap-in with nothing else running, and of
+        a plain pinned copy of the same size (the host link as this machine delivers it)."""
+        torch, lam = self.torch, self.lam
+        ids = self.swap_ids[0]
+        if not ids:
+            return None
+        nbytes = len(ids) * self.block_bytes
+        res = {}
+        for _ in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            lam.ticket_wait(lam.swap_out(ids, self.host[0]))
+            t1 = time.perf_counter()
+            lam.ticket_wait(lam.swap_in(self.host[0], ids))
+            t2 = time.perf_counter()
+            res["swap_out_GBs"] = nbytes / (t1 - t0) / 1e9
+            res["swap_in_GBs"] = nbytes / (t2 - t1) / 1e9
+        dbuf = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+        for _ in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.host[0][:nbytes].copy_(dbuf, non_blocking=True)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            dbuf.copy_(self.host[0][:nbytes], non_blocking=True)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            res["memcpy_d2h_GBs"] = nbytes / (t1 - t0) / 1e9
+            res["memcpy_h2d_GBs"] = nbytes / (t2 - t1) / 1e9
+        res["bytes_each_way"] = nbytes
+        return res
+
+    def unpage(self, b, r):
+        """Logical K, V of request r of rotation batch b, layer 0, as numpy (oracle input)."""
+        torch, g = self.torch, self.g
+        C = int(self.wl.ctx_lens[r])
+        ids = torch.as_tensor(self.tables[b][r, :g.blocks_for(C)].astype(np.int64), device=self.dev)
+
+        def logical(pool):
+            x = pool[ids, 0].cpu()                              # [nb][Hkv][bs][D]
+            x = x.view(torch.int16).numpy().view(np.uint16) if x.dtype == torch.bfloat16 else x.numpy()
+            return np.ascontiguousarray(
+                np.swapaxes(x, 1, 2).reshape(-1, g.num_kv_heads, g.head_dim)[:C])
+        return logical(self.k_pool), logical(self.v_pool)
+
+
+def cpu_baseline(job):
+    """The oracle, as it stands, on the host cores: all running requests of one
+    batch, one layer.  Un-paging is done before the clock starts."""
+    import oracle
+    torch = job.torch
+    cores = len(os.sched_getaffinity(0))
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit():
+        cores = min(cores, int(env))
+    q = job.q[0].cpu()
+    q = q.view(torch.int16).numpy().view(np.uint16) if q.dtype == torch.bfloat16 else q.numpy()
+    B = job.wl.batch
+    K, V = [None] * B, [None] * B
+    for r in np.flatnonzero(job.running):
+        K[r], V[r] = job.unpage(0, r)
+    t0 = time.perf_counter()
+    ref = oracle.decode_attn(q, K, V, job.wl.ctx_lens, job.running, threads=cores)
+    dt = time.perf_counter() - t0
+    got = job.out[0].cpu().to(torch.float64).numpy()
+    run = job.running == 1
+    err = float(np.abs(got[run] - ref[run]).max())
+    return {"value": job.n_running / (dt * job.g.num_layers), "unit": "tokens/s", "cores": cores,
+            "kind": "oracle",
+            "sample": "all %d running requests of one batch, 1 of %d layer(s), %.2f s; "
+                      "scaled by the layer count" % (job.n_running, job.g.num_layers, dt),
+            "max_abs_err_gpu_vs_oracle": err}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build measures one MI355X; --gpus %d is not supported "
+              "(no collectives or sharding are part of it)" % a.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    job = Job(a.config, a.rotations, a.part_tokens, a.table)
+    with_swap = not a.no_swap
+
+    # calibrate: one short train to size the run
+    job.train(2 * job.R, False)
+    _, dec = job.train(2 * job.R, False)
+    per_step = dec / (2 * job.R)
+    steps = a.steps if a.steps > 0 else int(min(4000, max(job.R, 0.05 / per_step)))
+    warmup = a.warmup if a.warmup >= 0 else max(job.R, steps // 4)
+
+    job.train(warmup, with_swap)
+    wall, dec = job.train(steps, with_swap)
+    wall_alone, dec_alone = job.train(steps, False)
+
+    launches = steps * job.g.num_layers
+    kernel_s = dec / launches
+    achieved = job.algo_bytes / kernel_s / 1e9
+    line = {
+        "metric": "decode-attention tokens/s (achieved HBM GB/s in roofline; swap GB/s in swap)",
+        "value": job.n_running * steps / wall,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": wall / steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": job.g.dtype, "data": "synthetic",
+        "config": {"workload": job.wl.name, "batch": job.wl.batch, "running": job.n_running,
+                   "running_tokens": job.run_tokens, "layers": job.g.num_layers,
+                   "q_heads": job.g.num_q_heads, "kv_heads": job.g.num_kv_heads,
+                   "head_dim": job.g.head_dim, "block_size": job.g.block_size,
+                   "num_blocks": job.g.num_blocks, "rotations": job.R,
+                   "part_tokens": int(job.cfg.part_tokens),
+                   "swap_bytes_each_way_per_train": 0 if not with_swap else job.swap_bytes},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "decode_partial", "algorithmic_bytes_per_launch": job.algo_bytes,
+                     "kernel_us": kernel_s * 1e6,
+                     "timing": "HIP events on the compute stream around the timed steps / launches"},
+        "decode_alone": {"ms_per_step": dec_alone / steps * 1e3,
+                         "tokens_per_s": job.n_running * steps / wall_alone,
+                         "GBs": job.algo_bytes * job.g.num_layers / (dec_alone / steps) / 1e9},
+        "decode_slowdown_under_swap": dec / dec_alone,
+    }
+    if with_swap:
+        line["swap"] = job.swap_alone()
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(job)
+    job.lam.destroy()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

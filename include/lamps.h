@@ -149,8 +149,11 @@ int lamps_swap_out(lamps_ctx *ctx, const int32_t *block_ids, int32_t n, void *ho
  * swap-in stream (hipMemcpyAsync into staging, then scatter).  The listed
  * blocks must be allocated (typically just obtained from lamps_alloc_blocks;
  * they need not be the blocks the images came from).  No other block changes.
- * A request may run again only in steps enqueued after
- * lamps_compute_wait(ticket). */
+ * If host_buf overlaps the buffer of a swap-out that has not finished, the
+ * copy is ordered after it on the device (and a swap-out into a buffer that
+ * an unfinished swap-in still reads waits likewise), so a swap-in may be
+ * enqueued right behind the swap-out that fills its buffer.  A request may run
+ * again only in steps enqueued after lamps_compute_wait(ticket). */
 int lamps_swap_in(lamps_ctx *ctx, const void *host_buf, const int32_t *block_ids, int32_t n,
                   uint64_t *ticket);
 

@@ -43,6 +43,12 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    try:
+        # torch bundles its own HIP runtime under the same soname as /opt/rocm's; whichever is
+        # loaded first serves the whole process, and it has to be the one torch was built with
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     path = lib_path()
     if not os.path.exists(path):
         raise ImportError("liblamps.so is not built: run `python -m paper_2410_18248_amd.build`")

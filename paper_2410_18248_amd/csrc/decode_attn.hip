@@ -6,7 +6,8 @@
 // block table (paged attention, Section 7).  The context is cut into
 // partitions of `part_tokens` tokens; one workgroup reduces one
 // (request, kv head, partition) to (max, sum, weighted value sum) with an
-// online softmax, and a second kernel merges the partitions of a request.
+// online softmax, and a second small kernel merges the partitions of a request
+// (skipped when the configuration has a single partition per request).
 //
 // Mapping to the hardware.  The path is a stream over K and V (every byte is
 // used once: ~1 flop/byte), so it is HBM-bound and runs on the vector ALUs, not
@@ -68,6 +69,15 @@ __device__ __forceinline__ uint16_t to_bf16_rne(float f)
     uint32_t b = __float_as_uint(f);
     if ((b & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;
     return (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+}
+
+template <bool BF16>
+__device__ __forceinline__ void store_out(void *out, size_t i, float o)
+{
+    if (BF16)
+        static_cast<uint16_t *>(out)[i] = to_bf16_rne(o);
+    else
+        static_cast<float *>(out)[i] = o;
 }
 
 // Partial dot product of a lane's 16 bytes of q and K.
@@ -274,6 +284,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     }
     __syncthreads();
 
+    const size_t rh0 = (size_t)r * a.num_q_heads + h0;
     for (int idx = threadIdx.x; idx < GH * D; idx += kThreads) {
         const int h = idx / D, d = idx % D;
         float M = sm_m[0][h];
@@ -286,15 +297,10 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
             L += sm_l[ww][h] * f;
             A += sm_acc[ww][h][d] * f;
         }
-        const size_t rh = (size_t)r * a.num_q_heads + h0 + h;
         if (n_parts == 1) {
-            float o = L > 0.0f ? A / L : 0.0f;
-            if (BF16)
-                static_cast<uint16_t *>(a.out)[rh * D + d] = to_bf16_rne(o);
-            else
-                static_cast<float *>(a.out)[rh * D + d] = o;
+            store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
         } else {
-            float *pp = a.partials + (rh * a.max_parts + part) * (D + 2);
+            float *pp = a.partials + ((rh0 + h) * a.max_parts + part) * (D + 2);
             pp[d] = A;
             if (d == 0) {
                 pp[D] = M;
@@ -304,7 +310,10 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     }
 }
 
-// Merge of the partitions of one (request, head); block = D threads.
+// Merge of the partitions of one (request, query head), always in partition
+// order; block = head_dim threads.  A separate launch on purpose: a kernel
+// boundary makes the partials visible across the eight XCDs' L2s once, whereas
+// a device-scope fence per workgroup writes back and invalidates an L2 each time.
 template <bool BF16>
 __global__ void decode_merge(const DecodeArgs a)
 {
@@ -320,16 +329,12 @@ __global__ void decode_merge(const DecodeArgs a)
     for (int p = 0; p < n_parts; ++p) M = fmaxf(M, pp[(size_t)p * (D + 2) + D]);
     float L = 0.0f, A = 0.0f;
     for (int p = 0; p < n_parts; ++p) {
-        const float *q = pp + (size_t)p * (D + 2);
-        float f = fast_exp2(q[D] - M);
-        L += q[D + 1] * f;
-        A += q[d] * f;
+        const float *x = pp + (size_t)p * (D + 2);
+        float f = fast_exp2(x[D] - M);
+        L += x[D + 1] * f;
+        A += x[d] * f;
     }
-    float o = L > 0.0f ? A / L : 0.0f;
-    if (BF16)
-        static_cast<uint16_t *>(a.out)[rh * D + d] = to_bf16_rne(o);
-    else
-        static_cast<float *>(a.out)[rh * D + d] = o;
+    store_out<BF16>(a.out, rh * D + d, L > 0.0f ? A / L : 0.0f);
 }
 
 template <bool BF16, int LPT>
@@ -374,16 +379,13 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
         if (lpt == 16) e = launch_partial<false, 16>(a, gh, grid, stream);
         if (lpt == 32) e = launch_partial<false, 32>(a, gh, grid, stream);
     }
-    if (e != hipSuccess) return e;
-    if (a.max_parts > 1) {
-        dim3 mg(a.num_q_heads, a.batch);
-        if (a.bf16)
-            hipLaunchKernelGGL(decode_merge<true>, mg, dim3(a.head_dim), 0, stream, a);
-        else
-            hipLaunchKernelGGL(decode_merge<false>, mg, dim3(a.head_dim), 0, stream, a);
-        e = hipGetLastError();
-    }
-    return e;
+    if (e != hipSuccess || a.max_parts == 1) return e;
+    dim3 mg(a.num_q_heads, a.batch);
+    if (a.bf16)
+        hipLaunchKernelGGL(decode_merge<true>, mg, dim3(a.head_dim), 0, stream, a);
+    else
+        hipLaunchKernelGGL(decode_merge<false>, mg, dim3(a.head_dim), 0, stream, a);
+    return hipGetLastError();
 }
 
 }  // namespace lamps

@@ -25,7 +25,8 @@ struct DecodeArgs {
 // (0 if the geometry is not supported).
 int decode_heads_per_group(int bf16, int head_dim, int group);
 
-// Enqueues the split partial kernel and the merge kernel.
+// Enqueues one layer of decode attention: the partition kernel, then the merge
+// kernel if a request can have more than one partition.
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
 
 // Gather: staging image i (key bytes then value bytes of block ids[i]) <- pools.

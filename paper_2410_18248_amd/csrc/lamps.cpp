@@ -80,6 +80,8 @@ const char *derive(const lamps_config *c, Derived *d)
 struct Ticket {
     hipEvent_t ev;
     size_t ring_slots;
+    const char *host_lo, *host_hi;   // host bytes the copy writes (swap-out) or reads (swap-in)
+    bool is_out;
 };
 
 }  // namespace
@@ -246,6 +248,19 @@ int wait_guards(lamps_ctx *c, hipStream_t stream, const std::vector<uint64_t> &g
     return LAMPS_OK;
 }
 
+// Orders `stream` after every unfinished copy of the other direction that
+// touches host bytes [lo, hi): a swap-in may be enqueued right after the
+// swap-out that fills its buffer, and the other way round.
+int wait_host_overlap(lamps_ctx *c, hipStream_t stream, const char *lo, const char *hi,
+                      bool other_is_out)
+{
+    for (Ticket &t : c->tickets)
+        if (t.is_out == other_is_out && t.host_lo < hi && lo < t.host_hi &&
+            hipEventQuery(t.ev) != hipSuccess)
+            LAMPS_HIP(hipStreamWaitEvent(stream, t.ev, 0));
+    return LAMPS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -399,8 +414,10 @@ int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host
     LAMPS_HIP(hipEventRecord(c->fence, c->cs));
     LAMPS_HIP(hipStreamWaitEvent(c->os, c->fence, 0));
     if ((rc = wait_guards(c, c->os, c->in_guard, block_ids, n)) != LAMPS_OK) return rc;
-
     char *host = static_cast<char *>(host_buf);
+    const size_t total = (size_t)n * c->d.block_bytes;
+    if ((rc = wait_host_overlap(c, c->os, host, host + total, false)) != LAMPS_OK) return rc;
+
     for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
         const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
         LAMPS_HIP(lamps::launch_gather(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
@@ -409,7 +426,7 @@ int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host
                                  (size_t)cnt * c->d.block_bytes, hipMemcpyDeviceToHost, c->os));
     }
     LAMPS_HIP(hipEventRecord(ev, c->os));
-    c->tickets.push_back(Ticket{ev, slots});
+    c->tickets.push_back(Ticket{ev, slots, host, host + total, true});
     const uint64_t id = c->base_ticket + c->tickets.size() - 1;
     for (int32_t i = 0; i < n; ++i) c->out_guard[block_ids[i]] = id;
     *ticket = id;
@@ -438,8 +455,10 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
     LAMPS_HIP(hipEventRecord(c->fence, c->cs));
     LAMPS_HIP(hipStreamWaitEvent(c->is, c->fence, 0));
     if ((rc = wait_guards(c, c->is, c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
-
     const char *host = static_cast<const char *>(host_buf);
+    const size_t total = (size_t)n * c->d.block_bytes;
+    if ((rc = wait_host_overlap(c, c->is, host, host + total, true)) != LAMPS_OK) return rc;
+
     for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
         const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
         LAMPS_HIP(hipMemcpyAsync(c->stage_in, host + (size_t)done * c->d.block_bytes,
@@ -448,7 +467,7 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
                                         c->stage_in, c->is));
     }
     LAMPS_HIP(hipEventRecord(ev, c->is));
-    c->tickets.push_back(Ticket{ev, slots});
+    c->tickets.push_back(Ticket{ev, slots, host, host + total, false});
     const uint64_t id = c->base_ticket + c->tickets.size() - 1;
     for (int32_t i = 0; i < n; ++i) c->in_guard[block_ids[i]] = id;
     *ticket = id;
