@@ -1,0 +1,182 @@
+"""Swap / free-list behaviour of liblamps on the GPU against the oracle's
+byte-exact block model (handling strategies of Section 1 / Section 4.2)."""
+import numpy as np
+import pytest
+import torch
+
+import lamps_workloads as W
+import oracle
+import paper_2410_18248_amd as P
+from rig import Rig, t2n, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _bytes(t):
+    return t.detach().cpu().contiguous().view(torch.uint8).numpy()
+
+
+def _fill_random(rig, seed):
+    gen = torch.Generator(device=rig.dev).manual_seed(seed)
+    # random BYTES (every bit pattern, NaNs included): the copy must not interpret them
+    for pool in (rig.k_pool, rig.v_pool):
+        raw = pool.view(torch.uint8)
+        raw.copy_(torch.randint(0, 256, raw.shape, dtype=torch.uint8, device=rig.dev, generator=gen))
+    torch.cuda.synchronize()
+
+
+def _model(rig):
+    nb = rig.geom.num_blocks
+    return oracle.PoolModel(_bytes(rig.k_pool).reshape(nb, -1), _bytes(rig.v_pool).reshape(nb, -1))
+
+
+def _pinned(n):
+    return torch.empty(max(n, 1), dtype=torch.uint8).pin_memory()
+
+
+@pytest.mark.parametrize("dtype,L,Hkv,D,bs,staging_blocks", [
+    ("f32", 1, 8, 64, 16, 0), ("bf16", 3, 2, 128, 16, 4), ("bf16", 2, 4, 128, 32, 1)])
+def test_swap_out_image_and_round_trip(dtype, L, Hkv, D, bs, staging_blocks):
+    geom = W.Geometry(L, Hkv, Hkv, D, bs, 48, 8, dtype)
+    bb = 2 * geom.block_half_bytes
+    rig = Rig(geom, max_batch=2, staging_bytes=staging_blocks * bb)     # small staging: several chunks
+    lam = rig.lamps
+    assert P.lamps_block_bytes(rig.cfg) == bb
+    _fill_random(rig, 11)
+    model = _model(rig)
+    ids_all = lam.alloc_blocks(geom.num_blocks)
+    assert ids_all == oracle.AllocatorModel(geom.num_blocks).alloc(geom.num_blocks)
+    src = [int(x) for x in W.permutation(5, geom.num_blocks)[:11]]
+    host = _pinned(len(src) * bb)
+    t = lam.swap_out(src, host)
+    lam.ticket_wait(t)
+    assert lam.ticket_query(t)
+    want = model.swap_out(src)
+    np.testing.assert_array_equal(host.numpy().reshape(len(src), bb), want)     # image layout, bit-exact
+    np.testing.assert_array_equal(_bytes(rig.k_pool).reshape(geom.num_blocks, -1), model.k)  # pool untouched
+    np.testing.assert_array_equal(_bytes(rig.v_pool).reshape(geom.num_blocks, -1), model.v)
+
+    # back into different blocks; every other block byte-identical
+    dst = [int(x) for x in W.permutation(5, geom.num_blocks)[20:31]]
+    t2 = lam.swap_in(host, dst)
+    lam.ticket_wait(t2)
+    model.swap_in(want, dst)
+    np.testing.assert_array_equal(_bytes(rig.k_pool).reshape(geom.num_blocks, -1), model.k)
+    np.testing.assert_array_equal(_bytes(rig.v_pool).reshape(geom.num_blocks, -1), model.v)
+    rig.close()
+
+
+def test_empty_list_and_ticket_errors():
+    geom = W.Geometry(1, 2, 2, 64, 16, 8, 2, "bf16")
+    rig = Rig(geom, max_batch=1)
+    lam = rig.lamps
+    host = _pinned(16)
+    t = lam.swap_out([], host)
+    lam.ticket_wait(t)
+    assert lam.ticket_query(t)
+    with pytest.raises(P.LampsError) as e:
+        lam.ticket_wait(t + 5)
+    assert e.value.status == -2
+    with pytest.raises(P.LampsError) as e:
+        lam.swap_out([3], host)                     # block 3 is not allocated
+    assert e.value.status == -4
+    rig.close()
+
+
+def test_freed_block_reuse_waits_for_its_swap_out():
+    """swap-out, free, allocate again (LIFO gives the same ids back) and overwrite
+    at once: the host image must still hold the old bytes."""
+    geom = W.Geometry(8, 8, 8, 128, 16, 160, 8, "bf16")     # 512 KiB images, ~70 MB per swap
+    bb = 2 * geom.block_half_bytes
+    rig = Rig(geom, max_batch=1)
+    lam = rig.lamps
+    _fill_random(rig, 21)
+    model = _model(rig)
+    lam.alloc_blocks(geom.num_blocks)
+    ids = list(range(10, 150))
+    other = _pinned(len(ids) * bb)
+    other.numpy()[:] = 0x5A
+    host = _pinned(len(ids) * bb)
+    want = model.swap_out(ids)
+    t_out = lam.swap_out(ids, host)
+    lam.free_blocks(ids)
+    again = lam.alloc_blocks(len(ids))
+    assert again == ids[::-1]                       # LIFO, as in the oracle's allocator model
+    t_in = lam.swap_in(other, again)                # overwrites the same physical blocks
+    lam.ticket_wait(t_in)
+    lam.ticket_wait(t_out)
+    np.testing.assert_array_equal(host.numpy().reshape(len(ids), bb), want)
+    assert (_bytes(rig.k_pool[again[0]]) == 0x5A).all()
+    rig.close()
+
+
+def test_swap_in_right_behind_swap_out_through_one_buffer():
+    geom = W.Geometry(4, 8, 8, 128, 16, 128, 8, "bf16")
+    bb = 2 * geom.block_half_bytes
+    rig = Rig(geom, max_batch=1)
+    lam = rig.lamps
+    _fill_random(rig, 31)
+    model = _model(rig)
+    lam.alloc_blocks(geom.num_blocks)
+    src, dst = list(range(0, 50)), list(range(60, 110))
+    host = _pinned(len(src) * bb)
+    host.numpy()[:] = 0
+    lam.swap_out(src, host)
+    t = lam.swap_in(host, dst)                      # no host wait in between
+    lam.ticket_wait(t)
+    model.swap_in(model.swap_out(src), dst)
+    np.testing.assert_array_equal(_bytes(rig.k_pool).reshape(geom.num_blocks, -1), model.k)
+    np.testing.assert_array_equal(_bytes(rig.v_pool).reshape(geom.num_blocks, -1), model.v)
+    rig.close()
+
+
+def test_decode_while_others_swap():
+    """Requests in Swap state move out and back on the side streams while the
+    others are decoded; outputs match the oracle and paused rows stay untouched;
+    after lamps_compute_wait the returned requests decode correctly from their
+    new blocks."""
+    geom = W.Geometry(2, 8, 2, 128, 16, 400, 40, "bf16")
+    ctx = [600, 37, 512, 300, 129, 640]
+    B = len(ctx)
+    rig = Rig(geom, max_batch=B, part_tokens=128)
+    lam = rig.lamps
+    lam.alloc_blocks(geom.num_blocks)
+    perm = W.permutation(8, geom.num_blocks)
+    table, used = W.deal_block_table(perm, ctx, geom)
+    lam.free_blocks([int(x) for x in perm[used:]])
+    K, V, q = [], [], W.queries(8, geom, B)
+    for r, c in enumerate(ctx):
+        k, v = W.logical_kv(100 + r, geom, c)
+        K.append(k)
+        V.append(v)
+    for layer in range(geom.num_layers):
+        rig.page_requests(layer, table, K, V)
+    ref = oracle.decode_attn(q, K, V, ctx, [1] * B)
+    swapped = [0, 3]
+    running = np.ones(B, dtype=np.uint8)
+    running[swapped] = 0
+    bb = 2 * geom.block_half_bytes
+    tickets, new_tab = [], table.copy()
+    bufs = []
+    for r in swapped:
+        old = [int(x) for x in table[r, :geom.blocks_for(ctx[r])]]
+        new = lam.alloc_blocks(len(old))
+        host = _pinned(len(old) * bb)
+        bufs.append(host)
+        lam.swap_out(old, host)
+        lam.free_blocks(old)
+        tickets.append(lam.swap_in(host, new))
+        new_tab[r, :len(new)] = new
+    for layer in range(geom.num_layers):            # decode of the others, swaps in flight
+        out = rig.decode(layer, q, table, ctx, running, sentinel=9.0)
+        got = to_f64(out)
+        for r in range(B):
+            if running[r]:
+                assert np.abs(got[r] - ref[r]).max() <= 2e-2
+            else:
+                assert (got[r] == 9.0).all()
+    for t in tickets:
+        lam.compute_wait(t)
+    out = rig.decode(1, q, new_tab, ctx, [1] * B)
+    assert np.abs(to_f64(out) - ref).max() <= 2e-2
+    rig.close()
