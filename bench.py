@@ -37,6 +37,10 @@ def parse():
     ap.add_argument("--part-tokens", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-swap", action="store_true", help="decode only (for profiling)")
+    ap.add_argument("--ctx-override", type=int, default=0,
+                    help="diagnostic: give every request this context length")
+    ap.add_argument("--geom", default="",
+                    help="diagnostic: override geometry, e.g. H=8,Hkv=8,bs=32,B=64,MB=128,NB=50000")
     ap.add_argument("--table", choices=["random", "sequential"], default="random",
                     help="physical placement of the blocks (sequential is a diagnostic)")
     return ap.parse_args()
@@ -45,13 +49,30 @@ def parse():
 class Job:
     """Device-resident state of one benchmark workload."""
 
-    def __init__(self, cfg_id, rotations, part_tokens, table_kind="random"):
+    def __init__(self, cfg_id, rotations, part_tokens, table_kind="random", ctx_override=0,
+                 geom_override=""):
         import torch
 
         import lamps_workloads as W
         import paper_2410_18248_amd as P
         self.torch, self.W, self.P = torch, W, P
         wl = W.workload(cfg_id)
+        if geom_override:
+            import dataclasses
+            kv = dict(x.split("=") for x in geom_override.split(","))
+            names = {"H": "num_q_heads", "Hkv": "num_kv_heads", "bs": "block_size",
+                     "MB": "max_blocks_per_req", "NB": "num_blocks", "D": "head_dim",
+                     "L": "num_layers"}
+            wl.geom = dataclasses.replace(wl.geom, **{names[k]: int(v) for k, v in kv.items()
+                                                      if k in names})
+            if "B" in kv:
+                wl.batch = int(kv["B"])
+                wl.ctx_lens = np.resize(wl.ctx_lens, wl.batch)
+                wl.state = np.resize(wl.state, wl.batch)
+            wl.name += "-" + geom_override
+        if ctx_override:
+            wl.ctx_lens[:] = ctx_override
+            wl.name += "-ctx%d" % ctx_override
         g = wl.geom
         self.wl, self.g = wl, g
         dev = torch.device("cuda:0")
@@ -252,7 +273,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    job = Job(a.config, a.rotations, a.part_tokens, a.table)
+    job = Job(a.config, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom)
     with_swap = not a.no_swap
 
     # calibrate: one short train to size the run

@@ -36,6 +36,15 @@ constexpr int loads_per_chunk(int lpt) { return lpt == 8 ? 2 : 4; }
 constexpr float kLowest = -3.0e38f;     // finite stand-in for "no score seen yet"
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+// K and V are read exactly once per launch: a non-temporal 16-byte load keeps
+// the stream from displacing anything in the caches (measurably faster here).
+__device__ __forceinline__ uint4 load_stream16(const char *p)
+{
+    u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float x)
@@ -131,8 +140,8 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float (&acc)[VEC
     m = mn;
 }
 
-// One workgroup: request blockIdx.z, kv head / head chunk blockIdx.y,
-// partition blockIdx.x.  GH query heads of the kv group share the K/V stream.
+// One workgroup: one (partition, request, kv head / head chunk), decoded from a
+// 1-D grid.  GH query heads of the kv group share the K/V stream.
 template <bool BF16, int LPT, int GH>
 __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
 {
@@ -142,19 +151,25 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     constexpr int kLoads = loads_per_chunk(LPT);
     constexpr int CT = TPW * kLoads;           // tokens per chunk (<= 16 <= block_size)
 
-    const int r = blockIdx.z;
+    // Workgroups are handed to the eight XCDs round-robin in launch order, so the
+    // index that varies fastest must be one along which the work is even: the
+    // kv head (and head chunk), then the request, then the partition.  (With the
+    // partition fastest and eight partitions, all first partitions -- most of
+    // the work -- would land on one XCD.)
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int chunks_per_group = G / GH;
+    const int hc_count = a.num_kv_heads * chunks_per_group;
+    const int hc = blockIdx.x % hc_count;
+    const int r = (blockIdx.x / hc_count) % a.batch;
+    const int part = blockIdx.x / (hc_count * a.batch);
     if (!a.running[r]) return;                 // Preserve / Swap / Discard: not in the batch
     const int C = a.ctx_lens[r];
-    const int part = blockIdx.x;
     const int t_begin = part * a.part_tokens;
     if (t_begin >= C && part != 0) return;     // partition 0 of an empty context writes zeros
     const int t_end = min(C, t_begin + a.part_tokens);
     const int n_parts = max(1, (C + a.part_tokens - 1) / a.part_tokens);
-
-    const int G = a.num_q_heads / a.num_kv_heads;
-    const int chunks_per_group = G / GH;
-    const int g = blockIdx.y / chunks_per_group;
-    const int h0 = g * G + (blockIdx.y % chunks_per_group) * GH;
+    const int g = hc / chunks_per_group;
+    const int h0 = g * G + (hc % chunks_per_group) * GH;
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -196,10 +211,10 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
         uint4 kx[kLoads], vx[kLoads];
 #pragma unroll
         for (int i = 0; i < kLoads; ++i)
-            kx[i] = *reinterpret_cast<const uint4 *>(kp + off + i * 1024);
+            kx[i] = load_stream16(kp + off + i * 1024);
 #pragma unroll
         for (int i = 0; i < kLoads; ++i)
-            vx[i] = *reinterpret_cast<const uint4 *>(vp + off + i * 1024);
+            vx[i] = load_stream16(vp + off + i * 1024);
 
         // physical block of this wave's next chunk, fetched while the tiles arrive
         const int chn = ch + kWaves;
@@ -368,7 +383,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
     const int gh = decode_heads_per_group(a.bf16, a.head_dim, G);
     if (gh == 0) return hipErrorInvalidValue;
     const int lpt = a.head_dim * (a.bf16 ? 2 : 4) / 16;
-    dim3 grid(a.max_parts, a.num_kv_heads * (G / gh), a.batch);
+    dim3 grid((unsigned)((size_t)a.max_parts * a.num_kv_heads * (G / gh) * a.batch));
     hipError_t e = hipErrorInvalidValue;
     if (a.bf16) {
         if (lpt == 8) e = launch_partial<true, 8>(a, gh, grid, stream);
