@@ -26,6 +26,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
+# HBM bytes per decode launch measured with rocprofv3 --pmc (FETCH_SIZE run + WRITE_SIZE run,
+# each scaled by the same counter's reading for a plain 1 GiB copy: x2.0 and x1.0), keyed by
+# workload name; summaries in profiles/.  None where not measured.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg1-7b-mha-bf16": 887_993_000,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -39,6 +46,9 @@ def parse():
     ap.add_argument("--no-swap", action="store_true", help="decode only (for profiling)")
     ap.add_argument("--ctx-override", type=int, default=0,
                     help="diagnostic: give every request this context length")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device-to-device copies (a kernel of known "
+                         "traffic, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--geom", default="",
                     help="diagnostic: override geometry, e.g. H=8,Hkv=8,bs=32,B=64,MB=128,NB=50000")
     ap.add_argument("--table", choices=["random", "sequential"], default="random",
@@ -181,11 +191,19 @@ class Job:
         t0 = time.perf_counter()
         if with_swap:
             self.enqueue_swaps()
+        ta = time.perf_counter()
         e0.record(self.compute)
         self.decode_steps(k)
         e1.record(self.compute)
+        tb = time.perf_counter()
+        self.compute.synchronize()
+        tc = time.perf_counter()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        if os.environ.get("LAMPS_BENCH_DEBUG"):
+            print("train k=%d swap=%s: swaps enqueued %.2f ms, decode enqueued %.2f, compute drained "
+                  "%.2f, all drained %.2f" % (k, with_swap, (ta - t0) * 1e3, (tb - t0) * 1e3,
+                                              (tc - t0) * 1e3, (t1 - t0) * 1e3), file=sys.stderr)
         return t1 - t0, e0.elapsed_time(e1) * 1e-3
 
     def swap_alone(self):
@@ -283,6 +301,19 @@ def main():
     steps = a.steps if a.steps > 0 else int(min(4000, max(job.R, 0.05 / per_step)))
     warmup = a.warmup if a.warmup >= 0 else max(job.R, steps // 4)
 
+    if a.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=job.dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    if with_swap:
+        # the runtime sets up its copy path lazily (first large copies block the host for
+        # milliseconds each); get that out of the way before anything is timed
+        for _ in range(3):
+            job.enqueue_swaps()
+            torch.cuda.synchronize()
     job.train(warmup, with_swap)
     wall, dec = job.train(steps, with_swap)
     wall_alone, dec_alone = job.train(steps, False)
@@ -306,7 +337,8 @@ def main():
                    "part_tokens": int(job.cfg.part_tokens),
                    "swap_bytes_each_way_per_train": 0 if not with_swap else job.swap_bytes},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(job.wl.name),
                      "kernel": "decode_partial", "algorithmic_bytes_per_launch": job.algo_bytes,
                      "kernel_us": kernel_s * 1e6,
                      "timing": "HIP events on the compute stream around the timed steps / launches"},

@@ -75,7 +75,7 @@ typedef struct {
     int32_t dtype;              /* lamps_dtype of q, the pools and out               */
     float softmax_scale;        /* 0 => 1/sqrt(head_dim), the Section 2.2 equation   */
     int32_t part_tokens;        /* tokens per split partition, multiple of
-                                   block_size; 0 => library default                  */
+                                   block_size; 0 => library default (1024)           */
     int64_t staging_bytes;      /* device staging per swap direction; 0 => default   */
 } lamps_config;
 
@@ -136,9 +136,11 @@ int lamps_decode_attn(lamps_ctx *ctx, int32_t layer, int32_t batch, const void *
  * device staging, then moved by hipMemcpyAsync.  The copy is ordered after all
  * compute-stream work enqueued before this call and after earlier swap-ins
  * into the same blocks.  The pool is not modified and the blocks stay
- * allocated; the caller frees them afterwards with lamps_free_blocks, and
- * their reuse is held back on the device until the copy has finished (the
- * delay before the memory is fully released, Section 4.2).
+ * allocated; the caller frees them afterwards with lamps_free_blocks.  The
+ * library remembers the unfinished copy per block, so that a later swap-in
+ * into a re-allocated block, or lamps_compute_wait_blocks, is ordered behind
+ * it on the device (the delay before the memory is fully released,
+ * Section 4.2).
  * block_ids is a HOST array, copied inside the call.  *ticket identifies the
  * copy.  n == 0 is allowed.
  * Errors: INVALID, RANGE, DUP, DOUBLE_FREE (a listed block is not allocated),
@@ -163,12 +165,20 @@ int lamps_ticket_query(lamps_ctx *ctx, uint64_t ticket);
 int lamps_ticket_wait(lamps_ctx *ctx, uint64_t ticket);
 /* Makes the compute stream wait (on the device) for the ticket's copy. */
 int lamps_compute_wait(lamps_ctx *ctx, uint64_t ticket);
+/* Makes the compute stream wait (on the device) for every unfinished swap-out
+ * or swap-in that touches one of the n listed (allocated) blocks: the release
+ * of a swapped-out block is complete only when its copy is (Section 4.2), and
+ * compute-stream work that overwrites such a block must come after it.
+ * Errors: INVALID, RANGE, DUP, DOUBLE_FREE, HIP. */
+int lamps_compute_wait_blocks(lamps_ctx *ctx, const int32_t *block_ids, int32_t n);
 
 /* ---- block free list (Discard; and the release half of Swap) ---- */
 
 /* Pops n ids (LIFO: the most recently freed id first; a fresh pool yields
- * 0, 1, 2, ...).  If a popped block still has an unfinished swap-out, the
- * compute and swap-in streams are made to wait for it before any later work.
+ * 0, 1, 2, ...).  A popped block may still be the source of a swap-out that has
+ * not finished: lamps_swap_in into it waits for that copy by itself; a caller
+ * that will write it from the compute stream (recompute after Discard, KV
+ * append) calls lamps_compute_wait_blocks first.  Makes no HIP call.
  * Errors: INVALID, NOMEM (fewer than n free; nothing is popped). */
 int lamps_alloc_blocks(lamps_ctx *ctx, int32_t n, int32_t *block_ids_out);
 /* Pushes the listed ids, in the order given; their contents become undefined.

@@ -68,6 +68,7 @@ def load_library():
         "lamps_ticket_query": [vp, u64],
         "lamps_ticket_wait": [vp, u64],
         "lamps_compute_wait": [vp, u64],
+        "lamps_compute_wait_blocks": [vp, vp, i32],
         "lamps_alloc_blocks": [vp, i32, vp],
         "lamps_free_blocks": [vp, vp, i32],
         "lamps_num_free": [vp],
@@ -170,6 +171,10 @@ class Lamps:
 
     def compute_wait(self, ticket):
         self._check(self.lib.lamps_compute_wait(self.h, ticket))
+
+    def compute_wait_blocks(self, block_ids):
+        arr, n = _ids(block_ids)
+        self._check(self.lib.lamps_compute_wait_blocks(self.h, arr, n))
 
     def alloc_blocks(self, n):
         arr = (ctypes.c_int32 * max(n, 1))()

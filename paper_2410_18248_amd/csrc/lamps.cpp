@@ -55,7 +55,7 @@ const char *derive(const lamps_config *c, Derived *d)
     d->block_bytes = 2 * d->half_bytes;
     d->pool_bytes = d->half_bytes * (size_t)c->num_blocks;
     d->part_tokens = c->part_tokens;
-    if (d->part_tokens == 0) d->part_tokens = c->block_size > 256 ? c->block_size : 256;
+    if (d->part_tokens == 0) d->part_tokens = c->block_size > 1024 ? c->block_size : 1024;
     if (d->part_tokens < 0 || d->part_tokens % c->block_size != 0)
         return "part_tokens must be a positive multiple of block_size";
     const int64_t max_ctx = (int64_t)c->max_blocks_per_req * c->block_size;
@@ -498,6 +498,15 @@ int lamps_compute_wait(lamps_ctx *c, uint64_t ticket)
     return LAMPS_OK;
 }
 
+int lamps_compute_wait_blocks(lamps_ctx *c, const int32_t *block_ids, int32_t n)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    int rc = check_ids(c, block_ids, n, "lamps_compute_wait_blocks");
+    if (rc != LAMPS_OK) return rc;
+    if ((rc = wait_guards(c, c->cs, c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
+    return wait_guards(c, c->cs, c->in_guard, block_ids, n);
+}
+
 int lamps_alloc_blocks(lamps_ctx *c, int32_t n, int32_t *block_ids_out)
 {
     if (!c) return LAMPS_ERR_INVALID;
@@ -510,17 +519,11 @@ int lamps_alloc_blocks(lamps_ctx *c, int32_t n, int32_t *block_ids_out)
         c->free_stack.pop_back();
         c->allocated[block_ids_out[i]] = 1;
     }
-    // a popped block may still be the source of an unfinished swap-out (or the
-    // target of an unfinished swap-in): later writers wait for it on the device
-    int rc;
-    if ((rc = wait_guards(c, c->cs, c->out_guard, block_ids_out, n)) != LAMPS_OK) return rc;
-    if (c->is != c->cs && (rc = wait_guards(c, c->is, c->out_guard, block_ids_out, n)) != LAMPS_OK)
-        return rc;
-    if ((rc = wait_guards(c, c->cs, c->in_guard, block_ids_out, n)) != LAMPS_OK) return rc;
-    for (int32_t i = 0; i < n; ++i) {
-        c->out_guard[block_ids_out[i]] = 0;
-        c->in_guard[block_ids_out[i]] = 0;
-    }
+    // A popped block may still be the source of an unfinished swap-out.  Its
+    // guard stays in place: lamps_swap_in orders itself behind it, and a caller
+    // that writes the block from the compute stream asks for the same with
+    // lamps_compute_wait_blocks.  Nothing is made to wait here, so decode steps
+    // of other requests keep running while the copy drains.
     return LAMPS_OK;
 }
 

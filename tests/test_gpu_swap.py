@@ -110,6 +110,34 @@ def test_freed_block_reuse_waits_for_its_swap_out():
     rig.close()
 
 
+def test_compute_stream_writer_is_ordered_by_compute_wait_blocks():
+    """A compute-stream writer of a re-allocated block (recompute after Discard,
+    KV append) goes behind the block's unfinished swap-out."""
+    geom = W.Geometry(8, 8, 8, 128, 16, 160, 8, "bf16")
+    bb = 2 * geom.block_half_bytes
+    rig = Rig(geom, max_batch=1)
+    lam = rig.lamps
+    _fill_random(rig, 22)
+    model = _model(rig)
+    lam.alloc_blocks(geom.num_blocks)
+    ids = list(range(5, 145))
+    host = _pinned(len(ids) * bb)
+    want = model.swap_out(ids)
+    t_out = lam.swap_out(ids, host)
+    lam.free_blocks(ids)
+    again = lam.alloc_blocks(len(ids))
+    lam.compute_wait_blocks(again)
+    with torch.cuda.stream(rig.compute):
+        idx = torch.as_tensor(again, device=rig.dev)
+        rig.k_pool[idx] = 0.0
+        rig.v_pool[idx] = 0.0
+    lam.ticket_wait(t_out)
+    rig.compute.synchronize()
+    np.testing.assert_array_equal(host.numpy().reshape(len(ids), bb), want)
+    assert (_bytes(rig.k_pool[again[0]]) == 0).all()
+    rig.close()
+
+
 def test_swap_in_right_behind_swap_out_through_one_buffer():
     geom = W.Geometry(4, 8, 8, 128, 16, 128, 8, "bf16")
     bb = 2 * geom.block_half_bytes
