@@ -239,14 +239,14 @@ class Job:
         res["bytes_each_way"] = nbytes
         return res
 
-    def unpage(self, b, r):
-        """Logical K, V of request r of rotation batch b, layer 0, as numpy (oracle input)."""
+    def unpage(self, b, r, layer):
+        """Logical K, V of request r of rotation batch b in one layer, as numpy (oracle input)."""
         torch, g = self.torch, self.g
         C = int(self.wl.ctx_lens[r])
         ids = torch.as_tensor(self.tables[b][r, :g.blocks_for(C)].astype(np.int64), device=self.dev)
 
         def logical(pool):
-            x = pool[ids, 0].cpu()                              # [nb][Hkv][bs][D]
+            x = pool[ids, layer].cpu()                          # [nb][Hkv][bs][D]
             x = x.view(torch.int16).numpy().view(np.uint16) if x.dtype == torch.bfloat16 else x.numpy()
             return np.ascontiguousarray(
                 np.swapaxes(x, 1, 2).reshape(-1, g.num_kv_heads, g.head_dim)[:C])
@@ -266,8 +266,9 @@ def cpu_baseline(job):
     q = q.view(torch.int16).numpy().view(np.uint16) if q.dtype == torch.bfloat16 else q.numpy()
     B = job.wl.batch
     K, V = [None] * B, [None] * B
+    last = job.g.num_layers - 1                     # job.out holds the last layer's result
     for r in np.flatnonzero(job.running):
-        K[r], V[r] = job.unpage(0, r)
+        K[r], V[r] = job.unpage(0, r, last)
     t0 = time.perf_counter()
     ref = oracle.decode_attn(q, K, V, job.wl.ctx_lens, job.running, threads=cores)
     dt = time.perf_counter() - t0

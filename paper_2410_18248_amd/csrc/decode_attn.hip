@@ -33,6 +33,10 @@ constexpr int kThreads = 64 * kWaves;
 // wave-wide 16-byte loads per chunk and pool; a chunk (loads * tokens per load)
 // must fit in the smallest block (16 tokens)
 constexpr int loads_per_chunk(int lpt) { return lpt == 8 ? 2 : 4; }
+#ifndef LAMPS_HALVES
+#define LAMPS_HALVES 2
+#endif
+constexpr int kHalves = LAMPS_HALVES;   // half-chunks in flight per wave for 1- and 2-head groups
 constexpr float kLowest = -3.0e38f;     // finite stand-in for "no score seen yet"
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -142,14 +146,16 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float (&acc)[VEC
 
 // One workgroup: one (partition, request, kv head / head chunk), decoded from a
 // 1-D grid.  GH query heads of the kv group share the K/V stream.
-template <bool BF16, int LPT, int GH>
+template <bool BF16, int LPT, int GH, int NH>
 __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
 {
     constexpr int VEC = BF16 ? 8 : 4;          // elements per 16-byte load
     constexpr int D = LPT * VEC;
     constexpr int TPW = 64 / LPT;              // tokens per wave-wide load
     constexpr int kLoads = loads_per_chunk(LPT);
-    constexpr int CT = TPW * kLoads;           // tokens per chunk (<= 16 <= block_size)
+    constexpr int HT = TPW * kLoads;           // tokens per half-chunk (<= 16 <= block_size)
+    constexpr int NL = NH * kLoads;            // wave-wide loads per chunk and pool
+    constexpr int CT = HT * NH;                // tokens per chunk
 
     // Workgroups are handed to the eight XCDs round-robin in launch order, so the
     // index that varies fastest must be one along which the work is even: the
@@ -201,36 +207,56 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     const char *kp = static_cast<const char *>(a.k_pool) + head_off + lane * 16;
     const char *vp = static_cast<const char *>(a.v_pool) + head_off + lane * 16;
 
+    // A chunk is NH half-chunks of HT tokens; a half-chunk never straddles a
+    // block (HT <= 16 <= block_size), so it needs one block-table entry.  All
+    // NH * kLoads K loads and as many V loads of a chunk are issued before any
+    // is consumed.
     int ch = w;
-    int pb = 0;
-    if (ch < n_chunks) pb = table[(t_begin + ch * CT) >> a.log2_block_size];
+    int pb[NH], pbn[NH];
+#pragma unroll
+    for (int f = 0; f < NH; ++f) {
+        const int th = t_begin + ch * CT + f * HT;
+        pb[f] = (ch < n_chunks && th < t_end) ? table[th >> a.log2_block_size] : -1;
+    }
     while (ch < n_chunks) {
         const int t0 = t_begin + ch * CT;
-        const size_t off = (size_t)pb * block_stride +
-                           (size_t)(t0 & (a.block_size - 1)) * D * (BF16 ? 2 : 4);
-        uint4 kx[kLoads], vx[kLoads];
+        uint4 kx[NL], vx[NL];
 #pragma unroll
-        for (int i = 0; i < kLoads; ++i)
-            kx[i] = load_stream16(kp + off + i * 1024);
+        for (int f = 0; f < NH; ++f) {
+            if (pb[f] >= 0) {                  // wave-uniform: half-chunks past the context are skipped
+                const size_t off = (size_t)pb[f] * block_stride +
+                                   (size_t)((t0 + f * HT) & (a.block_size - 1)) * D * (BF16 ? 2 : 4);
 #pragma unroll
-        for (int i = 0; i < kLoads; ++i)
-            vx[i] = load_stream16(vp + off + i * 1024);
+                for (int i = 0; i < kLoads; ++i) kx[f * kLoads + i] = load_stream16(kp + off + i * 1024);
+#pragma unroll
+                for (int i = 0; i < kLoads; ++i) vx[f * kLoads + i] = load_stream16(vp + off + i * 1024);
+            } else {
+#pragma unroll
+                for (int i = 0; i < kLoads; ++i) {
+                    kx[f * kLoads + i] = make_uint4(0, 0, 0, 0);
+                    vx[f * kLoads + i] = make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
 
-        // physical block of this wave's next chunk, fetched while the tiles arrive
+        // physical blocks of this wave's next chunk, fetched while the tiles arrive
         const int chn = ch + kWaves;
-        int pbn = 0;
-        if (chn < n_chunks) pbn = table[(t_begin + chn * CT) >> a.log2_block_size];
+#pragma unroll
+        for (int f = 0; f < NH; ++f) {
+            const int th = t_begin + chn * CT + f * HT;
+            pbn[f] = (chn < n_chunks && th < t_end) ? table[th >> a.log2_block_size] : -1;
+        }
 
-        float s[GH][kLoads];
+        float s[GH][NL];
 #pragma unroll
         for (int h = 0; h < GH; ++h)
 #pragma unroll
-            for (int i = 0; i < kLoads; ++i)
+            for (int i = 0; i < NL; ++i)
                 s[h][i] = sum_token_lanes<LPT>(dot16<BF16>(qv[h], kx[i])) * a.scale_log2e;
 
         if (t0 + CT > t_end) {                 // ragged tail: slots at or past ctx_len never count
 #pragma unroll
-            for (int i = 0; i < kLoads; ++i) {
+            for (int i = 0; i < NL; ++i) {
                 if (t0 + i * TPW + row >= t_end) {
 #pragma unroll
                     for (int h = 0; h < GH; ++h) s[h][i] = -INFINITY;
@@ -239,35 +265,35 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
             }
         }
 
-        float vf[kLoads][VEC];
-#pragma unroll
-        for (int i = 0; i < kLoads; ++i) unpack<BF16, VEC>(vx[i], vf[i]);
-
 #pragma unroll
         for (int h = 0; h < GH; ++h) {
             float mn = m[h];
 #pragma unroll
-            for (int i = 0; i < kLoads; ++i) mn = fmaxf(mn, s[h][i]);
-            float sc = fast_exp2(m[h] - mn);
-            float p[kLoads];
+            for (int i = 0; i < NL; ++i) mn = fmaxf(mn, s[h][i]);
+            const float sc = fast_exp2(m[h] - mn);
             float ps = 0.0f;
 #pragma unroll
-            for (int i = 0; i < kLoads; ++i) {
-                p[i] = fast_exp2(s[h][i] - mn);
-                ps += p[i];
+            for (int i = 0; i < NL; ++i) {
+                s[h][i] = fast_exp2(s[h][i] - mn);   // now the weight p
+                ps += s[h][i];
             }
             l[h] = l[h] * sc + ps;
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                float x = acc[h][e] * sc;
-#pragma unroll
-                for (int i = 0; i < kLoads; ++i) x = fmaf(p[i], vf[i][e], x);
-                acc[h][e] = x;
-            }
+            for (int e = 0; e < VEC; ++e) acc[h][e] *= sc;
             m[h] = mn;
         }
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            float vf[VEC];
+            unpack<BF16, VEC>(vx[i], vf);
+#pragma unroll
+            for (int h = 0; h < GH; ++h)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[h][e] = fmaf(s[h][i], vf[e], acc[h][e]);
+        }
         ch = chn;
-        pb = pbn;
+#pragma unroll
+        for (int f = 0; f < NH; ++f) pb[f] = pbn[f];
     }
 
     // rows of a wave -> one state per wave
@@ -356,9 +382,9 @@ template <bool BF16, int LPT>
 hipError_t launch_partial(const DecodeArgs &a, int gh, dim3 grid, hipStream_t s)
 {
     switch (gh) {
-    case 1: hipLaunchKernelGGL((decode_partial<BF16, LPT, 1>), grid, dim3(kThreads), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((decode_partial<BF16, LPT, 2>), grid, dim3(kThreads), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((decode_partial<BF16, LPT, 4>), grid, dim3(kThreads), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((decode_partial<BF16, LPT, 1, kHalves>), grid, dim3(kThreads), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((decode_partial<BF16, LPT, 2, kHalves>), grid, dim3(kThreads), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((decode_partial<BF16, LPT, 4, 1>), grid, dim3(kThreads), 0, s, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -215,3 +215,37 @@ def _full_size(cfg, sample_requests, rep=0):
 def test_full_size_sampled_parity(cfg, sample):
     worst = _full_size(cfg, sample)
     assert worst <= 2e-2, worst
+
+
+def test_cfg4_full_size_layers_sampled():
+    """The 40-layer configuration at full size (about 110 GB of pools): layers
+    0, 19 and 39, a seeded sample of running requests each."""
+    wl = W.workload(4)
+    geom = wl.geom
+    seed = W.config_seed(4)
+    free, _ = torch.cuda.mem_get_info()
+    need = 2 * geom.num_blocks * geom.block_half_bytes
+    if free < need * 1.05:
+        pytest.skip("needs %.0f GB of free HBM" % (need / 1e9))
+    rig = Rig(geom, max_batch=wl.batch, poison=False)
+    gen = torch.Generator(device=rig.dev).manual_seed(seed)
+    rig.k_pool.normal_(generator=gen)
+    rig.v_pool.normal_(generator=gen)
+    perm = W.permutation(seed + 3, geom.num_blocks)
+    table, _ = W.deal_block_table(perm, wl.ctx_lens, geom)
+    q = torch.empty((wl.batch, geom.num_q_heads, geom.head_dim), dtype=rig.tdtype,
+                    device=rig.dev).normal_(generator=gen)
+    qn = t2n(q)
+    running = (wl.state == W.RUNNING).astype(np.uint8)
+    run_idx = np.flatnonzero(running)
+    for layer in (0, 19, 39):
+        out = rig.decode(layer, q, table, wl.ctx_lens, running, sentinel=3.0)
+        got = to_f64(out)
+        pick = run_idx[W.permutation(seed + 10 + layer, len(run_idx))[:6]]
+        for r in pick:
+            C = int(wl.ctx_lens[r])
+            k, v = rig.unpage_request(layer, table[r], C)
+            ref = oracle.decode_attn(qn[r:r + 1], [k], [v], [C], [1], threads=8)
+            assert np.abs(got[r] - ref[0]).max() <= 2e-2, (layer, r)
+        assert (got[running == 0] == 3.0).all()
+    rig.close()
