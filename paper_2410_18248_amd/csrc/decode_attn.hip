@@ -3,24 +3,35 @@
 // Computes, for every running request r and query head h, the Section 2.2
 // equation of arXiv 2410.18248,  out = softmax(q K^T * scale) V,  over the
 // first ctx_lens[r] cached positions of r, with K and V reached through the
-// block table (paged attention, Section 7).  The context is cut into
-// partitions of `part_tokens` tokens; one workgroup reduces one
-// (request, kv head, partition) to (max, sum, weighted value sum) with an
-// online softmax, and a second small kernel merges the partitions of a request
-// (skipped when the configuration has a single partition per request).
+// block table (paged attention, Section 7).
+//
+// Work decomposition.  The unit of work is a chunk of CT tokens of one
+// (request, kv head).  Two schemes share the same inner loop:
+//   balanced (default): all chunks of all running requests form one flat
+//     sequence; a fixed number of workgroups (one full occupancy wave of the
+//     chip) each take an equal contiguous share of it, so every workgroup ends
+//     within a chunk of the others however skewed the context lengths are.  A
+//     share is at most: the tail of one (request, head), some whole ones, and
+//     the head of another; whole ones are written out directly, the two
+//     partial ends go to per-workgroup slots that a small second kernel merges.
+//   fixed partitions (part_tokens > 0): the context is cut every part_tokens
+//     tokens, one workgroup per (partition, request, kv head) in a dense grid.
 //
 // Mapping to the hardware.  The path is a stream over K and V (every byte is
 // used once: ~1 flop/byte), so it is HBM-bound and runs on the vector ALUs, not
 // on MFMA.  A (block, layer, kv head) tile is block_size*head_dim contiguous
-// elements; a wavefront reads it with fully coalesced 16-byte-per-lane loads:
-// LPT = head_dim*sizeof/16 lanes cover one token, 64/LPT tokens per load.  Each
-// lane keeps its 16-byte slice of q for all heads of the kv group in
-// registers, so the G query heads of a group share every K/V byte that is
-// loaded.  The dot product is finished with DPP adds inside the LPT lanes (no
-// LDS).  Each group of LPT lanes ("row") carries its own running max / sum /
-// accumulator over the tokens it sees, so there is no cross-lane traffic in
-// the main loop beyond the dot-product reduction; rows are merged by shuffles
-// and the four waves through LDS once per workgroup.
+// elements; a wavefront reads it with fully coalesced, non-temporal 16-byte-
+// per-lane loads: LPT = head_dim*sizeof/16 lanes cover one token, 64/LPT
+// tokens per load.  Each lane keeps its 16-byte slice of q for all heads of
+// the kv group in registers, so the G query heads of a group share every K/V
+// byte that is loaded.  The dot product is finished with DPP adds inside the
+// LPT lanes (no LDS).  Each group of LPT lanes ("row") carries its own running
+// max / sum / accumulator over the tokens it sees, so there is no cross-lane
+// traffic in the main loop beyond the dot-product reduction; rows are merged
+// by shuffles and the four waves through LDS once per (request, head) range.
+// Partitions are merged by a separate launch on purpose: a kernel boundary
+// makes the partials visible across the eight XCDs' L2s once, whereas a
+// device-scope fence per workgroup writes back and invalidates an L2 each time.
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
@@ -38,6 +49,7 @@ constexpr int loads_per_chunk(int lpt) { return lpt == 8 ? 2 : 4; }
 #endif
 constexpr int kHalves = LAMPS_HALVES;   // half-chunks in flight per wave for 1- and 2-head groups
 constexpr float kLowest = -3.0e38f;     // finite stand-in for "no score seen yet"
+constexpr int kMaxShares = 4096;        // most workgroups the balanced scheme ever launches
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
@@ -144,51 +156,51 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float (&acc)[VEC
     m = mn;
 }
 
-// One workgroup: one (partition, request, kv head / head chunk), decoded from a
-// 1-D grid.  GH query heads of the kv group share the K/V stream.
+
+// Compile-time shape of one instantiation.
 template <bool BF16, int LPT, int GH, int NH>
-__global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
+struct Shape {
+    static constexpr int VEC = BF16 ? 8 : 4;          // elements per 16-byte load
+    static constexpr int D = LPT * VEC;
+    static constexpr int ES = BF16 ? 2 : 4;           // element bytes
+    static constexpr int TPW = 64 / LPT;              // tokens per wave-wide load
+    static constexpr int kLoads = loads_per_chunk(LPT);
+    static constexpr int HT = TPW * kLoads;           // tokens per half-chunk (<= 16 <= block_size)
+    static constexpr int NL = NH * kLoads;            // wave-wide loads per chunk and pool
+    static constexpr int CT = HT * NH;                // tokens per chunk
+};
+
+template <int GH, int D>
+struct WaveMerge {                                    // LDS for the cross-wave merge
+    float acc[kWaves][GH][D];
+    float m[kWaves][GH], l[kWaves][GH];
+};
+
+// Reduces cached positions [t_begin, t_end) of request r (kv head g, query heads
+// h0 .. h0+GH-1) with all four waves of the workgroup, then calls
+// sink(h, d, M, L, A) once for every (head, dim): M = running max (log2 domain),
+// L = sum of weights, A = weighted sum of V[:, d].  t_begin is a multiple of CT.
+// Contains two workgroup barriers; must be called by all threads.
+template <bool BF16, int LPT, int GH, int NH, typename Sink>
+__device__ __forceinline__ void reduce_range(const DecodeArgs &a, int r, int g, int h0, int t_begin,
+                                             int t_end, WaveMerge<GH, LPT *(BF16 ? 8 : 4)> &sm,
+                                             Sink sink)
 {
-    constexpr int VEC = BF16 ? 8 : 4;          // elements per 16-byte load
-    constexpr int D = LPT * VEC;
-    constexpr int TPW = 64 / LPT;              // tokens per wave-wide load
-    constexpr int kLoads = loads_per_chunk(LPT);
-    constexpr int HT = TPW * kLoads;           // tokens per half-chunk (<= 16 <= block_size)
-    constexpr int NL = NH * kLoads;            // wave-wide loads per chunk and pool
-    constexpr int CT = HT * NH;                // tokens per chunk
-
-    // Workgroups are handed to the eight XCDs round-robin in launch order, so the
-    // index that varies fastest must be one along which the work is even: the
-    // kv head (and head chunk), then the request, then the partition.  (With the
-    // partition fastest and eight partitions, all first partitions -- most of
-    // the work -- would land on one XCD.)
-    const int G = a.num_q_heads / a.num_kv_heads;
-    const int chunks_per_group = G / GH;
-    const int hc_count = a.num_kv_heads * chunks_per_group;
-    const int hc = blockIdx.x % hc_count;
-    const int r = (blockIdx.x / hc_count) % a.batch;
-    const int part = blockIdx.x / (hc_count * a.batch);
-    if (!a.running[r]) return;                 // Preserve / Swap / Discard: not in the batch
-    const int C = a.ctx_lens[r];
-    const int t_begin = part * a.part_tokens;
-    if (t_begin >= C && part != 0) return;     // partition 0 of an empty context writes zeros
-    const int t_end = min(C, t_begin + a.part_tokens);
-    const int n_parts = max(1, (C + a.part_tokens - 1) / a.part_tokens);
-    const int g = hc / chunks_per_group;
-    const int h0 = g * G + (hc % chunks_per_group) * GH;
-
+    using S = Shape<BF16, LPT, GH, NH>;
+    constexpr int VEC = S::VEC, D = S::D, TPW = S::TPW, kLoads = S::kLoads, HT = S::HT, NL = S::NL,
+                  CT = S::CT;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row = lane / LPT;                // which of the TPW tokens of a load
     const int col = lane % LPT;                // which 16-byte slice of the head vector
 
-    // q slices of the GH heads, kept in registers for the whole partition.
+    // q slices of the GH heads, kept in registers for the whole range
     uint4 qv[GH];
 #pragma unroll
     for (int h = 0; h < GH; ++h)
         qv[h] = *reinterpret_cast<const uint4 *>(
-            static_cast<const char *>(a.q) + (((size_t)r * a.num_q_heads + h0 + h) * D + col * VEC) *
-                                                 (BF16 ? 2 : 4));
+            static_cast<const char *>(a.q) +
+            (((size_t)r * a.num_q_heads + h0 + h) * D + col * VEC) * S::ES);
 
     float m[GH], l[GH], acc[GH][VEC];
 #pragma unroll
@@ -201,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
 
     const int n_chunks = (t_end - t_begin + CT - 1) / CT;
     const int32_t *table = a.block_table + (size_t)r * a.max_blocks;
-    const size_t tile_bytes = (size_t)a.block_size * D * (BF16 ? 2 : 4);
+    const size_t tile_bytes = (size_t)a.block_size * D * S::ES;
     const size_t block_stride = (size_t)a.num_layers * a.num_kv_heads * tile_bytes;
     const size_t head_off = ((size_t)a.layer * a.num_kv_heads + g) * tile_bytes;
     const char *kp = static_cast<const char *>(a.k_pool) + head_off + lane * 16;
@@ -210,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     // A chunk is NH half-chunks of HT tokens; a half-chunk never straddles a
     // block (HT <= 16 <= block_size), so it needs one block-table entry.  All
     // NH * kLoads K loads and as many V loads of a chunk are issued before any
-    // is consumed.
+    // is consumed.  Wave w takes chunks w, w + 4, ...
     int ch = w;
     int pb[NH], pbn[NH];
 #pragma unroll
@@ -225,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
         for (int f = 0; f < NH; ++f) {
             if (pb[f] >= 0) {                  // wave-uniform: half-chunks past the context are skipped
                 const size_t off = (size_t)pb[f] * block_stride +
-                                   (size_t)((t0 + f * HT) & (a.block_size - 1)) * D * (BF16 ? 2 : 4);
+                                   (size_t)((t0 + f * HT) & (a.block_size - 1)) * D * S::ES;
 #pragma unroll
                 for (int i = 0; i < kLoads; ++i) kx[f * kLoads + i] = load_stream16(kp + off + i * 1024);
 #pragma unroll
@@ -310,51 +322,88 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     }
 
     // waves -> one state per workgroup, through LDS
-    __shared__ float sm_acc[kWaves][GH][D];
-    __shared__ float sm_m[kWaves][GH], sm_l[kWaves][GH];
+    __syncthreads();                           // the previous range's readers are done with sm
     if (row == 0) {
 #pragma unroll
         for (int h = 0; h < GH; ++h) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) sm_acc[w][h][col * VEC + e] = acc[h][e];
+            for (int e = 0; e < VEC; ++e) sm.acc[w][h][col * VEC + e] = acc[h][e];
             if (col == 0) {
-                sm_m[w][h] = m[h];
-                sm_l[w][h] = l[h];
+                sm.m[w][h] = m[h];
+                sm.l[w][h] = l[h];
             }
         }
     }
     __syncthreads();
-
-    const size_t rh0 = (size_t)r * a.num_q_heads + h0;
     for (int idx = threadIdx.x; idx < GH * D; idx += kThreads) {
         const int h = idx / D, d = idx % D;
-        float M = sm_m[0][h];
+        float M = sm.m[0][h];
 #pragma unroll
-        for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, sm_m[ww][h]);
+        for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, sm.m[ww][h]);
         float L = 0.0f, A = 0.0f;
 #pragma unroll
         for (int ww = 0; ww < kWaves; ++ww) {
-            float f = fast_exp2(sm_m[ww][h] - M);
-            L += sm_l[ww][h] * f;
-            A += sm_acc[ww][h][d] * f;
+            float f = fast_exp2(sm.m[ww][h] - M);
+            L += sm.l[ww][h] * f;
+            A += sm.acc[ww][h][d] * f;
         }
-        if (n_parts == 1) {
-            store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
-        } else {
-            float *pp = a.partials + ((rh0 + h) * a.max_parts + part) * (D + 2);
-            pp[d] = A;
-            if (d == 0) {
-                pp[D] = M;
-                pp[D + 1] = L;
-            }
-        }
+        sink(h, d, M, L, A);
     }
 }
 
+__device__ __forceinline__ void store_partial(float *pp, int D, int d, float M, float L, float A)
+{
+    pp[d] = A;
+    if (d == 0) {
+        pp[D] = M;
+        pp[D + 1] = L;
+    }
+}
+
+// ---------------------------------------------------------------- fixed partitions
+
+// One workgroup: one (partition, request, kv head / head chunk), decoded from a
+// 1-D grid.  GH query heads of the kv group share the K/V stream.
+template <bool BF16, int LPT, int GH, int NH>
+__global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
+{
+    using S = Shape<BF16, LPT, GH, NH>;
+    constexpr int D = S::D;
+    __shared__ WaveMerge<GH, D> sm;
+
+    // Workgroups are handed to the eight XCDs round-robin in launch order, so the
+    // index that varies fastest must be one along which the work is even: the
+    // kv head (and head chunk), then the request, then the partition.  (With the
+    // partition fastest and eight partitions, all first partitions -- most of
+    // the work -- would land on one XCD.)
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int chunks_per_group = G / GH;
+    const int hc_count = a.num_kv_heads * chunks_per_group;
+    const int hc = blockIdx.x % hc_count;
+    const int r = (blockIdx.x / hc_count) % a.batch;
+    const int part = blockIdx.x / (hc_count * a.batch);
+    const int running = a.running[r];          // both loads are in flight together
+    const int C = a.ctx_lens[r];
+    if (!running) return;                      // Preserve / Swap / Discard: not in the batch
+    const int t_begin = part * a.part_tokens;
+    if (t_begin >= C && part != 0) return;     // partition 0 of an empty context writes zeros
+    const int t_end = min(C, t_begin + a.part_tokens);
+    const int n_parts = max(1, (C + a.part_tokens - 1) / a.part_tokens);
+    const int g = hc / chunks_per_group;
+    const int h0 = g * G + (hc % chunks_per_group) * GH;
+    const size_t rh0 = (size_t)r * a.num_q_heads + h0;
+
+    reduce_range<BF16, LPT, GH, NH>(a, r, g, h0, t_begin, t_end, sm,
+        [&](int h, int d, float M, float L, float A) {
+            if (n_parts == 1)
+                store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
+            else
+                store_partial(a.partials + ((rh0 + h) * a.max_parts + part) * (D + 2), D, d, M, L, A);
+        });
+}
+
 // Merge of the partitions of one (request, query head), always in partition
-// order; block = head_dim threads.  A separate launch on purpose: a kernel
-// boundary makes the partials visible across the eight XCDs' L2s once, whereas
-// a device-scope fence per workgroup writes back and invalidates an L2 each time.
+// order; block = head_dim threads.
 template <bool BF16>
 __global__ void decode_merge(const DecodeArgs a)
 {
@@ -378,16 +427,198 @@ __global__ void decode_merge(const DecodeArgs a)
     store_out<BF16>(a.out, rh * D + d, L > 0.0f ? A / L : 0.0f);
 }
 
+// ---------------------------------------------------------------- balanced shares
+
+// Chunks a running request contributes per (kv head, head chunk): an empty
+// context still gets one (empty) chunk so that its zero row is written.
+__device__ __forceinline__ int chunks_of(int running, int C, int CT)
+{
+    return running ? max(1, (C + CT - 1) / CT) : 0;
+}
+
+// gridDim.x workgroups, each an equal contiguous share of the flat chunk
+// sequence ordered (request, head chunk, chunk).  prefix[] (dynamic LDS,
+// batch + 1 ints) holds the running chunk count per request; every workgroup
+// computes it for itself from ctx_lens / running (a few hundred loads that hit
+// in L2), which costs less than a dependent launch.
+template <bool BF16, int LPT, int GH, int NH>
+__global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
+{
+    using S = Shape<BF16, LPT, GH, NH>;
+    constexpr int D = S::D, CT = S::CT;
+    extern __shared__ int prefix[];
+    __shared__ WaveMerge<GH, D> sm;
+    __shared__ int wave_total[kWaves];
+
+    const int B = a.batch;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int per = (B + kThreads - 1) / kThreads;   // consecutive requests per thread
+    int mine = 0;
+    for (int i = 0; i < per; ++i) {
+        const int r = tid * per + i;
+        if (r < B) mine += chunks_of(a.running[r], a.ctx_lens[r], CT);
+    }
+    int incl = mine;                                  // inclusive scan inside the wave
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt *= 2) {
+        const int up = __shfl_up(incl, dlt);
+        if (lane >= dlt) incl += up;
+    }
+    if (lane == 63) wave_total[wv] = incl;
+    __syncthreads();
+    int run = incl - mine;
+    for (int ww = 0; ww < wv; ++ww) run += wave_total[ww];
+    if (tid == 0) prefix[0] = 0;
+    for (int i = 0; i < per; ++i) {
+        const int r = tid * per + i;
+        if (r < B) {
+            run += chunks_of(a.running[r], a.ctx_lens[r], CT);
+            prefix[r + 1] = run;
+        }
+    }
+    __syncthreads();
+
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int chunks_per_group = G / GH;
+    const int HC = a.num_kv_heads * chunks_per_group;
+    const long long total = (long long)HC * prefix[B];
+    if (blockIdx.x == 0)                              // the merge kernel reads it back
+        for (int i = tid; i <= B; i += kThreads) a.chunk_prefix[i] = prefix[i];
+    const long long x_begin = (long long)blockIdx.x * total / gridDim.x;
+    const long long x_end = (long long)(blockIdx.x + 1) * total / gridDim.x;
+    if (x_begin >= x_end) return;
+
+    // request that holds position x_begin: the last r with HC * prefix[r] <= x_begin
+    int lo = 0, hi = B;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((long long)HC * prefix[mid] <= x_begin) lo = mid; else hi = mid;
+    }
+    int r = __builtin_amdgcn_readfirstlane(lo);
+    long long x = x_begin;
+    while (x < x_end) {
+        const int base = __builtin_amdgcn_readfirstlane(prefix[r]);
+        const int nr = __builtin_amdgcn_readfirstlane(prefix[r + 1]) - base;   // > 0 here
+        const long long rem = x - (long long)HC * base;
+        const int hc = (int)(rem / nr), c0 = (int)(rem % nr);
+        const int len = (int)min((long long)(nr - c0), x_end - x);
+        const int C = a.ctx_lens[r];
+        const int g = hc / chunks_per_group;
+        const int h0 = g * G + (hc % chunks_per_group) * GH;
+        const bool whole = (c0 == 0 && len == nr);
+        // a share's first range goes to slot 0, a later partial one (its last) to slot 1
+        float *slot = a.partials + ((size_t)blockIdx.x * 2 + (x == x_begin ? 0 : 1)) * GH * (D + 2);
+        const size_t rh0 = (size_t)r * a.num_q_heads + h0;
+        reduce_range<BF16, LPT, GH, NH>(a, r, g, h0, c0 * CT, min(C, (c0 + len) * CT), sm,
+            [&](int h, int d, float M, float L, float A) {
+                if (whole)
+                    store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
+                else
+                    store_partial(slot + (size_t)h * (D + 2), D, d, M, L, A);
+            });
+        x += len;
+        if (c0 + len == nr && hc == HC - 1) {         // request finished: next one with work
+            ++r;
+            while (r < B && prefix[r + 1] == prefix[r]) ++r;
+        }
+    }
+}
+
+// Position x of the flat chunk sequence belongs to workgroup w with
+// floor(w * total / P) <= x < floor((w + 1) * total / P).
+__device__ __forceinline__ long long share_of(long long x, long long total, int P)
+{
+    return ((x + 1) * P - 1) / total;
+}
+
+// Merges the pieces of every (request, head chunk) that was split over several
+// shares, in share order (= token order).  grid = (head chunks, batch).
+template <bool BF16, int GH>
+__global__ void decode_merge_balanced(const DecodeArgs a, int P)
+{
+    const int r = blockIdx.y, hc = blockIdx.x;
+    const int D = a.head_dim;
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int chunks_per_group = G / GH;
+    const int HC = a.num_kv_heads * chunks_per_group;
+    const int base = a.chunk_prefix[r], nr = a.chunk_prefix[r + 1] - base;
+    if (nr == 0) return;                              // not running: row untouched
+    const long long total = (long long)HC * a.chunk_prefix[a.batch];
+    const long long off = (long long)HC * base + (long long)hc * nr;
+    const int w_first = (int)share_of(off, total, P), w_last = (int)share_of(off + nr - 1, total, P);
+    if (w_first == w_last) return;                    // one share held it all and wrote the result
+    const int g = hc / chunks_per_group;
+    const size_t rh0 = (size_t)r * a.num_q_heads + g * G + (hc % chunks_per_group) * GH;
+    for (int idx = threadIdx.x; idx < GH * D; idx += blockDim.x) {
+        const int h = idx / D, d = idx % D;
+        float M = kLowest;
+        for (int w = w_first; w <= w_last; ++w) {
+            const long long xb = (long long)w * total / P;
+            if (xb >= (long long)(w + 1) * total / P) continue;     // empty share (more shares than chunks)
+            const int slot = xb >= off ? 0 : 1;
+            M = fmaxf(M, a.partials[(((size_t)w * 2 + slot) * GH + h) * (D + 2) + D]);
+        }
+        float L = 0.0f, A = 0.0f;
+        for (int w = w_first; w <= w_last; ++w) {
+            const long long xb = (long long)w * total / P;
+            if (xb >= (long long)(w + 1) * total / P) continue;
+            const int slot = xb >= off ? 0 : 1;
+            const float *x = a.partials + (((size_t)w * 2 + slot) * GH + h) * (D + 2);
+            const float f = fast_exp2(x[D] - M);
+            L += x[D + 1] * f;
+            A += x[d] * f;
+        }
+        store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
+    }
+}
+
+// ---------------------------------------------------------------- launchers
+
+template <bool BF16, int LPT, int GH, int NH>
+hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
+{
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int HC = a.num_kv_heads * (G / GH);
+    if (a.part_tokens > 0) {
+        dim3 grid((unsigned)((size_t)a.max_parts * HC * a.batch));
+        hipLaunchKernelGGL((decode_partial<BF16, LPT, GH, NH>), grid, dim3(kThreads), 0, s, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess || a.max_parts == 1) return e;
+        hipLaunchKernelGGL(decode_merge<BF16>, dim3(a.num_q_heads, a.batch), dim3(a.head_dim), 0, s, a);
+        return hipGetLastError();
+    }
+    // balanced: as many workgroups as the chip holds at once for this kernel
+    static int resident = 0;                          // per instantiation; one device per process
+    if (resident == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
+                &per_cu, decode_balanced<BF16, LPT, GH, NH>, kThreads, (a.max_batch + 1) * sizeof(int));
+        if (e != hipSuccess) return e;
+        if (cus < 1 || per_cu < 1) return hipErrorInvalidValue;
+        resident = cus * per_cu;
+        if (resident > kMaxShares) resident = kMaxShares;
+    }
+    const size_t lds = (size_t)(a.batch + 1) * sizeof(int);
+    hipLaunchKernelGGL((decode_balanced<BF16, LPT, GH, NH>), dim3(resident), dim3(kThreads), lds, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int mt = GH * a.head_dim < 256 ? GH * a.head_dim : 256;
+    hipLaunchKernelGGL((decode_merge_balanced<BF16, GH>), dim3(HC, a.batch), dim3(mt), 0, s, a, resident);
+    return hipGetLastError();
+}
+
 template <bool BF16, int LPT>
-hipError_t launch_partial(const DecodeArgs &a, int gh, dim3 grid, hipStream_t s)
+hipError_t launch_gh(const DecodeArgs &a, int gh, hipStream_t s)
 {
     switch (gh) {
-    case 1: hipLaunchKernelGGL((decode_partial<BF16, LPT, 1, kHalves>), grid, dim3(kThreads), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((decode_partial<BF16, LPT, 2, kHalves>), grid, dim3(kThreads), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((decode_partial<BF16, LPT, 4, 1>), grid, dim3(kThreads), 0, s, a); break;
+    case 1: return launch_one<BF16, LPT, 1, kHalves>(a, s);
+    case 2: return launch_one<BF16, LPT, 2, kHalves>(a, s);
+    case 4: return launch_one<BF16, LPT, 4, 1>(a, s);
     default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 }  // namespace
@@ -402,6 +633,8 @@ int decode_heads_per_group(int bf16, int head_dim, int group)
     return 1;
 }
 
+int decode_max_shares() { return kMaxShares; }
+
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
 {
     if (a.batch == 0) return hipSuccess;
@@ -409,24 +642,16 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
     const int gh = decode_heads_per_group(a.bf16, a.head_dim, G);
     if (gh == 0) return hipErrorInvalidValue;
     const int lpt = a.head_dim * (a.bf16 ? 2 : 4) / 16;
-    dim3 grid((unsigned)((size_t)a.max_parts * a.num_kv_heads * (G / gh) * a.batch));
-    hipError_t e = hipErrorInvalidValue;
     if (a.bf16) {
-        if (lpt == 8) e = launch_partial<true, 8>(a, gh, grid, stream);
-        if (lpt == 16) e = launch_partial<true, 16>(a, gh, grid, stream);
-        if (lpt == 32) e = launch_partial<true, 32>(a, gh, grid, stream);
+        if (lpt == 8) return launch_gh<true, 8>(a, gh, stream);
+        if (lpt == 16) return launch_gh<true, 16>(a, gh, stream);
+        if (lpt == 32) return launch_gh<true, 32>(a, gh, stream);
     } else {
-        if (lpt == 8) e = launch_partial<false, 8>(a, gh, grid, stream);
-        if (lpt == 16) e = launch_partial<false, 16>(a, gh, grid, stream);
-        if (lpt == 32) e = launch_partial<false, 32>(a, gh, grid, stream);
+        if (lpt == 8) return launch_gh<false, 8>(a, gh, stream);
+        if (lpt == 16) return launch_gh<false, 16>(a, gh, stream);
+        if (lpt == 32) return launch_gh<false, 32>(a, gh, stream);
     }
-    if (e != hipSuccess || a.max_parts == 1) return e;
-    dim3 mg(a.num_q_heads, a.batch);
-    if (a.bf16)
-        hipLaunchKernelGGL(decode_merge<true>, mg, dim3(a.head_dim), 0, stream, a);
-    else
-        hipLaunchKernelGGL(decode_merge<false>, mg, dim3(a.head_dim), 0, stream, a);
-    return hipGetLastError();
+    return hipErrorInvalidValue;
 }
 
 }  // namespace lamps

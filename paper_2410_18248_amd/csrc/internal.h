@@ -13,9 +13,11 @@ struct DecodeArgs {
     const int32_t *block_table;  // [batch][max_blocks]
     const int32_t *ctx_lens;     // [batch]
     const uint8_t *running;      // [batch]
-    float *partials;          // [batch][H][max_parts][D + 2]
+    float *partials;          // fixed partitions: [batch][H][max_parts][D + 2];
+                              // balanced: [share][2][heads per group][D + 2]
+    int32_t *chunk_prefix;    // balanced: [batch + 1] running chunk count per request
     void *out;                // [batch][H][D]
-    int32_t batch, layer, num_layers, num_q_heads, num_kv_heads, head_dim;
+    int32_t batch, max_batch, layer, num_layers, num_q_heads, num_kv_heads, head_dim;
     int32_t block_size, log2_block_size, max_blocks, part_tokens, max_parts;
     int32_t bf16;             // 0: fp32 storage, 1: bf16 storage
     float scale_log2e;        // softmax scale * log2(e)
@@ -25,8 +27,12 @@ struct DecodeArgs {
 // (0 if the geometry is not supported).
 int decode_heads_per_group(int bf16, int head_dim, int group);
 
-// Enqueues one layer of decode attention: the partition kernel, then the merge
-// kernel if a request can have more than one partition.
+// Most workgroups ("shares") the balanced scheme launches; sizes its partials.
+int decode_max_shares();
+
+// Enqueues one layer of decode attention.  part_tokens == 0 selects the balanced
+// scheme (then max_parts is ignored), part_tokens > 0 fixed partitions; either
+// way a small merge kernel follows unless no request can be split.
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
 
 // Gather: staging image i (key bytes then value bytes of block ids[i]) <- pools.

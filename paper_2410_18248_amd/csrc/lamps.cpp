@@ -28,7 +28,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Derived {
     size_t elem = 0, half_bytes = 0, block_bytes = 0, pool_bytes = 0;
-    size_t partial_bytes = 0, staging_bytes = 0, workspace_bytes = 0;
+    size_t partial_bytes = 0, prefix_bytes = 0, staging_bytes = 0, workspace_bytes = 0;
     int part_tokens = 0, max_parts = 0, log2_bs = 0, blocks_per_chunk = 0;
     float scale_log2e = 0.f;
 };
@@ -55,13 +55,22 @@ const char *derive(const lamps_config *c, Derived *d)
     d->block_bytes = 2 * d->half_bytes;
     d->pool_bytes = d->half_bytes * (size_t)c->num_blocks;
     d->part_tokens = c->part_tokens;
-    if (d->part_tokens == 0) d->part_tokens = c->block_size > 1024 ? c->block_size : 1024;
     if (d->part_tokens < 0 || d->part_tokens % c->block_size != 0)
-        return "part_tokens must be a positive multiple of block_size";
-    const int64_t max_ctx = (int64_t)c->max_blocks_per_req * c->block_size;
-    d->max_parts = (int)((max_ctx + d->part_tokens - 1) / d->part_tokens);
-    if (d->max_parts > 65535) return "too many partitions per request; raise part_tokens";
-    d->partial_bytes = (size_t)c->max_batch * c->num_q_heads * d->max_parts * (c->head_dim + 2) * 4;
+        return "part_tokens must be 0 or a positive multiple of block_size";
+    if (c->max_batch > 8192) return "max_batch is limited to 8192";
+    const int group = c->num_q_heads / c->num_kv_heads;
+    const int gh = lamps::decode_heads_per_group(bf16, c->head_dim, group);
+    if (d->part_tokens > 0) {
+        const int64_t max_ctx = (int64_t)c->max_blocks_per_req * c->block_size;
+        d->max_parts = (int)((max_ctx + d->part_tokens - 1) / d->part_tokens);
+        const int64_t wgs = (int64_t)d->max_parts * c->max_batch * c->num_kv_heads * (group / gh);
+        if (wgs > 0x7fffffff) return "too many partitions; raise part_tokens";
+        d->partial_bytes = (size_t)c->max_batch * c->num_q_heads * d->max_parts * (c->head_dim + 2) * 4;
+    } else {
+        d->max_parts = 0;
+        d->partial_bytes = (size_t)lamps::decode_max_shares() * 2 * gh * (c->head_dim + 2) * 4;
+    }
+    d->prefix_bytes = (size_t)(c->max_batch + 1) * sizeof(int32_t);
     if (c->staging_bytes < 0) return "staging_bytes is negative";
     size_t st = c->staging_bytes ? (size_t)c->staging_bytes : (size_t)64 << 20;
     if (c->staging_bytes == 0 && st < d->block_bytes) st = d->block_bytes;
@@ -71,7 +80,8 @@ const char *derive(const lamps_config *c, Derived *d)
     if (bpc > (size_t)c->num_blocks) bpc = c->num_blocks;
     d->blocks_per_chunk = (int)bpc;
     d->staging_bytes = bpc * d->block_bytes;
-    d->workspace_bytes = align256(d->partial_bytes) + 2 * align256(d->staging_bytes);
+    d->workspace_bytes = align256(d->partial_bytes) + align256(d->prefix_bytes) +
+                         2 * align256(d->staging_bytes);
     const float scale = c->softmax_scale != 0.f ? c->softmax_scale : 1.0f / std::sqrt((float)c->head_dim);
     d->scale_log2e = scale * 1.4426950408889634f;
     return nullptr;
@@ -91,6 +101,7 @@ struct lamps_ctx {
     Derived d;
     char *k_pool, *v_pool;
     float *partials;
+    int32_t *chunk_prefix;
     char *stage_out, *stage_in;
     hipStream_t cs, os, is;
 
@@ -322,7 +333,8 @@ int lamps_create(const lamps_config *cfg, void *k_pool, void *v_pool, void *work
     c->v_pool = static_cast<char *>(v_pool);
     char *ws = static_cast<char *>(workspace);
     c->partials = reinterpret_cast<float *>(ws);
-    c->stage_out = ws + align256(d.partial_bytes);
+    c->chunk_prefix = reinterpret_cast<int32_t *>(ws + align256(d.partial_bytes));
+    c->stage_out = ws + align256(d.partial_bytes) + align256(d.prefix_bytes);
     c->stage_in = c->stage_out + align256(d.staging_bytes);
     c->cs = static_cast<hipStream_t>(compute_stream);
     c->os = static_cast<hipStream_t>(swap_out_stream);
@@ -375,6 +387,8 @@ int lamps_decode_attn(lamps_ctx *c, int32_t layer, int32_t batch, const void *q,
     a.ctx_lens = ctx_lens;
     a.running = running_mask;
     a.partials = c->partials;
+    a.chunk_prefix = c->chunk_prefix;
+    a.max_batch = c->cfg.max_batch;
     a.out = out;
     a.batch = batch;
     a.layer = layer;

@@ -47,7 +47,11 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("dtype,H,Hkv,D,bs,part,ctx", CASES)
+# every case under both work decompositions: fixed partitions (part > 0) and balanced shares (0)
+BOTH = CASES + [c[:5] + (0,) + c[6:] for c in CASES if c[5] != 0]
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,D,bs,part,ctx", BOTH)
 def test_small_parity(dtype, H, Hkv, D, bs, part, ctx):
     mb = max(1, max((c + bs - 1) // bs for c in ctx))
     nb = sum((c + bs - 1) // bs for c in ctx) + 5
@@ -175,13 +179,14 @@ def test_scale_override():
     rig.close()
 
 
-def _full_size(cfg, sample_requests, rep=0):
+def _full_size(cfg, sample_requests, rep=0, part_tokens=None):
     """Physical-first: pools filled iid on the device, block table random over
     the pool; a seeded sample of running requests is un-paged for the oracle."""
     wl = W.workload(cfg, rep)
     geom = wl.geom
     seed = W.config_seed(cfg, rep)
-    rig = Rig(geom, max_batch=wl.batch, part_tokens=wl.part_tokens, poison=False)
+    rig = Rig(geom, max_batch=wl.batch, poison=False,
+              part_tokens=wl.part_tokens if part_tokens is None else part_tokens)
     gen = torch.Generator(device=rig.dev).manual_seed(seed)
     rig.k_pool.normal_(generator=gen)
     rig.v_pool.normal_(generator=gen)
@@ -211,9 +216,12 @@ def _full_size(cfg, sample_requests, rep=0):
     return worst
 
 
-@pytest.mark.parametrize("cfg,sample", [(1, 6), (2, 8), (3, 2)])
-def test_full_size_sampled_parity(cfg, sample):
-    worst = _full_size(cfg, sample)
+@pytest.mark.parametrize("cfg,sample,part", [(1, 6, None), (2, 8, None), (3, 2, None), (3, 2, 0),
+                                             (1, 4, 512), (2, 6, 1024)])
+def test_full_size_sampled_parity(cfg, sample, part):
+    """Configurations 1-3 at full size in the bench's launch configuration
+    (part=None: the workload's own setting) and in the other decomposition."""
+    worst = _full_size(cfg, sample, part_tokens=part)
     assert worst <= 2e-2, worst
 
 
