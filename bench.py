@@ -245,12 +245,12 @@ class Job:
         C = int(self.wl.ctx_lens[r])
         ids = torch.as_tensor(self.tables[b][r, :g.blocks_for(C)].astype(np.int64), device=self.dev)
 
-        def logical(pool):
-            x = pool[ids, layer].cpu()                          # [nb][Hkv][bs][D]
+        def logical(pool, index_map):
+            x = pool[ids, layer].cpu()                          # [nb][Hkv][tile]
             x = x.view(torch.int16).numpy().view(np.uint16) if x.dtype == torch.bfloat16 else x.numpy()
-            return np.ascontiguousarray(
-                np.swapaxes(x, 1, 2).reshape(-1, g.num_kv_heads, g.head_dim)[:C])
-        return logical(self.k_pool), logical(self.v_pool)
+            return self.W.tiles_to_logical(x, index_map, C)
+        k_index, v_index = g.tile_index_maps()
+        return logical(self.k_pool, k_index), logical(self.v_pool, v_index)
 
 
 def cpu_baseline(job):

@@ -29,14 +29,26 @@
  *   - A context is not thread-safe; calls on it must be serialised.
  *
  * KV pool layout (part of the ABI, so swap images can be checked byte by byte)
- *   Keys and values live in two pools of identical shape
- *       pool[num_blocks][num_layers][num_kv_heads][block_size][head_dim]
- *   of `dtype` elements, C order.  Cached position t of a request is slot
+ *   Keys and values live in two pools of identical size
+ *       pool[num_blocks][num_layers][num_kv_heads][tile]
+ *   where a tile holds the block_size x head_dim elements of `dtype` of one
+ *   (block, layer, kv head), C order.  Cached position t of a request is slot
  *   t % block_size of physical block block_table[request][t / block_size].
  *   A block id names that block in every layer, keys and values.
  *   Host image of one swapped block = its key-pool bytes (all layers)
  *   followed by its value-pool bytes; images follow each other in the order
  *   of the id list.
+ *   Inside a tile, element (slot s, dim d) sits at element offset
+ *     LAMPS_LAYOUT_PLAIN (fp32, and bf16 with H == H_kv), keys and values:
+ *         s * head_dim + d
+ *     LAMPS_LAYOUT_TILED (bf16 with H > H_kv): the tile is block_size/16
+ *     sub-tiles of 16 slots; with u = s / 16, t = s % 16 and sub-tile base
+ *     u * 16 * head_dim,
+ *         keys:    base + ((d / 8) * 16 + t) * 8 + d % 8
+ *         values:  base + ((((d / 32) * 4 + t / 4) * 16 + d % 16) * 2 + (d % 32) / 16) * 4 + t % 4
+ *     (16-byte runs that a wavefront loads coalesced and feeds to the matrix
+ *     cores unchanged: 8 dims of one key; 4 consecutive slots of two dims of a
+ *     value).  lamps_kv_layout() tells which one a configuration uses.
  */
 #ifndef LAMPS_H
 #define LAMPS_H
@@ -51,6 +63,7 @@ extern "C" {
 typedef struct lamps_ctx lamps_ctx; /* opaque, library-owned */
 
 typedef enum { LAMPS_F32 = 0, LAMPS_BF16 = 1 } lamps_dtype;
+typedef enum { LAMPS_LAYOUT_PLAIN = 0, LAMPS_LAYOUT_TILED = 1 } lamps_layout;
 
 typedef enum {
     LAMPS_OK = 0,
@@ -74,8 +87,10 @@ typedef struct {
     int32_t max_batch;          /* largest `batch` passed to lamps_decode_attn       */
     int32_t dtype;              /* lamps_dtype of q, the pools and out               */
     float softmax_scale;        /* 0 => 1/sqrt(head_dim), the Section 2.2 equation   */
-    int32_t part_tokens;        /* tokens per split partition, multiple of
-                                   block_size; 0 => library default (1024)           */
+    int32_t part_tokens;        /* 0 => balanced shares (default: every workgroup gets
+                                   an equal part of all cached tokens); > 0 => fixed
+                                   partitions of this many tokens, multiple of
+                                   block_size                                        */
     int64_t staging_bytes;      /* device staging per swap direction; 0 => default   */
 } lamps_config;
 
@@ -84,6 +99,9 @@ typedef struct {
 /* M of equations (1)-(3): bytes of KV cache per token over all layers,
  * 2 * L * H_kv * d_h * sizeof(dtype) (Section 2.2.1). */
 size_t lamps_kv_bytes_per_token(const lamps_config *cfg);
+/* lamps_layout of the tiles of both pools for this configuration (see the
+ * layout section above), or LAMPS_ERR_INVALID. */
+int lamps_kv_layout(const lamps_config *cfg);
 /* Bytes of one block's host image: keys + values, all layers. */
 size_t lamps_block_bytes(const lamps_config *cfg);
 /* Bytes the caller must allocate for EACH of the two pools. */

@@ -90,8 +90,10 @@ BF16_NAN = np.uint16(0x7FC0)
 # ---------------------------------------------------------------- geometry
 @dataclass(frozen=True)
 class Geometry:
-    """Shape of the KV pool.  Pool layout (keys and values in separate pools of
-    the same shape): pool[block][layer][kv_head][slot][d]."""
+    """Shape of the KV pool.  Keys and values live in separate pools of the same
+    shape, pool[block][layer][kv_head][tile]; a tile holds the block_size x
+    head_dim elements of one (block, layer, kv head) in the order given by
+    `tile_index_maps` (the library's documented layout)."""
     num_layers: int
     num_q_heads: int
     num_kv_heads: int
@@ -110,14 +112,23 @@ class Geometry:
         return np.float32 if self.dtype == "f32" else np.uint16
 
     @property
+    def tile_elems(self):
+        return self.block_size * self.head_dim
+
+    @property
     def pool_shape(self):
-        return (self.num_blocks, self.num_layers, self.num_kv_heads, self.block_size, self.head_dim)
+        return (self.num_blocks, self.num_layers, self.num_kv_heads, self.tile_elems)
+
+    @property
+    def kv_layout(self):
+        """"tiled" for bf16 with grouped query heads, else "plain"."""
+        grouped = self.num_q_heads // self.num_kv_heads >= 2
+        return "tiled" if self.dtype == "bf16" and grouped else "plain"
 
     @property
     def block_half_bytes(self):
         """Bytes of one block in ONE pool (all layers)."""
-        return (self.num_layers * self.num_kv_heads * self.block_size * self.head_dim
-                * self.elem_bytes)
+        return self.num_layers * self.num_kv_heads * self.tile_elems * self.elem_bytes
 
     @property
     def token_bytes_per_layer(self):
@@ -126,6 +137,20 @@ class Geometry:
 
     def blocks_for(self, ctx_len):
         return (int(ctx_len) + self.block_size - 1) // self.block_size
+
+    def tile_index_maps(self):
+        """(k_index, v_index): int arrays [block_size][head_dim] giving the element
+        offset of (slot, dim) inside a tile of the key pool / the value pool."""
+        s = np.arange(self.block_size)[:, None]
+        d = np.arange(self.head_dim)[None, :]
+        if self.kv_layout == "plain":
+            idx = s * self.head_dim + d
+            return idx, idx
+        base = (s // 16) * 16 * self.head_dim
+        t = s % 16
+        k = base + ((d // 8) * 16 + t) * 8 + d % 8
+        v = base + ((((d // 32) * 4 + t // 4) * 16 + d % 16) * 2 + (d % 32) // 16) * 4 + t % 4
+        return k, v
 
 
 def deal_block_table(perm, ctx_lens, geom, start=0):
@@ -145,26 +170,33 @@ def deal_block_table(perm, ctx_lens, geom, start=0):
     return table, pos - start
 
 
-def page(pool, layer, table_row, seq):
-    """Scatter a logical sequence seq[C][H_kv][D] into pool (numpy view of shape
-    Geometry.pool_shape) through one block-table row.  Tail slots of the last
-    block are left as they are."""
+def page(pool, layer, table_row, seq, index_map):
+    """Scatter a logical sequence seq[C][H_kv][D] into pool (numpy array of shape
+    Geometry.pool_shape) through one block-table row; index_map is the pool's
+    entry of Geometry.tile_index_maps().  Slots past C are left as they are."""
     C = seq.shape[0]
-    bs = pool.shape[3]
+    bs = index_map.shape[0]
     for j in range((C + bs - 1) // bs):
         n = min(bs, C - j * bs)
-        # pool[block, layer] is [H_kv][slot][D]; seq chunk is [slot][H_kv][D]
-        pool[table_row[j], layer, :, :n, :] = np.swapaxes(seq[j * bs:j * bs + n], 0, 1)
+        # pool[block, layer] is [H_kv][tile]; seq chunk is [slot][H_kv][D]
+        pool[table_row[j], layer][:, index_map[:n].ravel()] = \
+            np.swapaxes(seq[j * bs:j * bs + n], 0, 1).reshape(seq.shape[1], -1)
 
 
-def unpage(pool, layer, table_row, C):
+def tiles_to_logical(tiles, index_map, C):
+    """tiles[nb][H_kv][tile] (the blocks of one request, in logical order) ->
+    the first C cached positions as [C][H_kv][D]."""
+    bs, D = index_map.shape
+    x = tiles[..., index_map.ravel()]                       # [nb][H_kv][bs * D] in (slot, dim) order
+    x = x.reshape(tiles.shape[0], tiles.shape[1], bs, D)
+    return np.ascontiguousarray(np.swapaxes(x, 1, 2).reshape(-1, tiles.shape[1], D)[:C])
+
+
+def unpage(pool, layer, table_row, C, index_map):
     """Gather the first C cached positions of one request back into [C][H_kv][D]."""
-    bs = pool.shape[3]
-    out = np.empty((C, pool.shape[2], pool.shape[4]), dtype=pool.dtype)
-    for j in range((C + bs - 1) // bs):
-        n = min(bs, C - j * bs)
-        out[j * bs:j * bs + n] = np.swapaxes(pool[table_row[j], layer, :, :n, :], 0, 1)
-    return out
+    nb = (C + index_map.shape[0] - 1) // index_map.shape[0]
+    ids = np.asarray(table_row[:nb], dtype=np.int64)
+    return tiles_to_logical(pool[ids, layer], index_map, C)
 
 
 # ---------------------------------------------------------------- context lengths

@@ -8,6 +8,7 @@ import ctypes
 import os
 
 LAMPS_F32, LAMPS_BF16 = 0, 1
+LAMPS_LAYOUT_PLAIN, LAMPS_LAYOUT_TILED = 0, 1
 
 STATUS = {0: "LAMPS_OK", -1: "LAMPS_ERR_INVALID", -2: "LAMPS_ERR_RANGE", -3: "LAMPS_ERR_DUP",
           -4: "LAMPS_ERR_DOUBLE_FREE", -5: "LAMPS_ERR_BUSY", -6: "LAMPS_ERR_NOMEM",
@@ -59,6 +60,8 @@ def load_library():
                  "lamps_workspace_bytes"):
         getattr(lib, name).restype = ctypes.c_size_t
         getattr(lib, name).argtypes = [cfgp]
+    lib.lamps_kv_layout.restype = ctypes.c_int
+    lib.lamps_kv_layout.argtypes = [cfgp]
     sig = {
         "lamps_create": [cfgp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)],
         "lamps_destroy": [vp],
@@ -101,6 +104,10 @@ def _ids(block_ids):
 
 def lamps_kv_bytes_per_token(cfg):
     return load_library().lamps_kv_bytes_per_token(ctypes.byref(cfg))
+
+
+def lamps_kv_layout(cfg):
+    return load_library().lamps_kv_layout(ctypes.byref(cfg))
 
 
 def lamps_block_bytes(cfg):

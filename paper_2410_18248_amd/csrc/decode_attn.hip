@@ -6,7 +6,8 @@
 // block table (paged attention, Section 7).
 //
 // Work decomposition.  The unit of work is a chunk of CT tokens of one
-// (request, kv head).  Two schemes share the same inner loop:
+// (request, kv head, pass over GH query heads of the group).  Two schemes share
+// the same inner loops:
 //   balanced (default): all chunks of all running requests form one flat
 //     sequence; a fixed number of workgroups (one full occupancy wave of the
 //     chip) each take an equal contiguous share of it, so every workgroup ends
@@ -16,22 +17,28 @@
 //     partial ends go to per-workgroup slots that a small second kernel merges.
 //   fixed partitions (part_tokens > 0): the context is cut every part_tokens
 //     tokens, one workgroup per (partition, request, kv head) in a dense grid.
-//
-// Mapping to the hardware.  The path is a stream over K and V (every byte is
-// used once: ~1 flop/byte), so it is HBM-bound and runs on the vector ALUs, not
-// on MFMA.  A (block, layer, kv head) tile is block_size*head_dim contiguous
-// elements; a wavefront reads it with fully coalesced, non-temporal 16-byte-
-// per-lane loads: LPT = head_dim*sizeof/16 lanes cover one token, 64/LPT
-// tokens per load.  Each lane keeps its 16-byte slice of q for all heads of
-// the kv group in registers, so the G query heads of a group share every K/V
-// byte that is loaded.  The dot product is finished with DPP adds inside the
-// LPT lanes (no LDS).  Each group of LPT lanes ("row") carries its own running
-// max / sum / accumulator over the tokens it sees, so there is no cross-lane
-// traffic in the main loop beyond the dot-product reduction; rows are merged
-// by shuffles and the four waves through LDS once per (request, head) range.
 // Partitions are merged by a separate launch on purpose: a kernel boundary
 // makes the partials visible across the eight XCDs' L2s once, whereas a
 // device-scope fence per workgroup writes back and invalidates an L2 each time.
+//
+// Inner loops.  The path is a stream over K and V: every byte is used once, by
+// the G query heads of its group.
+//   G == 1 (and all fp32): ~1 flop per byte, a matrix-vector product.  Vector
+//     ALUs, no MFMA: a tile is block_size*head_dim contiguous elements read
+//     with coalesced non-temporal 16-byte-per-lane loads, LPT = head_dim*size/16
+//     lanes per token; q slices stay in registers; the dot product ends with
+//     DPP adds inside the LPT lanes; each group of LPT lanes ("row") carries
+//     its own running max / sum / accumulator, rows are merged by shuffles.
+//   bf16 with G >= 2: the group's heads make q a G x d_h matrix and both
+//     products real (skinny) contractions, and on the vector ALUs their cost
+//     grows with G until it co-limits with HBM.  They go to MFMA instead
+//     (16x16x32 for K q^T, 16x16x16 for V^T p^T, up to 16 heads per pass), and
+//     the pools use the tiled layout of lamps.h so that a coalesced 16-byte
+//     load IS an MFMA operand: no LDS staging, no shuffles.  The weights p are
+//     fed as a bf16 pair (high part + remainder), which keeps fp32-grade
+//     weights at the price of a second, nearly free, MFMA.
+// In both, the four waves of a workgroup take chunks round-robin and are merged
+// through LDS once per range.
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
@@ -41,17 +48,18 @@ namespace {
 
 constexpr int kWaves = 4;               // wavefronts per workgroup
 constexpr int kThreads = 64 * kWaves;
-// wave-wide 16-byte loads per chunk and pool; a chunk (loads * tokens per load)
-// must fit in the smallest block (16 tokens)
+// wave-wide 16-byte loads per half-chunk and pool; a half-chunk (loads * tokens
+// per load) must fit in the smallest block (16 tokens)
 constexpr int loads_per_chunk(int lpt) { return lpt == 8 ? 2 : 4; }
-#ifndef LAMPS_HALVES
-#define LAMPS_HALVES 2
-#endif
-constexpr int kHalves = LAMPS_HALVES;   // half-chunks in flight per wave for 1- and 2-head groups
+constexpr int kHalves = 2;              // half-chunks a wave keeps in flight on the 1-2 head paths
 constexpr float kLowest = -3.0e38f;     // finite stand-in for "no score seen yet"
 constexpr int kMaxShares = 4096;        // most workgroups the balanced scheme ever launches
+constexpr int kMergeList = 64;          // pieces whose slots are resolved per pass of the balanced merge
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 // K and V are read exactly once per launch: a non-temporal 16-byte load keeps
@@ -105,6 +113,15 @@ __device__ __forceinline__ void store_out(void *out, size_t i, float o)
         static_cast<float *>(out)[i] = o;
 }
 
+__device__ __forceinline__ void store_partial(float *pp, int D, int d, float M, float L, float A)
+{
+    pp[d] = A;
+    if (d == 0) {
+        pp[D] = M;
+        pp[D + 1] = L;
+    }
+}
+
 // Partial dot product of a lane's 16 bytes of q and K.
 template <bool BF16>
 __device__ __forceinline__ float dot16(const uint4 &q, const uint4 &k)
@@ -156,186 +173,20 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float (&acc)[VEC
     m = mn;
 }
 
-
-// Compile-time shape of one instantiation.
-template <bool BF16, int LPT, int GH, int NH>
-struct Shape {
-    static constexpr int VEC = BF16 ? 8 : 4;          // elements per 16-byte load
-    static constexpr int D = LPT * VEC;
-    static constexpr int ES = BF16 ? 2 : 4;           // element bytes
-    static constexpr int TPW = 64 / LPT;              // tokens per wave-wide load
-    static constexpr int kLoads = loads_per_chunk(LPT);
-    static constexpr int HT = TPW * kLoads;           // tokens per half-chunk (<= 16 <= block_size)
-    static constexpr int NL = NH * kLoads;            // wave-wide loads per chunk and pool
-    static constexpr int CT = HT * NH;                // tokens per chunk
+// LDS for the merge of the four waves of a workgroup: per wave and head the
+// running max (log2 domain), the weight sum and the weighted sum of V.
+template <int HEADS, int D>
+struct WaveMerge {
+    float acc[kWaves][HEADS][D];
+    float m[kWaves][HEADS], l[kWaves][HEADS];
 };
 
-template <int GH, int D>
-struct WaveMerge {                                    // LDS for the cross-wave merge
-    float acc[kWaves][GH][D];
-    float m[kWaves][GH], l[kWaves][GH];
-};
-
-// Reduces cached positions [t_begin, t_end) of request r (kv head g, query heads
-// h0 .. h0+GH-1) with all four waves of the workgroup, then calls
-// sink(h, d, M, L, A) once for every (head, dim): M = running max (log2 domain),
-// L = sum of weights, A = weighted sum of V[:, d].  t_begin is a multiple of CT.
-// Contains two workgroup barriers; must be called by all threads.
-template <bool BF16, int LPT, int GH, int NH, typename Sink>
-__device__ __forceinline__ void reduce_range(const DecodeArgs &a, int r, int g, int h0, int t_begin,
-                                             int t_end, WaveMerge<GH, LPT *(BF16 ? 8 : 4)> &sm,
-                                             Sink sink)
+// Last step of both reducers: combines the four waves' states (already written
+// to sm by the caller, behind a barrier) and hands every (head, dim) to sink.
+template <int HEADS, int D, typename Sink>
+__device__ __forceinline__ void combine_waves(const WaveMerge<HEADS, D> &sm, int heads, Sink sink)
 {
-    using S = Shape<BF16, LPT, GH, NH>;
-    constexpr int VEC = S::VEC, D = S::D, TPW = S::TPW, kLoads = S::kLoads, HT = S::HT, NL = S::NL,
-                  CT = S::CT;
-    const int lane = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int row = lane / LPT;                // which of the TPW tokens of a load
-    const int col = lane % LPT;                // which 16-byte slice of the head vector
-
-    // q slices of the GH heads, kept in registers for the whole range
-    uint4 qv[GH];
-#pragma unroll
-    for (int h = 0; h < GH; ++h)
-        qv[h] = *reinterpret_cast<const uint4 *>(
-            static_cast<const char *>(a.q) +
-            (((size_t)r * a.num_q_heads + h0 + h) * D + col * VEC) * S::ES);
-
-    float m[GH], l[GH], acc[GH][VEC];
-#pragma unroll
-    for (int h = 0; h < GH; ++h) {
-        m[h] = kLowest;
-        l[h] = 0.0f;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[h][e] = 0.0f;
-    }
-
-    const int n_chunks = (t_end - t_begin + CT - 1) / CT;
-    const int32_t *table = a.block_table + (size_t)r * a.max_blocks;
-    const size_t tile_bytes = (size_t)a.block_size * D * S::ES;
-    const size_t block_stride = (size_t)a.num_layers * a.num_kv_heads * tile_bytes;
-    const size_t head_off = ((size_t)a.layer * a.num_kv_heads + g) * tile_bytes;
-    const char *kp = static_cast<const char *>(a.k_pool) + head_off + lane * 16;
-    const char *vp = static_cast<const char *>(a.v_pool) + head_off + lane * 16;
-
-    // A chunk is NH half-chunks of HT tokens; a half-chunk never straddles a
-    // block (HT <= 16 <= block_size), so it needs one block-table entry.  All
-    // NH * kLoads K loads and as many V loads of a chunk are issued before any
-    // is consumed.  Wave w takes chunks w, w + 4, ...
-    int ch = w;
-    int pb[NH], pbn[NH];
-#pragma unroll
-    for (int f = 0; f < NH; ++f) {
-        const int th = t_begin + ch * CT + f * HT;
-        pb[f] = (ch < n_chunks && th < t_end) ? table[th >> a.log2_block_size] : -1;
-    }
-    while (ch < n_chunks) {
-        const int t0 = t_begin + ch * CT;
-        uint4 kx[NL], vx[NL];
-#pragma unroll
-        for (int f = 0; f < NH; ++f) {
-            if (pb[f] >= 0) {                  // wave-uniform: half-chunks past the context are skipped
-                const size_t off = (size_t)pb[f] * block_stride +
-                                   (size_t)((t0 + f * HT) & (a.block_size - 1)) * D * S::ES;
-#pragma unroll
-                for (int i = 0; i < kLoads; ++i) kx[f * kLoads + i] = load_stream16(kp + off + i * 1024);
-#pragma unroll
-                for (int i = 0; i < kLoads; ++i) vx[f * kLoads + i] = load_stream16(vp + off + i * 1024);
-            } else {
-#pragma unroll
-                for (int i = 0; i < kLoads; ++i) {
-                    kx[f * kLoads + i] = make_uint4(0, 0, 0, 0);
-                    vx[f * kLoads + i] = make_uint4(0, 0, 0, 0);
-                }
-            }
-        }
-
-        // physical blocks of this wave's next chunk, fetched while the tiles arrive
-        const int chn = ch + kWaves;
-#pragma unroll
-        for (int f = 0; f < NH; ++f) {
-            const int th = t_begin + chn * CT + f * HT;
-            pbn[f] = (chn < n_chunks && th < t_end) ? table[th >> a.log2_block_size] : -1;
-        }
-
-        float s[GH][NL];
-#pragma unroll
-        for (int h = 0; h < GH; ++h)
-#pragma unroll
-            for (int i = 0; i < NL; ++i)
-                s[h][i] = sum_token_lanes<LPT>(dot16<BF16>(qv[h], kx[i])) * a.scale_log2e;
-
-        if (t0 + CT > t_end) {                 // ragged tail: slots at or past ctx_len never count
-#pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                if (t0 + i * TPW + row >= t_end) {
-#pragma unroll
-                    for (int h = 0; h < GH; ++h) s[h][i] = -INFINITY;
-                    vx[i] = make_uint4(0, 0, 0, 0);
-                }
-            }
-        }
-
-#pragma unroll
-        for (int h = 0; h < GH; ++h) {
-            float mn = m[h];
-#pragma unroll
-            for (int i = 0; i < NL; ++i) mn = fmaxf(mn, s[h][i]);
-            const float sc = fast_exp2(m[h] - mn);
-            float ps = 0.0f;
-#pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                s[h][i] = fast_exp2(s[h][i] - mn);   // now the weight p
-                ps += s[h][i];
-            }
-            l[h] = l[h] * sc + ps;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[h][e] *= sc;
-            m[h] = mn;
-        }
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            float vf[VEC];
-            unpack<BF16, VEC>(vx[i], vf);
-#pragma unroll
-            for (int h = 0; h < GH; ++h)
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[h][e] = fmaf(s[h][i], vf[e], acc[h][e]);
-        }
-        ch = chn;
-#pragma unroll
-        for (int f = 0; f < NH; ++f) pb[f] = pbn[f];
-    }
-
-    // rows of a wave -> one state per wave
-#pragma unroll
-    for (int h = 0; h < GH; ++h) {
-#pragma unroll
-        for (int stride = LPT; stride < 64; stride *= 2) {
-            float mo = __shfl_xor(m[h], stride), lo = __shfl_xor(l[h], stride);
-            float ao[VEC];
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) ao[e] = __shfl_xor(acc[h][e], stride);
-            merge_state<VEC>(m[h], l[h], acc[h], mo, lo, ao);
-        }
-    }
-
-    // waves -> one state per workgroup, through LDS
-    __syncthreads();                           // the previous range's readers are done with sm
-    if (row == 0) {
-#pragma unroll
-        for (int h = 0; h < GH; ++h) {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) sm.acc[w][h][col * VEC + e] = acc[h][e];
-            if (col == 0) {
-                sm.m[w][h] = m[h];
-                sm.l[w][h] = l[h];
-            }
-        }
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < GH * D; idx += kThreads) {
+    for (int idx = threadIdx.x; idx < heads * D; idx += kThreads) {
         const int h = idx / D, d = idx % D;
         float M = sm.m[0][h];
 #pragma unroll
@@ -351,34 +202,356 @@ __device__ __forceinline__ void reduce_range(const DecodeArgs &a, int r, int g, 
     }
 }
 
-__device__ __forceinline__ void store_partial(float *pp, int D, int d, float M, float L, float A)
-{
-    pp[d] = A;
-    if (d == 0) {
-        pp[D] = M;
-        pp[D + 1] = L;
+// ---------------------------------------------------------------- vector-ALU reducer
+
+// Plain pool layout, GH query heads of the group per pass (GH == 1 for bf16).
+template <bool BF16, int LPT, int GH, int NH>
+struct ValuReducer {
+    static constexpr bool kBF16 = BF16;
+    static constexpr int VEC = BF16 ? 8 : 4;          // elements per 16-byte load
+    static constexpr int D = LPT * VEC;
+    static constexpr int ES = BF16 ? 2 : 4;           // element bytes
+    static constexpr int TPW = 64 / LPT;              // tokens per wave-wide load
+    static constexpr int kLoads = loads_per_chunk(LPT);
+    static constexpr int HT = TPW * kLoads;           // tokens per half-chunk (<= 16 <= block_size)
+    static constexpr int NL = NH * kLoads;            // wave-wide loads per chunk and pool
+    static constexpr int CT = HT * NH;                // tokens per chunk
+    static constexpr int HEADS = GH;                  // heads per pass (LDS is sized for it)
+    using Smem = WaveMerge<HEADS, D>;
+
+    // Reduces cached positions [t_begin, t_end) of request r (kv head g, query
+    // heads h0 .. h0+GH-1) with all four waves of the workgroup, then calls
+    // sink(h, d, M, L, A) once for every (head, dim): M = running max (log2
+    // domain), L = sum of weights, A = weighted sum of V[:, d].  t_begin is a
+    // multiple of CT.  Contains two workgroup barriers: all threads call it.
+    template <typename Sink>
+    static __device__ __forceinline__ void run(const DecodeArgs &a, int r, int g, int h0, int,
+                                               int t_begin, int t_end, Smem &sm, Sink sink)
+    {
+        const int lane = threadIdx.x & 63;
+        const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int row = lane / LPT;                // which of the TPW tokens of a load
+        const int col = lane % LPT;                // which 16-byte slice of the head vector
+
+        // q slices of the GH heads, kept in registers for the whole range
+        uint4 qv[GH];
+#pragma unroll
+        for (int h = 0; h < GH; ++h)
+            qv[h] = *reinterpret_cast<const uint4 *>(
+                static_cast<const char *>(a.q) +
+                (((size_t)r * a.num_q_heads + h0 + h) * D + col * VEC) * ES);
+
+        float m[GH], l[GH], acc[GH][VEC];
+#pragma unroll
+        for (int h = 0; h < GH; ++h) {
+            m[h] = kLowest;
+            l[h] = 0.0f;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[h][e] = 0.0f;
+        }
+
+        const int n_chunks = (t_end - t_begin + CT - 1) / CT;
+        const int32_t *table = a.block_table + (size_t)r * a.max_blocks;
+        const size_t tile_bytes = (size_t)a.block_size * D * ES;
+        const size_t block_stride = (size_t)a.num_layers * a.num_kv_heads * tile_bytes;
+        const size_t head_off = ((size_t)a.layer * a.num_kv_heads + g) * tile_bytes;
+        const char *kp = static_cast<const char *>(a.k_pool) + head_off + lane * 16;
+        const char *vp = static_cast<const char *>(a.v_pool) + head_off + lane * 16;
+
+        // A chunk is NH half-chunks of HT tokens; a half-chunk never straddles a
+        // block (HT <= 16 <= block_size), so it needs one block-table entry.  All
+        // NH * kLoads K loads and as many V loads of a chunk are issued before
+        // any is consumed.  Wave w takes chunks w, w + 4, ...
+        int ch = w;
+        int pb[NH], pbn[NH];
+#pragma unroll
+        for (int f = 0; f < NH; ++f) {
+            const int th = t_begin + ch * CT + f * HT;
+            pb[f] = (ch < n_chunks && th < t_end) ? table[th >> a.log2_block_size] : -1;
+        }
+        while (ch < n_chunks) {
+            const int t0 = t_begin + ch * CT;
+            uint4 kx[NL], vx[NL];
+#pragma unroll
+            for (int f = 0; f < NH; ++f) {
+                if (pb[f] >= 0) {              // wave-uniform: half-chunks past the context are skipped
+                    const size_t off = (size_t)pb[f] * block_stride +
+                                       (size_t)((t0 + f * HT) & (a.block_size - 1)) * D * ES;
+#pragma unroll
+                    for (int i = 0; i < kLoads; ++i)
+                        kx[f * kLoads + i] = load_stream16(kp + off + i * 1024);
+#pragma unroll
+                    for (int i = 0; i < kLoads; ++i)
+                        vx[f * kLoads + i] = load_stream16(vp + off + i * 1024);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < kLoads; ++i) {
+                        kx[f * kLoads + i] = make_uint4(0, 0, 0, 0);
+                        vx[f * kLoads + i] = make_uint4(0, 0, 0, 0);
+                    }
+                }
+            }
+
+            // physical blocks of this wave's next chunk, fetched while the tiles arrive
+            const int chn = ch + kWaves;
+#pragma unroll
+            for (int f = 0; f < NH; ++f) {
+                const int th = t_begin + chn * CT + f * HT;
+                pbn[f] = (chn < n_chunks && th < t_end) ? table[th >> a.log2_block_size] : -1;
+            }
+
+            float s[GH][NL];
+#pragma unroll
+            for (int h = 0; h < GH; ++h)
+#pragma unroll
+                for (int i = 0; i < NL; ++i)
+                    s[h][i] = sum_token_lanes<LPT>(dot16<BF16>(qv[h], kx[i])) * a.scale_log2e;
+
+            if (t0 + CT > t_end) {             // ragged tail: slots at or past ctx_len never count
+#pragma unroll
+                for (int i = 0; i < NL; ++i) {
+                    if (t0 + i * TPW + row >= t_end) {
+#pragma unroll
+                        for (int h = 0; h < GH; ++h) s[h][i] = -INFINITY;
+                        vx[i] = make_uint4(0, 0, 0, 0);
+                    }
+                }
+            }
+
+#pragma unroll
+            for (int h = 0; h < GH; ++h) {
+                float mn = m[h];
+#pragma unroll
+                for (int i = 0; i < NL; ++i) mn = fmaxf(mn, s[h][i]);
+                const float sc = fast_exp2(m[h] - mn);
+                float ps = 0.0f;
+#pragma unroll
+                for (int i = 0; i < NL; ++i) {
+                    s[h][i] = fast_exp2(s[h][i] - mn);   // now the weight p
+                    ps += s[h][i];
+                }
+                l[h] = l[h] * sc + ps;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[h][e] *= sc;
+                m[h] = mn;
+            }
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                float vf[VEC];
+                unpack<BF16, VEC>(vx[i], vf);
+#pragma unroll
+                for (int h = 0; h < GH; ++h)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) acc[h][e] = fmaf(s[h][i], vf[e], acc[h][e]);
+            }
+            ch = chn;
+#pragma unroll
+            for (int f = 0; f < NH; ++f) pb[f] = pbn[f];
+        }
+
+        // rows of a wave -> one state per wave
+#pragma unroll
+        for (int h = 0; h < GH; ++h) {
+#pragma unroll
+            for (int stride = LPT; stride < 64; stride *= 2) {
+                float mo = __shfl_xor(m[h], stride), lo = __shfl_xor(l[h], stride);
+                float ao[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) ao[e] = __shfl_xor(acc[h][e], stride);
+                merge_state<VEC>(m[h], l[h], acc[h], mo, lo, ao);
+            }
+        }
+
+        // waves -> one state per workgroup, through LDS
+        __syncthreads();                       // the previous range's readers are done with sm
+        if (row == 0) {
+#pragma unroll
+            for (int h = 0; h < GH; ++h) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) sm.acc[w][h][col * VEC + e] = acc[h][e];
+                if (col == 0) {
+                    sm.m[w][h] = m[h];
+                    sm.l[w][h] = l[h];
+                }
+            }
+        }
+        __syncthreads();
+        combine_waves<HEADS, D>(sm, GH, sink);
     }
-}
+};
+
+// ---------------------------------------------------------------- MFMA reducer
+
+// bf16, tiled pool layout, up to 16 query heads of one kv group per pass.
+// Per 16-token sub-tile (a chunk): scores^T[token][head] = K . q^T with D/32
+// 16x16x32 MFMAs (A = a coalesced K load as it arrives, B = q slices held in
+// registers); the result leaves each lane with 4 consecutive tokens of head
+// lane%16, which after the softmax step is, converted to bf16, already the B
+// operand p^T[token][head] of the 16x16x16 MFMAs that accumulate
+// out^T[dim][head] += V^T . p^T (A = a coalesced V load).  So every statistic of
+// head j lives in the lanes with lane%16 == j, and the only cross-lane step per
+// sub-tile is the max over the four token groups (two shuffles).
+template <int DIM, int HEADS_PAD>
+struct MfmaReducer {
+    static constexpr bool kBF16 = true;
+    static constexpr int D = DIM;
+    static constexpr int CT = 16;                     // tokens per chunk = one sub-tile
+    static constexpr int NK = D / 32;                 // K loads = score MFMAs per sub-tile
+    static constexpr int NS = D / 32;                 // V loads per sub-tile (two 16-dim slabs each)
+    static constexpr int HEADS = HEADS_PAD;
+    using Smem = WaveMerge<HEADS, D>;
+
+    template <typename Sink>
+    static __device__ __forceinline__ void run(const DecodeArgs &a, int r, int g, int h0, int heads,
+                                               int t_begin, int t_end, Smem &sm, Sink sink)
+    {
+        const int lane = threadIdx.x & 63;
+        const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int j = lane & 15;                   // head (B / result column); dim in slab (V rows)
+        const int qd = lane >> 4;                  // token group of 4 (results) / k slice (operands)
+
+        // B operands of the score MFMAs: q[h0 + j][32 i + 8 qd .. + 8]; zero rows pad to 16 heads
+        bf16x8 qb[NK];
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            uint4 t = make_uint4(0, 0, 0, 0);
+            if (j < heads)
+                t = *reinterpret_cast<const uint4 *>(
+                    static_cast<const char *>(a.q) +
+                    (((size_t)r * a.num_q_heads + h0 + j) * D + 32 * i + 8 * qd) * 2);
+            qb[i] = __builtin_bit_cast(bf16x8, t);
+        }
+
+        float m = kLowest, l = 0.0f;               // m is the same in the 4 lanes of a head
+        f32x4 o[2 * NS];                           // out^T: dims 16 s + 4 qd + e, head j
+#pragma unroll
+        for (int s = 0; s < 2 * NS; ++s) o[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        const int n_chunks = (t_end - t_begin + CT - 1) / CT;
+        const int32_t *table = a.block_table + (size_t)r * a.max_blocks;
+        const size_t tile_bytes = (size_t)a.block_size * D * 2;
+        const size_t block_stride = (size_t)a.num_layers * a.num_kv_heads * tile_bytes;
+        const size_t head_off = ((size_t)a.layer * a.num_kv_heads + g) * tile_bytes;
+        const char *kp = static_cast<const char *>(a.k_pool) + head_off + lane * 16;
+        const char *vp = static_cast<const char *>(a.v_pool) + head_off + lane * 16;
+
+        int ch = w;
+        int pb = ch < n_chunks ? table[(t_begin + ch * CT) >> a.log2_block_size] : 0;
+        while (ch < n_chunks) {
+            const int t0 = t_begin + ch * CT;
+            // sub-tile (t0 % block_size) / 16 of the block's tile: 16 * D elements each
+            const size_t off = (size_t)pb * block_stride +
+                               (size_t)((t0 & (a.block_size - 1)) >> 4) * (16 * D * 2);
+            uint4 kx[NK], vx[NS];
+#pragma unroll
+            for (int i = 0; i < NK; ++i) kx[i] = load_stream16(kp + off + i * 1024);
+#pragma unroll
+            for (int i = 0; i < NS; ++i) vx[i] = load_stream16(vp + off + i * 1024);
+
+            const int chn = ch + kWaves;
+            const int pbn = chn < n_chunks ? table[(t_begin + chn * CT) >> a.log2_block_size] : 0;
+
+            f32x4 s = {0.f, 0.f, 0.f, 0.f};        // tokens t0 + 4 qd + e, head j
+#pragma unroll
+            for (int i = 0; i < NK; ++i)
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kx[i]), qb[i],
+                                                            s, 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] *= a.scale_log2e;
+
+            if (t0 + CT > t_end) {                 // ragged tail: slots at or past ctx_len never count
+                const int valid = min(4, max(0, t_end - (t0 + 4 * qd)));   // of this lane's 4 tokens
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (e >= valid) s[e] = -INFINITY;
+                // a V load holds tokens 4 qd + {0,1} in .x/.z and + {2,3} in .y/.w (16 bits each)
+                const uint32_t m01 = valid >= 2 ? 0xFFFFFFFFu : (valid == 1 ? 0x0000FFFFu : 0u);
+                const uint32_t m23 = valid >= 4 ? 0xFFFFFFFFu : (valid == 3 ? 0x0000FFFFu : 0u);
+#pragma unroll
+                for (int i = 0; i < NS; ++i) {
+                    vx[i].x &= m01; vx[i].z &= m01;
+                    vx[i].y &= m23; vx[i].w &= m23;
+                }
+            }
+
+            float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float mn = fmaxf(m, mx);
+            const float sc = fast_exp2(m - mn);
+            m = mn;
+            float p[4], ps = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                p[e] = fast_exp2(s[e] - mn);
+                ps += p[e];
+            }
+            l = l * sc + ps;
+            // p as a bf16 pair: high part and (exactly computed) remainder
+            union { s16x4 v; uint16_t u[4]; } ph, pl;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                ph.u[e] = to_bf16_rne(p[e]);
+                pl.u[e] = to_bf16_rne(p[e] - __uint_as_float((uint32_t)ph.u[e] << 16));
+            }
+#pragma unroll
+            for (int sidx = 0; sidx < 2 * NS; ++sidx) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[sidx][e] *= sc;
+            }
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                union { uint2 u; s16x4 v; } a0, a1;    // V^T rows: dim 32 i + j, and 32 i + 16 + j
+                a0.u = make_uint2(vx[i].x, vx[i].y);
+                a1.u = make_uint2(vx[i].z, vx[i].w);
+                o[2 * i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a0.v, ph.v, o[2 * i], 0, 0, 0);
+                o[2 * i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a0.v, pl.v, o[2 * i], 0, 0, 0);
+                o[2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1.v, ph.v, o[2 * i + 1], 0, 0, 0);
+                o[2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1.v, pl.v, o[2 * i + 1], 0, 0, 0);
+            }
+            ch = chn;
+            pb = pbn;
+        }
+
+        // the weight sum was kept per token group: add the four groups of a head
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+
+        __syncthreads();                           // the previous range's readers are done with sm
+        if (j < heads) {
+#pragma unroll
+            for (int sidx = 0; sidx < 2 * NS; ++sidx)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sm.acc[w][j][16 * sidx + 4 * qd + e] = o[sidx][e];
+            if (qd == 0) {
+                sm.m[w][j] = m;
+                sm.l[w][j] = l;
+            }
+        }
+        __syncthreads();
+        combine_waves<HEADS, D>(sm, heads, sink);
+    }
+};
 
 // ---------------------------------------------------------------- fixed partitions
 
-// One workgroup: one (partition, request, kv head / head chunk), decoded from a
-// 1-D grid.  GH query heads of the kv group share the K/V stream.
-template <bool BF16, int LPT, int GH, int NH>
+// One workgroup: one (partition, request, kv head / pass), decoded from a 1-D
+// grid.  The heads of one pass share the K/V stream.
+template <typename R>
 __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
 {
-    using S = Shape<BF16, LPT, GH, NH>;
-    constexpr int D = S::D;
-    __shared__ WaveMerge<GH, D> sm;
+    constexpr int D = R::D;
+    __shared__ typename R::Smem sm;
 
     // Workgroups are handed to the eight XCDs round-robin in launch order, so the
     // index that varies fastest must be one along which the work is even: the
-    // kv head (and head chunk), then the request, then the partition.  (With the
+    // kv head (and pass), then the request, then the partition.  (With the
     // partition fastest and eight partitions, all first partitions -- most of
     // the work -- would land on one XCD.)
     const int G = a.num_q_heads / a.num_kv_heads;
-    const int chunks_per_group = G / GH;
-    const int hc_count = a.num_kv_heads * chunks_per_group;
+    const int GH = a.heads_per_pass;
+    const int passes = G / GH;
+    const int hc_count = a.num_kv_heads * passes;
     const int hc = blockIdx.x % hc_count;
     const int r = (blockIdx.x / hc_count) % a.batch;
     const int part = blockIdx.x / (hc_count * a.batch);
@@ -389,17 +562,16 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     if (t_begin >= C && part != 0) return;     // partition 0 of an empty context writes zeros
     const int t_end = min(C, t_begin + a.part_tokens);
     const int n_parts = max(1, (C + a.part_tokens - 1) / a.part_tokens);
-    const int g = hc / chunks_per_group;
-    const int h0 = g * G + (hc % chunks_per_group) * GH;
+    const int g = hc / passes;
+    const int h0 = g * G + (hc % passes) * GH;
     const size_t rh0 = (size_t)r * a.num_q_heads + h0;
 
-    reduce_range<BF16, LPT, GH, NH>(a, r, g, h0, t_begin, t_end, sm,
-        [&](int h, int d, float M, float L, float A) {
-            if (n_parts == 1)
-                store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
-            else
-                store_partial(a.partials + ((rh0 + h) * a.max_parts + part) * (D + 2), D, d, M, L, A);
-        });
+    R::run(a, r, g, h0, GH, t_begin, t_end, sm, [&](int h, int d, float M, float L, float A) {
+        if (n_parts == 1)
+            store_out<R::kBF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
+        else
+            store_partial(a.partials + ((rh0 + h) * a.max_parts + part) * (D + 2), D, d, M, L, A);
+    });
 }
 
 // Merge of the partitions of one (request, query head), always in partition
@@ -429,25 +601,24 @@ __global__ void decode_merge(const DecodeArgs a)
 
 // ---------------------------------------------------------------- balanced shares
 
-// Chunks a running request contributes per (kv head, head chunk): an empty
-// context still gets one (empty) chunk so that its zero row is written.
+// Chunks a running request contributes per (kv head, pass): an empty context
+// still gets one (empty) chunk so that its zero row is written.
 __device__ __forceinline__ int chunks_of(int running, int C, int CT)
 {
     return running ? max(1, (C + CT - 1) / CT) : 0;
 }
 
 // gridDim.x workgroups, each an equal contiguous share of the flat chunk
-// sequence ordered (request, head chunk, chunk).  prefix[] (dynamic LDS,
+// sequence ordered (request, kv head / pass, chunk).  prefix[] (dynamic LDS,
 // batch + 1 ints) holds the running chunk count per request; every workgroup
 // computes it for itself from ctx_lens / running (a few hundred loads that hit
 // in L2), which costs less than a dependent launch.
-template <bool BF16, int LPT, int GH, int NH>
+template <typename R>
 __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
 {
-    using S = Shape<BF16, LPT, GH, NH>;
-    constexpr int D = S::D, CT = S::CT;
+    constexpr int D = R::D, CT = R::CT;
     extern __shared__ int prefix[];
-    __shared__ WaveMerge<GH, D> sm;
+    __shared__ typename R::Smem sm;
     __shared__ int wave_total[kWaves];
 
     const int B = a.batch;
@@ -479,8 +650,9 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     __syncthreads();
 
     const int G = a.num_q_heads / a.num_kv_heads;
-    const int chunks_per_group = G / GH;
-    const int HC = a.num_kv_heads * chunks_per_group;
+    const int GH = a.heads_per_pass;
+    const int passes = G / GH;
+    const int HC = a.num_kv_heads * passes;
     const long long total = (long long)HC * prefix[B];
     if (blockIdx.x == 0)                              // the merge kernel reads it back
         for (int i = tid; i <= B; i += kThreads) a.chunk_prefix[i] = prefix[i];
@@ -503,19 +675,19 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
         const int hc = (int)(rem / nr), c0 = (int)(rem % nr);
         const int len = (int)min((long long)(nr - c0), x_end - x);
         const int C = a.ctx_lens[r];
-        const int g = hc / chunks_per_group;
-        const int h0 = g * G + (hc % chunks_per_group) * GH;
+        const int g = hc / passes;
+        const int h0 = g * G + (hc % passes) * GH;
         const bool whole = (c0 == 0 && len == nr);
         // a share's first range goes to slot 0, a later partial one (its last) to slot 1
         float *slot = a.partials + ((size_t)blockIdx.x * 2 + (x == x_begin ? 0 : 1)) * GH * (D + 2);
         const size_t rh0 = (size_t)r * a.num_q_heads + h0;
-        reduce_range<BF16, LPT, GH, NH>(a, r, g, h0, c0 * CT, min(C, (c0 + len) * CT), sm,
-            [&](int h, int d, float M, float L, float A) {
-                if (whole)
-                    store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
-                else
-                    store_partial(slot + (size_t)h * (D + 2), D, d, M, L, A);
-            });
+        R::run(a, r, g, h0, GH, c0 * CT, min(C, (c0 + len) * CT), sm,
+               [&](int h, int d, float M, float L, float A) {
+                   if (whole)
+                       store_out<R::kBF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
+                   else
+                       store_partial(slot + (size_t)h * (D + 2), D, d, M, L, A);
+               });
         x += len;
         if (c0 + len == nr && hc == HC - 1) {         // request finished: next one with work
             ++r;
@@ -524,67 +696,76 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     }
 }
 
-// Position x of the flat chunk sequence belongs to workgroup w with
+// Position x of the flat chunk sequence belongs to the share w with
 // floor(w * total / P) <= x < floor((w + 1) * total / P).
 __device__ __forceinline__ long long share_of(long long x, long long total, int P)
 {
     return ((x + 1) * P - 1) / total;
 }
 
-// Merges the pieces of every (request, head chunk) that was split over several
-// shares, in share order (= token order).  grid = (head chunks, batch).
-template <bool BF16, int GH>
-__global__ void decode_merge_balanced(const DecodeArgs a, int P)
+// Merges the pieces of every (request, kv head / pass) that was split over
+// several shares, in share order (= token order).  grid = (kv heads * passes,
+// batch, slices of 256 (head, dim) outputs); one output per thread.
+template <bool BF16>
+__global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a, int P)
 {
     const int r = blockIdx.y, hc = blockIdx.x;
     const int D = a.head_dim;
     const int G = a.num_q_heads / a.num_kv_heads;
-    const int chunks_per_group = G / GH;
-    const int HC = a.num_kv_heads * chunks_per_group;
+    const int GH = a.heads_per_pass;
+    const int passes = G / GH;
+    const int HC = a.num_kv_heads * passes;
     const int base = a.chunk_prefix[r], nr = a.chunk_prefix[r + 1] - base;
     if (nr == 0) return;                              // not running: row untouched
     const long long total = (long long)HC * a.chunk_prefix[a.batch];
     const long long off = (long long)HC * base + (long long)hc * nr;
     const int w_first = (int)share_of(off, total, P), w_last = (int)share_of(off + nr - 1, total, P);
     if (w_first == w_last) return;                    // one share held it all and wrote the result
-    const int g = hc / chunks_per_group;
-    const size_t rh0 = (size_t)r * a.num_q_heads + g * G + (hc % chunks_per_group) * GH;
-    for (int idx = threadIdx.x; idx < GH * D; idx += blockDim.x) {
-        const int h = idx / D, d = idx % D;
-        float M = kLowest;
-        for (int w = w_first; w <= w_last; ++w) {
+    const int g = hc / passes;
+    const size_t rh0 = (size_t)r * a.num_q_heads + g * G + (hc % passes) * GH;
+    const int idx = blockIdx.z * 256 + threadIdx.x;
+    const bool live = idx < GH * D;
+    const int h = live ? idx / D : 0, d = live ? idx % D : 0;
+    // the pieces' slots, worked out once per block (64-bit divisions), kMergeList at a time
+    __shared__ int piece[kMergeList];
+    float M = kLowest, L = 0.0f, A = 0.0f;
+    for (int w0 = w_first; w0 <= w_last; w0 += kMergeList) {
+        const int cnt = min(kMergeList, w_last - w0 + 1);
+        __syncthreads();
+        if ((int)threadIdx.x < cnt) {
+            const int w = w0 + threadIdx.x;
             const long long xb = (long long)w * total / P;
-            if (xb >= (long long)(w + 1) * total / P) continue;     // empty share (more shares than chunks)
-            const int slot = xb >= off ? 0 : 1;
-            M = fmaxf(M, a.partials[(((size_t)w * 2 + slot) * GH + h) * (D + 2) + D]);
+            piece[threadIdx.x] = xb >= (long long)(w + 1) * total / P ? -1      // empty share
+                                                                      : w * 2 + (xb >= off ? 0 : 1);
         }
-        float L = 0.0f, A = 0.0f;
-        for (int w = w_first; w <= w_last; ++w) {
-            const long long xb = (long long)w * total / P;
-            if (xb >= (long long)(w + 1) * total / P) continue;
-            const int slot = xb >= off ? 0 : 1;
-            const float *x = a.partials + (((size_t)w * 2 + slot) * GH + h) * (D + 2);
-            const float f = fast_exp2(x[D] - M);
-            L += x[D + 1] * f;
-            A += x[d] * f;
+        __syncthreads();
+        for (int i = 0; i < cnt; ++i) {                // share order = token order
+            if (piece[i] < 0) continue;
+            const float *x = a.partials + ((size_t)piece[i] * GH + h) * (D + 2);
+            const float mo = x[D], mn = fmaxf(M, mo);
+            const float fa = fast_exp2(M - mn), fb = fast_exp2(mo - mn);
+            L = L * fa + x[D + 1] * fb;
+            A = A * fa + x[d] * fb;
+            M = mn;
         }
-        store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
     }
+    if (live) store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
 }
 
 // ---------------------------------------------------------------- launchers
 
-template <bool BF16, int LPT, int GH, int NH>
+template <typename R>
 hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
 {
     const int G = a.num_q_heads / a.num_kv_heads;
-    const int HC = a.num_kv_heads * (G / GH);
+    const int HC = a.num_kv_heads * (G / a.heads_per_pass);
     if (a.part_tokens > 0) {
         dim3 grid((unsigned)((size_t)a.max_parts * HC * a.batch));
-        hipLaunchKernelGGL((decode_partial<BF16, LPT, GH, NH>), grid, dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL(decode_partial<R>, grid, dim3(kThreads), 0, s, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess || a.max_parts == 1) return e;
-        hipLaunchKernelGGL(decode_merge<BF16>, dim3(a.num_q_heads, a.batch), dim3(a.head_dim), 0, s, a);
+        hipLaunchKernelGGL(decode_merge<R::kBF16>, dim3(a.num_q_heads, a.batch), dim3(a.head_dim), 0,
+                           s, a);
         return hipGetLastError();
     }
     // balanced: as many workgroups as the chip holds at once for this kernel
@@ -594,40 +775,58 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess)
-            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                &per_cu, decode_balanced<BF16, LPT, GH, NH>, kThreads, (a.max_batch + 1) * sizeof(int));
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_balanced<R>, kThreads,
+                                                             (a.max_batch + 1) * sizeof(int));
         if (e != hipSuccess) return e;
         if (cus < 1 || per_cu < 1) return hipErrorInvalidValue;
         resident = cus * per_cu;
         if (resident > kMaxShares) resident = kMaxShares;
     }
     const size_t lds = (size_t)(a.batch + 1) * sizeof(int);
-    hipLaunchKernelGGL((decode_balanced<BF16, LPT, GH, NH>), dim3(resident), dim3(kThreads), lds, s, a);
+    hipLaunchKernelGGL(decode_balanced<R>, dim3(resident), dim3(kThreads), lds, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int mt = GH * a.head_dim < 256 ? GH * a.head_dim : 256;
-    hipLaunchKernelGGL((decode_merge_balanced<BF16, GH>), dim3(HC, a.batch), dim3(mt), 0, s, a, resident);
+    const int slices = (a.heads_per_pass * a.head_dim + 255) / 256;
+    hipLaunchKernelGGL(decode_merge_balanced<R::kBF16>, dim3(HC, a.batch, slices), dim3(256), 0, s, a,
+                       resident);
     return hipGetLastError();
 }
 
 template <bool BF16, int LPT>
-hipError_t launch_gh(const DecodeArgs &a, int gh, hipStream_t s)
+hipError_t launch_valu(const DecodeArgs &a, hipStream_t s)
 {
-    switch (gh) {
-    case 1: return launch_one<BF16, LPT, 1, kHalves>(a, s);
-    case 2: return launch_one<BF16, LPT, 2, kHalves>(a, s);
-    case 4: return launch_one<BF16, LPT, 4, 1>(a, s);
-    default: return hipErrorInvalidValue;
+    switch (a.heads_per_pass) {
+    case 1: return launch_one<ValuReducer<BF16, LPT, 1, kHalves>>(a, s);
+    case 2: if (!BF16) return launch_one<ValuReducer<BF16, LPT, 2, kHalves>>(a, s); break;
+    case 4: if (!BF16) return launch_one<ValuReducer<BF16, LPT, 4, 1>>(a, s); break;
     }
+    return hipErrorInvalidValue;
+}
+
+template <int D>
+hipError_t launch_mfma(const DecodeArgs &a, hipStream_t s)
+{
+    const int gh = a.heads_per_pass;
+    if (gh <= 2) return launch_one<MfmaReducer<D, 2>>(a, s);
+    if (gh <= 4) return launch_one<MfmaReducer<D, 4>>(a, s);
+    if (gh <= 8) return launch_one<MfmaReducer<D, 8>>(a, s);
+    if (gh <= 16) return launch_one<MfmaReducer<D, 16>>(a, s);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-int decode_heads_per_group(int bf16, int head_dim, int group)
+int decode_uses_tiled_layout(int bf16, int group) { return bf16 && group >= 2; }
+
+int decode_heads_per_pass(int bf16, int head_dim, int group)
 {
     const int lpt = head_dim * (bf16 ? 2 : 4) / 16;
     if (head_dim * (bf16 ? 2 : 4) % 16 != 0 || (lpt != 8 && lpt != 16 && lpt != 32)) return 0;
     if (group <= 0) return 0;
+    if (decode_uses_tiled_layout(bf16, group)) {      // MFMA path: the largest divisor <= 16
+        for (int gh = 16; gh >= 1; --gh)
+            if (group % gh == 0) return gh;
+    }
     if (group % 4 == 0) return 4;
     if (group % 2 == 0) return 2;
     return 1;
@@ -639,17 +838,21 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
 {
     if (a.batch == 0) return hipSuccess;
     const int G = a.num_q_heads / a.num_kv_heads;
-    const int gh = decode_heads_per_group(a.bf16, a.head_dim, G);
-    if (gh == 0) return hipErrorInvalidValue;
+    if (a.heads_per_pass != decode_heads_per_pass(a.bf16, a.head_dim, G) || a.heads_per_pass == 0)
+        return hipErrorInvalidValue;
     const int lpt = a.head_dim * (a.bf16 ? 2 : 4) / 16;
-    if (a.bf16) {
-        if (lpt == 8) return launch_gh<true, 8>(a, gh, stream);
-        if (lpt == 16) return launch_gh<true, 16>(a, gh, stream);
-        if (lpt == 32) return launch_gh<true, 32>(a, gh, stream);
+    if (decode_uses_tiled_layout(a.bf16, G)) {
+        if (a.head_dim == 64) return launch_mfma<64>(a, stream);
+        if (a.head_dim == 128) return launch_mfma<128>(a, stream);
+        if (a.head_dim == 256) return launch_mfma<256>(a, stream);
+    } else if (a.bf16) {
+        if (lpt == 8) return launch_valu<true, 8>(a, stream);
+        if (lpt == 16) return launch_valu<true, 16>(a, stream);
+        if (lpt == 32) return launch_valu<true, 32>(a, stream);
     } else {
-        if (lpt == 8) return launch_gh<false, 8>(a, gh, stream);
-        if (lpt == 16) return launch_gh<false, 16>(a, gh, stream);
-        if (lpt == 32) return launch_gh<false, 32>(a, gh, stream);
+        if (lpt == 8) return launch_valu<false, 8>(a, stream);
+        if (lpt == 16) return launch_valu<false, 16>(a, stream);
+        if (lpt == 32) return launch_valu<false, 32>(a, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -8,7 +8,7 @@ namespace lamps {
 
 struct DecodeArgs {
     const void *q;            // [batch][H][D]
-    const void *k_pool;       // pool[block][layer][kv_head][slot][d]
+    const void *k_pool;       // pool[block][layer][kv_head][tile of block_size * head_dim]
     const void *v_pool;
     const int32_t *block_table;  // [batch][max_blocks]
     const int32_t *ctx_lens;     // [batch]
@@ -20,12 +20,15 @@ struct DecodeArgs {
     int32_t batch, max_batch, layer, num_layers, num_q_heads, num_kv_heads, head_dim;
     int32_t block_size, log2_block_size, max_blocks, part_tokens, max_parts;
     int32_t bf16;             // 0: fp32 storage, 1: bf16 storage
+    int32_t heads_per_pass;   // query heads of a kv group that share one pass over K/V
     float scale_log2e;        // softmax scale * log2(e)
 };
 
-// Heads of one kv group handled by one workgroup for this geometry
-// (0 if the geometry is not supported).
-int decode_heads_per_group(int bf16, int head_dim, int group);
+// Query heads of one kv group that share a pass over K/V for this geometry
+// (0 if the geometry is not supported); group / result passes re-read K/V.
+int decode_heads_per_pass(int bf16, int head_dim, int group);
+// Nonzero if the geometry's pools use the tiled (MFMA operand) layout.
+int decode_uses_tiled_layout(int bf16, int group);
 
 // Most workgroups ("shares") the balanced scheme launches; sizes its partials.
 int decode_max_shares();

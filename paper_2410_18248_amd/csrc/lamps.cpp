@@ -43,7 +43,7 @@ const char *derive(const lamps_config *c, Derived *d)
         return "sizes must be positive";
     if (c->num_q_heads % c->num_kv_heads != 0) return "num_q_heads must be a multiple of num_kv_heads";
     const int bf16 = c->dtype == LAMPS_BF16;
-    if (lamps::decode_heads_per_group(bf16, c->head_dim, c->num_q_heads / c->num_kv_heads) == 0)
+    if (lamps::decode_heads_per_pass(bf16, c->head_dim, c->num_q_heads / c->num_kv_heads) == 0)
         return "unsupported head_dim for this dtype (bf16: 64/128/256, f32: 32/64/128)";
     if (c->block_size < 16 || (c->block_size & (c->block_size - 1)) != 0)
         return "block_size must be a power of two >= 16";
@@ -59,7 +59,7 @@ const char *derive(const lamps_config *c, Derived *d)
         return "part_tokens must be 0 or a positive multiple of block_size";
     if (c->max_batch > 8192) return "max_batch is limited to 8192";
     const int group = c->num_q_heads / c->num_kv_heads;
-    const int gh = lamps::decode_heads_per_group(bf16, c->head_dim, group);
+    const int gh = lamps::decode_heads_per_pass(bf16, c->head_dim, group);
     if (d->part_tokens > 0) {
         const int64_t max_ctx = (int64_t)c->max_blocks_per_req * c->block_size;
         d->max_parts = (int)((max_ctx + d->part_tokens - 1) / d->part_tokens);
@@ -283,6 +283,15 @@ size_t lamps_kv_bytes_per_token(const lamps_config *cfg)
     return 2 * (size_t)cfg->num_layers * cfg->num_kv_heads * cfg->head_dim * d.elem;
 }
 
+int lamps_kv_layout(const lamps_config *cfg)
+{
+    Derived d;
+    if (derive(cfg, &d)) return LAMPS_ERR_INVALID;
+    return lamps::decode_uses_tiled_layout(cfg->dtype == LAMPS_BF16, cfg->num_q_heads / cfg->num_kv_heads)
+               ? LAMPS_LAYOUT_TILED
+               : LAMPS_LAYOUT_PLAIN;
+}
+
 size_t lamps_block_bytes(const lamps_config *cfg)
 {
     Derived d;
@@ -402,6 +411,7 @@ int lamps_decode_attn(lamps_ctx *c, int32_t layer, int32_t batch, const void *q,
     a.part_tokens = c->d.part_tokens;
     a.max_parts = c->d.max_parts;
     a.bf16 = c->cfg.dtype == LAMPS_BF16;
+    a.heads_per_pass = lamps::decode_heads_per_pass(a.bf16, a.head_dim, a.num_q_heads / a.num_kv_heads);
     a.scale_log2e = c->d.scale_log2e;
     LAMPS_HIP(lamps::launch_decode(a, c->cs));
     return LAMPS_OK;

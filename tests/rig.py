@@ -40,6 +40,9 @@ class Rig:
         self.tdtype = torch.bfloat16 if geom.dtype == "bf16" else torch.float32
         self.cfg = make_config(geom, max_batch, part_tokens, staging_bytes, scale)
         assert P.lamps_pool_bytes(self.cfg) == int(np.prod(geom.pool_shape)) * geom.elem_bytes
+        assert P.lamps_kv_layout(self.cfg) == (P.LAMPS_LAYOUT_TILED if geom.kv_layout == "tiled"
+                                               else P.LAMPS_LAYOUT_PLAIN)
+        self.k_index, self.v_index = geom.tile_index_maps()
         self.k_pool = torch.empty(geom.pool_shape, dtype=self.tdtype, device=self.dev)
         self.v_pool = torch.empty(geom.pool_shape, dtype=self.tdtype, device=self.dev)
         if poison:
@@ -73,20 +76,17 @@ class Rig:
         kp, vp = kp.copy(), vp.copy()
         for r in range(len(K)):
             if K[r] is not None:
-                W.page(kp, layer, table[r], K[r])
-                W.page(vp, layer, table[r], V[r])
+                W.page(kp, layer, table[r], K[r], self.k_index)
+                W.page(vp, layer, table[r], V[r], self.v_index)
         self.upload_pools(kp, vp)
 
     # ---- un-paging (device -> logical) for physical-first inputs
     def unpage_request(self, layer, table_row, C):
         nb = self.geom.blocks_for(C)
         ids = torch.as_tensor(np.asarray(table_row[:nb], dtype=np.int64), device=self.dev)
-        kb = t2n(self.k_pool[ids, layer])            # [nb][Hkv][bs][D]
+        kb = t2n(self.k_pool[ids, layer])            # [nb][Hkv][tile]
         vb = t2n(self.v_pool[ids, layer])
-        Hkv, D = self.geom.num_kv_heads, self.geom.head_dim
-        k = np.swapaxes(kb, 1, 2).reshape(-1, Hkv, D)[:C]
-        v = np.swapaxes(vb, 1, 2).reshape(-1, Hkv, D)[:C]
-        return np.ascontiguousarray(k), np.ascontiguousarray(v)
+        return W.tiles_to_logical(kb, self.k_index, C), W.tiles_to_logical(vb, self.v_index, C)
 
     # ---- one decode call through the C ABI
     def decode(self, layer, q, table, ctx, running, out=None, sentinel=None):

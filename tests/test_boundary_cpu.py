@@ -38,7 +38,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "lamps.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = sorted(set(re.findall(r"\b(lamps_[a-z_]+)\s*\(", header)))
-    assert len(names) == 17
+    assert len(names) == 18
     lib = P.load_library()
     for n in names:
         assert hasattr(lib, n), n
@@ -55,6 +55,13 @@ def test_sizes():
     c1 = _cfg(num_layers=1, num_q_heads=32, num_kv_heads=32, num_blocks=40000, max_blocks_per_req=128,
               max_batch=64)
     assert P.lamps_pool_bytes(c1) == g.num_blocks * g.block_half_bytes
+
+
+def test_layout_query():
+    assert P.lamps_kv_layout(_cfg()) == P.LAMPS_LAYOUT_TILED                       # bf16, 8 / 2 heads
+    assert P.lamps_kv_layout(_cfg(num_kv_heads=8)) == P.LAMPS_LAYOUT_PLAIN        # bf16 MHA
+    assert P.lamps_kv_layout(_cfg(dtype=P.LAMPS_F32)) == P.LAMPS_LAYOUT_PLAIN     # fp32
+    assert P.lamps_kv_layout(_cfg(head_dim=96)) == -1
 
 
 def test_kv_bytes_matches_paper_example():

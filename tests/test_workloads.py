@@ -33,19 +33,46 @@ def test_bf16_rounding_matches_torch():
                                   torch.from_numpy(x).to(torch.bfloat16).float().numpy())
 
 
-def test_page_unpage_round_trip_and_layout():
-    g = W.Geometry(2, 4, 2, 8, 16, 10, 4, "f32")
+def test_page_unpage_round_trip_and_plain_layout():
+    g = W.Geometry(2, 4, 4, 8, 16, 10, 4, "f32")
+    assert g.kv_layout == "plain"
+    k_index, v_index = g.tile_index_maps()
     kp = np.full(g.pool_shape, np.nan, dtype=np.float32)
     k, _ = W.logical_kv(1, g, 37)
     row = np.array([6, 1, 9, -1], dtype=np.int32)
-    W.page(kp, 1, row, k)
-    np.testing.assert_array_equal(W.unpage(kp, 1, row, 37), k)
-    # element (t, head, d) sits at pool[table[t // bs], layer, head, t % bs, d]
-    for t, h, d in [(0, 0, 0), (16, 1, 3), (36, 0, 7)]:
-        flat = ((((row[t // 16] * 2 + 1) * 2 + h) * 16 + t % 16) * 8 + d)
+    W.page(kp, 1, row, k, k_index)
+    np.testing.assert_array_equal(W.unpage(kp, 1, row, 37, k_index), k)
+    # element (t, head, d) sits at pool[table[t // bs], layer, head][(t % bs) * D + d]
+    for t, h, d in [(0, 0, 0), (16, 1, 3), (36, 3, 7)]:
+        flat = ((((row[t // 16] * 2 + 1) * 4 + h) * 16 + t % 16) * 8 + d)
         assert kp.reshape(-1)[flat] == k[t, h, d]
-    assert np.isnan(kp[9, 1, :, 5:, :]).all()        # tail slots untouched
-    assert np.isnan(kp[:, 0]).all()                  # other layer untouched
+    assert np.isnan(kp[9, 1].reshape(4, 16, 8)[:, 5:, :]).all()    # tail slots untouched
+    assert np.isnan(kp[:, 0]).all()                                   # other layer untouched
+
+
+def test_tiled_layout_is_a_permutation_with_the_documented_runs():
+    g = W.Geometry(1, 8, 2, 128, 32, 4, 2, "bf16")
+    assert g.kv_layout == "tiled" and W.Geometry(1, 8, 8, 128, 32, 4, 2, "bf16").kv_layout == "plain"
+    k_index, v_index = g.tile_index_maps()
+    for m in (k_index, v_index):                       # a bijection onto the tile
+        assert sorted(m.ravel().tolist()) == list(range(32 * 128))
+    # keys: the 8 dims d..d+7 (d % 8 == 0) of one slot are one 16-byte run; the 16 slots of a
+    # sub-tile follow each other for a fixed group of 8 dims
+    assert (np.diff(k_index[5, 40:48]) == 1).all() and k_index[5, 40] % 8 == 0
+    assert k_index[6, 40] - k_index[5, 40] == 8 and k_index[21, 40] - k_index[5, 40] == 16 * 128
+    # values: 4 consecutive slots of one dim are adjacent; then the same slots of dim + 16
+    assert (np.diff(v_index[8:12, 3]) == 1).all() and v_index[8, 3] % 4 == 0
+    assert v_index[8, 19] - v_index[8, 3] == 4 and v_index[8, 4] - v_index[8, 3] == 8
+    assert v_index[8, 35] - v_index[8, 3] == 4 * 16 * 8          # next pair of 16-dim slabs
+    # round trip through the pager
+    kp = np.zeros(g.pool_shape, dtype=np.uint16)
+    vp = np.zeros(g.pool_shape, dtype=np.uint16)
+    k, v = W.logical_kv(3, g, 45)
+    row = np.array([2, 0], dtype=np.int32)
+    W.page(kp, 0, row, k, k_index)
+    W.page(vp, 0, row, v, v_index)
+    np.testing.assert_array_equal(W.unpage(kp, 0, row, 45, k_index), k)
+    np.testing.assert_array_equal(W.unpage(vp, 0, row, 45, v_index), v)
 
 
 def test_configurations_have_the_stated_shape():
