@@ -36,7 +36,8 @@ class LampsConfig(ctypes.Structure):
 
 
 def lib_path():
-    return os.path.join(_HERE, "liblamps.so")
+    """The built library; LAMPS_LIBRARY overrides the in-tree path (to compare builds)."""
+    return os.environ.get("LAMPS_LIBRARY") or os.path.join(_HERE, "liblamps.so")
 
 
 def load_library():

@@ -29,17 +29,25 @@ def _compile(src, obj, extra):
     return obj
 
 
-def build(verbose=False, extra=()):
-    bdir = os.path.join(ROOT, "_build")
+def build(verbose=False, extra=(), out=None):
+    """Compiles the sources and links `out` (default: liblamps.so next to this file)."""
+    lib = out or LIB
+    bdir = os.path.join(ROOT, "_build", os.path.basename(lib))
     os.makedirs(bdir, exist_ok=True)
     objs = [os.path.join(bdir, s.rsplit(".", 1)[0] + ".o") for s in SOURCES]
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         list(ex.map(lambda so: _compile(so[0], so[1], list(extra)), zip(SOURCES, objs)))
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":
-    build(verbose=True, extra=sys.argv[1:])
+    args = sys.argv[1:]
+    out = None
+    if "-o" in args:
+        i = args.index("-o")
+        out = os.path.abspath(args[i + 1])
+        del args[i:i + 2]
+    build(verbose=True, extra=args, out=out)

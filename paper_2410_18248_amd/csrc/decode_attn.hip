@@ -726,7 +726,8 @@ __global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a,
     const int idx = blockIdx.z * 256 + threadIdx.x;
     const bool live = idx < GH * D;
     const int h = live ? idx / D : 0, d = live ? idx % D : 0;
-    // the pieces' slots, worked out once per block (64-bit divisions), kMergeList at a time
+    // The pieces' slots are worked out once per block (64-bit divisions), kMergeList
+    // at a time; each list is then reduced eight pieces at a time.
     __shared__ int piece[kMergeList];
     float M = kLowest, L = 0.0f, A = 0.0f;
     for (int w0 = w_first; w0 <= w_last; w0 += kMergeList) {
@@ -739,14 +740,29 @@ __global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a,
                                                                       : w * 2 + (xb >= off ? 0 : 1);
         }
         __syncthreads();
-        for (int i = 0; i < cnt; ++i) {                // share order = token order
-            if (piece[i] < 0) continue;
-            const float *x = a.partials + ((size_t)piece[i] * GH + h) * (D + 2);
-            const float mo = x[D], mn = fmaxf(M, mo);
-            const float fa = fast_exp2(M - mn), fb = fast_exp2(mo - mn);
-            L = L * fa + x[D + 1] * fb;
-            A = A * fa + x[d] * fb;
-            M = mn;
+        for (int i0 = 0; i0 < cnt; i0 += 8) {          // share order = token order
+            float mo[8], lo[8], ao[8];                 // eight pieces' loads in flight together
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int pc = i0 + k < cnt ? piece[i0 + k] : -1;
+                const float *x = a.partials + ((size_t)max(pc, 0) * GH + h) * (D + 2);
+                mo[k] = pc >= 0 ? x[D] : kLowest;
+                lo[k] = pc >= 0 ? x[D + 1] : 0.0f;
+                ao[k] = pc >= 0 ? x[d] : 0.0f;
+            }
+            float Mn = M;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, mo[k]);
+            const float f0 = fast_exp2(M - Mn);
+            L *= f0;
+            A *= f0;
+            M = Mn;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float f = fast_exp2(mo[k] - M);
+                L += lo[k] * f;
+                A += ao[k] * f;
+            }
         }
     }
     if (live) store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);

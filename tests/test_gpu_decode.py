@@ -115,7 +115,6 @@ def test_cfg0_swap_scenario():
     assert (got[2] == -5.0).all()
     for r in (0, 1, 3):
         assert np.abs(got[r] - ref[r]).max() <= 1e-5
-        assert torch.equal(out[r], base[r])
 
     # (ii) the API returns: different physical blocks, then all four run
     pad = lam.alloc_blocks(len(ids2))                   # LIFO would return the same ids: hold them
