@@ -30,7 +30,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # each scaled by the same counter's reading for a plain 1 GiB copy: x2.0 and x1.0), keyed by
 # workload name; summaries in profiles/.  None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1-7b-mha-bf16": 887_993_000,
+    "cfg1-7b-mha-bf16": 890_506_000,     # decode_balanced + decode_merge_balanced
+    "cfg2-8b-gqa-bf16": 1_706_955_000,
 }
 
 
@@ -340,9 +341,11 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(job.wl.name),
-                     "kernel": "decode_partial", "algorithmic_bytes_per_launch": job.algo_bytes,
+                     "kernel": "decode_balanced" if int(job.cfg.part_tokens) == 0 else "decode_partial",
+                     "algorithmic_bytes_per_launch": job.algo_bytes,
                      "kernel_us": kernel_s * 1e6,
-                     "timing": "HIP events on the compute stream around the timed steps / launches"},
+                     "timing": "HIP events on the compute stream around the timed steps / launches "
+                               "(includes the small merge kernel that follows each launch)"},
         "decode_alone": {"ms_per_step": dec_alone / steps * 1e3,
                          "tokens_per_s": job.n_running * steps / wall_alone,
                          "GBs": job.algo_bytes * job.g.num_layers / (dec_alone / steps) / 1e9},
