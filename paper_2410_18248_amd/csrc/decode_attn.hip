@@ -9,14 +9,17 @@
 // (request, kv head, pass over GH query heads of the group).  Two schemes share
 // the same inner loops:
 //   balanced (default): all chunks of all running requests form one flat
-//     sequence; a fixed number of workgroups (one full occupancy wave of the
-//     chip) each take an equal contiguous share of it, so every workgroup ends
-//     within a chunk of the others however skewed the context lengths are.  A
-//     share is at most: the tail of one (request, head), some whole ones, and
-//     the head of another; whole ones are written out directly, the two
-//     partial ends go to per-workgroup slots that a small second kernel merges.
+//     sequence; as many wavefronts as the chip holds at once each take an equal
+//     contiguous share of it, so every wavefront ends within a chunk of the
+//     others however skewed the context lengths are.  A share is at most: the
+//     tail of one (request, head), some whole ones, and the head of another;
+//     whole ones are written out directly, the two partial ends go to
+//     per-share slots that a small second kernel merges.
 //   fixed partitions (part_tokens > 0): the context is cut every part_tokens
-//     tokens, one workgroup per (partition, request, kv head) in a dense grid.
+//     tokens, one wavefront per (partition, request, kv head) in a dense grid.
+// A wavefront works alone (no LDS, no barrier in the main path): with many short
+// requests there are far more (request, head) ranges than workgroups, and four
+// waves cooperating on each would spend their time in start-up and hand-over.
 // Partitions are merged by a separate launch on purpose: a kernel boundary
 // makes the partials visible across the eight XCDs' L2s once, whereas a
 // device-scope fence per workgroup writes back and invalidates an L2 each time.
@@ -37,8 +40,6 @@
 //     load IS an MFMA operand: no LDS staging, no shuffles.  The weights p are
 //     fed as a bf16 pair (high part + remainder), which keeps fp32-grade
 //     weights at the price of a second, nearly free, MFMA.
-// In both, the four waves of a workgroup take chunks round-robin and are merged
-// through LDS once per range.
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
@@ -51,9 +52,10 @@ constexpr int kThreads = 64 * kWaves;
 // wave-wide 16-byte loads per half-chunk and pool; a half-chunk (loads * tokens
 // per load) must fit in the smallest block (16 tokens)
 constexpr int loads_per_chunk(int lpt) { return lpt == 8 ? 2 : 4; }
-constexpr int kHalves = 2;              // half-chunks a wave keeps in flight on the 1-2 head paths
+constexpr int kHalves = 2;              // half-chunks per chunk on the 1-2 head vector-ALU paths
 constexpr float kLowest = -3.0e38f;     // finite stand-in for "no score seen yet"
-constexpr int kMaxShares = 4096;        // most workgroups the balanced scheme ever launches
+constexpr int kMaxShares = 16384;       // most wave shares the balanced scheme ever uses
+constexpr size_t kPartialBudget = (size_t)64 << 20;   // bytes of partial slots it may need
 constexpr int kMergeList = 64;          // pieces whose slots are resolved per pass of the balanced merge
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -173,35 +175,6 @@ __device__ __forceinline__ void merge_state(float &m, float &l, float (&acc)[VEC
     m = mn;
 }
 
-// LDS for the merge of the four waves of a workgroup: per wave and head the
-// running max (log2 domain), the weight sum and the weighted sum of V.
-template <int HEADS, int D>
-struct WaveMerge {
-    float acc[kWaves][HEADS][D];
-    float m[kWaves][HEADS], l[kWaves][HEADS];
-};
-
-// Last step of both reducers: combines the four waves' states (already written
-// to sm by the caller, behind a barrier) and hands every (head, dim) to sink.
-template <int HEADS, int D, typename Sink>
-__device__ __forceinline__ void combine_waves(const WaveMerge<HEADS, D> &sm, int heads, Sink sink)
-{
-    for (int idx = threadIdx.x; idx < heads * D; idx += kThreads) {
-        const int h = idx / D, d = idx % D;
-        float M = sm.m[0][h];
-#pragma unroll
-        for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, sm.m[ww][h]);
-        float L = 0.0f, A = 0.0f;
-#pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww) {
-            float f = fast_exp2(sm.m[ww][h] - M);
-            L += sm.l[ww][h] * f;
-            A += sm.acc[ww][h][d] * f;
-        }
-        sink(h, d, M, L, A);
-    }
-}
-
 // ---------------------------------------------------------------- vector-ALU reducer
 
 // Plain pool layout, GH query heads of the group per pass (GH == 1 for bf16).
@@ -216,20 +189,17 @@ struct ValuReducer {
     static constexpr int HT = TPW * kLoads;           // tokens per half-chunk (<= 16 <= block_size)
     static constexpr int NL = NH * kLoads;            // wave-wide loads per chunk and pool
     static constexpr int CT = HT * NH;                // tokens per chunk
-    static constexpr int HEADS = GH;                  // heads per pass (LDS is sized for it)
-    using Smem = WaveMerge<HEADS, D>;
 
-    // Reduces cached positions [t_begin, t_end) of request r (kv head g, query
-    // heads h0 .. h0+GH-1) with all four waves of the workgroup, then calls
+    // One wavefront reduces cached positions [t_begin, t_end) of request r (kv
+    // head g, query heads h0 .. h0+GH-1), chunk after chunk, then calls
     // sink(h, d, M, L, A) once for every (head, dim): M = running max (log2
     // domain), L = sum of weights, A = weighted sum of V[:, d].  t_begin is a
-    // multiple of CT.  Contains two workgroup barriers: all threads call it.
+    // multiple of CT.  No barrier, no LDS: waves of a workgroup are independent.
     template <typename Sink>
     static __device__ __forceinline__ void run(const DecodeArgs &a, int r, int g, int h0, int,
-                                               int t_begin, int t_end, Smem &sm, Sink sink)
+                                               int t_begin, int t_end, Sink sink)
     {
         const int lane = threadIdx.x & 63;
-        const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int row = lane / LPT;                // which of the TPW tokens of a load
         const int col = lane % LPT;                // which 16-byte slice of the head vector
 
@@ -261,8 +231,9 @@ struct ValuReducer {
         // A chunk is NH half-chunks of HT tokens; a half-chunk never straddles a
         // block (HT <= 16 <= block_size), so it needs one block-table entry.  All
         // NH * kLoads K loads and as many V loads of a chunk are issued before
-        // any is consumed.  Wave w takes chunks w, w + 4, ...
-        int ch = w;
+        // any is consumed (a deeper software pipeline brought nothing here: with
+        // up to eight waves per SIMD the other waves' loads fill the gaps).
+        int ch = 0;
         int pb[NH], pbn[NH];
 #pragma unroll
         for (int f = 0; f < NH; ++f) {
@@ -292,8 +263,8 @@ struct ValuReducer {
                 }
             }
 
-            // physical blocks of this wave's next chunk, fetched while the tiles arrive
-            const int chn = ch + kWaves;
+            // physical blocks of the next chunk, fetched while the tiles arrive
+            const int chn = ch + 1;
 #pragma unroll
             for (int f = 0; f < NH; ++f) {
                 const int th = t_begin + chn * CT + f * HT;
@@ -362,21 +333,12 @@ struct ValuReducer {
             }
         }
 
-        // waves -> one state per workgroup, through LDS
-        __syncthreads();                       // the previous range's readers are done with sm
         if (row == 0) {
 #pragma unroll
-            for (int h = 0; h < GH; ++h) {
+            for (int h = 0; h < GH; ++h)
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) sm.acc[w][h][col * VEC + e] = acc[h][e];
-                if (col == 0) {
-                    sm.m[w][h] = m[h];
-                    sm.l[w][h] = l[h];
-                }
-            }
+                for (int e = 0; e < VEC; ++e) sink(h, col * VEC + e, m[h], l[h], acc[h][e]);
         }
-        __syncthreads();
-        combine_waves<HEADS, D>(sm, GH, sink);
     }
 };
 
@@ -391,22 +353,19 @@ struct ValuReducer {
 // out^T[dim][head] += V^T . p^T (A = a coalesced V load).  So every statistic of
 // head j lives in the lanes with lane%16 == j, and the only cross-lane step per
 // sub-tile is the max over the four token groups (two shuffles).
-template <int DIM, int HEADS_PAD>
+template <int DIM>
 struct MfmaReducer {
     static constexpr bool kBF16 = true;
     static constexpr int D = DIM;
     static constexpr int CT = 16;                     // tokens per chunk = one sub-tile
     static constexpr int NK = D / 32;                 // K loads = score MFMAs per sub-tile
     static constexpr int NS = D / 32;                 // V loads per sub-tile (two 16-dim slabs each)
-    static constexpr int HEADS = HEADS_PAD;
-    using Smem = WaveMerge<HEADS, D>;
 
     template <typename Sink>
     static __device__ __forceinline__ void run(const DecodeArgs &a, int r, int g, int h0, int heads,
-                                               int t_begin, int t_end, Smem &sm, Sink sink)
+                                               int t_begin, int t_end, Sink sink)
     {
         const int lane = threadIdx.x & 63;
-        const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int j = lane & 15;                   // head (B / result column); dim in slab (V rows)
         const int qd = lane >> 4;                  // token group of 4 (results) / k slice (operands)
 
@@ -435,21 +394,31 @@ struct MfmaReducer {
         const char *kp = static_cast<const char *>(a.k_pool) + head_off + lane * 16;
         const char *vp = static_cast<const char *>(a.v_pool) + head_off + lane * 16;
 
-        int ch = w;
-        int pb = ch < n_chunks ? table[(t_begin + ch * CT) >> a.log2_block_size] : 0;
-        while (ch < n_chunks) {
-            const int t0 = t_begin + ch * CT;
-            // sub-tile (t0 % block_size) / 16 of the block's tile: 16 * D elements each
-            const size_t off = (size_t)pb * block_stride +
-                               (size_t)((t0 & (a.block_size - 1)) >> 4) * (16 * D * 2);
-            uint4 kx[NK], vx[NS];
+        // Software pipeline: the loads of chunk ch + 1 are issued before chunk ch is
+        // consumed, and the block-table entry of chunk ch + 2 is fetched with them,
+        // so a wave always has a sub-tile of K and V in flight while it computes.
+        auto entry = [&](int c) -> int {
+            return c < n_chunks ? table[(t_begin + c * CT) >> a.log2_block_size] : 0;
+        };
+        auto issue = [&](int c, int block, uint4 (&kx)[NK], uint4 (&vx)[NS]) {
+            // sub-tile (t % block_size) / 16 of the block's tile: 16 * D elements each
+            const int t = t_begin + c * CT;
+            const size_t off = (size_t)block * block_stride +
+                               (size_t)((t & (a.block_size - 1)) >> 4) * (16 * D * 2);
 #pragma unroll
             for (int i = 0; i < NK; ++i) kx[i] = load_stream16(kp + off + i * 1024);
 #pragma unroll
             for (int i = 0; i < NS; ++i) vx[i] = load_stream16(vp + off + i * 1024);
-
-            const int chn = ch + kWaves;
-            const int pbn = chn < n_chunks ? table[(t_begin + chn * CT) >> a.log2_block_size] : 0;
+        };
+        uint4 kx[NK], vx[NS], kn[NK], vn[NS];
+        int ch = 0;
+        int pb1 = entry(1);
+        if (n_chunks > 0) issue(0, entry(0), kx, vx);
+        while (ch < n_chunks) {
+            const int t0 = t_begin + ch * CT;
+            const int pb2 = entry(ch + 2);
+            if (ch + 1 < n_chunks) issue(ch + 1, pb1, kn, vn);
+            pb1 = pb2;
 
             f32x4 s = {0.f, 0.f, 0.f, 0.f};        // tokens t0 + 4 qd + e, head j
 #pragma unroll
@@ -509,40 +478,34 @@ struct MfmaReducer {
                 o[2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1.v, ph.v, o[2 * i + 1], 0, 0, 0);
                 o[2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1.v, pl.v, o[2 * i + 1], 0, 0, 0);
             }
-            ch = chn;
-            pb = pbn;
+            ++ch;
+#pragma unroll
+            for (int i = 0; i < NK; ++i) kx[i] = kn[i];
+#pragma unroll
+            for (int i = 0; i < NS; ++i) vx[i] = vn[i];
         }
 
         // the weight sum was kept per token group: add the four groups of a head
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
 
-        __syncthreads();                           // the previous range's readers are done with sm
         if (j < heads) {
 #pragma unroll
             for (int sidx = 0; sidx < 2 * NS; ++sidx)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) sm.acc[w][j][16 * sidx + 4 * qd + e] = o[sidx][e];
-            if (qd == 0) {
-                sm.m[w][j] = m;
-                sm.l[w][j] = l;
-            }
+                for (int e = 0; e < 4; ++e) sink(j, 16 * sidx + 4 * qd + e, m, l, o[sidx][e]);
         }
-        __syncthreads();
-        combine_waves<HEADS, D>(sm, heads, sink);
     }
 };
 
 // ---------------------------------------------------------------- fixed partitions
 
-// One workgroup: one (partition, request, kv head / pass), decoded from a 1-D
-// grid.  The heads of one pass share the K/V stream.
+// One wavefront: one (partition, request, kv head / pass), decoded from a 1-D
+// index.  The heads of one pass share the K/V stream.
 template <typename R>
 __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
 {
     constexpr int D = R::D;
-    __shared__ typename R::Smem sm;
-
     // Workgroups are handed to the eight XCDs round-robin in launch order, so the
     // index that varies fastest must be one along which the work is even: the
     // kv head (and pass), then the request, then the partition.  (With the
@@ -552,9 +515,12 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     const int GH = a.heads_per_pass;
     const int passes = G / GH;
     const int hc_count = a.num_kv_heads * passes;
-    const int hc = blockIdx.x % hc_count;
-    const int r = (blockIdx.x / hc_count) % a.batch;
-    const int part = blockIdx.x / (hc_count * a.batch);
+    const long long item = (long long)blockIdx.x * kWaves +
+                           __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (item >= (long long)a.max_parts * hc_count * a.batch) return;
+    const int hc = (int)(item % hc_count);
+    const int r = (int)((item / hc_count) % a.batch);
+    const int part = (int)(item / ((long long)hc_count * a.batch));
     const int running = a.running[r];          // both loads are in flight together
     const int C = a.ctx_lens[r];
     if (!running) return;                      // Preserve / Swap / Discard: not in the batch
@@ -566,7 +532,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     const int h0 = g * G + (hc % passes) * GH;
     const size_t rh0 = (size_t)r * a.num_q_heads + h0;
 
-    R::run(a, r, g, h0, GH, t_begin, t_end, sm, [&](int h, int d, float M, float L, float A) {
+    R::run(a, r, g, h0, GH, t_begin, t_end, [&](int h, int d, float M, float L, float A) {
         if (n_parts == 1)
             store_out<R::kBF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
         else
@@ -587,14 +553,30 @@ __global__ void decode_merge(const DecodeArgs a)
     const int D = a.head_dim;
     const size_t rh = (size_t)r * a.num_q_heads + h;
     const float *pp = a.partials + rh * a.max_parts * (D + 2);
-    float M = kLowest;
-    for (int p = 0; p < n_parts; ++p) M = fmaxf(M, pp[(size_t)p * (D + 2) + D]);
-    float L = 0.0f, A = 0.0f;
-    for (int p = 0; p < n_parts; ++p) {
-        const float *x = pp + (size_t)p * (D + 2);
-        float f = fast_exp2(x[D] - M);
-        L += x[D + 1] * f;
-        A += x[d] * f;
+    float M = kLowest, L = 0.0f, A = 0.0f;
+    for (int p0 = 0; p0 < n_parts; p0 += 8) {         // eight partitions' loads in flight together
+        float mo[8], lo[8], ao[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const bool ok = p0 + k < n_parts;
+            const float *x = pp + (size_t)(ok ? p0 + k : 0) * (D + 2);
+            mo[k] = ok ? x[D] : kLowest;
+            lo[k] = ok ? x[D + 1] : 0.0f;
+            ao[k] = ok ? x[d] : 0.0f;
+        }
+        float Mn = M;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, mo[k]);
+        const float f0 = fast_exp2(M - Mn);
+        L *= f0;
+        A *= f0;
+        M = Mn;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float f = fast_exp2(mo[k] - M);
+            L += lo[k] * f;
+            A += ao[k] * f;
+        }
     }
     store_out<BF16>(a.out, rh * D + d, L > 0.0f ? A / L : 0.0f);
 }
@@ -608,7 +590,7 @@ __device__ __forceinline__ int chunks_of(int running, int C, int CT)
     return running ? max(1, (C + CT - 1) / CT) : 0;
 }
 
-// gridDim.x workgroups, each an equal contiguous share of the flat chunk
+// gridDim.x * 4 wavefronts, each an equal contiguous share of the flat chunk
 // sequence ordered (request, kv head / pass, chunk).  prefix[] (dynamic LDS,
 // batch + 1 ints) holds the running chunk count per request; every workgroup
 // computes it for itself from ctx_lens / running (a few hundred loads that hit
@@ -618,7 +600,6 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
 {
     constexpr int D = R::D, CT = R::CT;
     extern __shared__ int prefix[];
-    __shared__ typename R::Smem sm;
     __shared__ int wave_total[kWaves];
 
     const int B = a.batch;
@@ -654,11 +635,21 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     const int passes = G / GH;
     const int HC = a.num_kv_heads * passes;
     const long long total = (long long)HC * prefix[B];
-    if (blockIdx.x == 0)                              // the merge kernel reads it back
-        for (int i = tid; i <= B; i += kThreads) a.chunk_prefix[i] = prefix[i];
-    const long long x_begin = (long long)blockIdx.x * total / gridDim.x;
-    const long long x_end = (long long)(blockIdx.x + 1) * total / gridDim.x;
-    if (x_begin >= x_end) return;
+    // from here on every wave is on its own: no barrier below
+    const int share = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(wv);
+    const int P = gridDim.x * kWaves;
+    if (tid == 0 && blockIdx.x == 0) {                // the merge kernel reads the total back
+        a.share_info[P] = make_int4((int)(total & 0xFFFFFFFFll), (int)(total >> 32), 0, 0);
+    }
+    // What the merge kernel needs to know about this share: the (request, head)
+    // range it starts but does not finish, if any (only its last range can be one).
+    int4 owned = make_int4(0, 0, 0, 0);
+    const long long x_begin = (long long)share * total / P;
+    const long long x_end = (long long)(share + 1) * total / P;
+    if (x_begin >= x_end) {
+        if (lane == 0) a.share_info[share] = owned;
+        return;
+    }
 
     // request that holds position x_begin: the last r with HC * prefix[r] <= x_begin
     int lo = 0, hi = B;
@@ -679,21 +670,23 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
         const int h0 = g * G + (hc % passes) * GH;
         const bool whole = (c0 == 0 && len == nr);
         // a share's first range goes to slot 0, a later partial one (its last) to slot 1
-        float *slot = a.partials + ((size_t)blockIdx.x * 2 + (x == x_begin ? 0 : 1)) * GH * (D + 2);
+        float *slot = a.partials + ((size_t)share * 2 + (x == x_begin ? 0 : 1)) * GH * (D + 2);
         const size_t rh0 = (size_t)r * a.num_q_heads + h0;
-        R::run(a, r, g, h0, GH, c0 * CT, min(C, (c0 + len) * CT), sm,
+        R::run(a, r, g, h0, GH, c0 * CT, min(C, (c0 + len) * CT),
                [&](int h, int d, float M, float L, float A) {
                    if (whole)
                        store_out<R::kBF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
                    else
                        store_partial(slot + (size_t)h * (D + 2), D, d, M, L, A);
                });
+        if (c0 == 0 && len < nr) owned = make_int4(r, hc, nr, base);
         x += len;
         if (c0 + len == nr && hc == HC - 1) {         // request finished: next one with work
             ++r;
             while (r < B && prefix[r + 1] == prefix[r]) ++r;
         }
     }
+    if (lane == 0) a.share_info[share] = owned;
 }
 
 // Position x of the flat chunk sequence belongs to the share w with
@@ -704,26 +697,28 @@ __device__ __forceinline__ long long share_of(long long x, long long total, int 
 }
 
 // Merges the pieces of every (request, kv head / pass) that was split over
-// several shares, in share order (= token order).  grid = (kv heads * passes,
-// batch, slices of 256 (head, dim) outputs); one output per thread.
+// several shares, in share order (= token order).  One block per share and slice
+// of 256 (head, dim) outputs: the share that holds the start of a split range
+// merges it (most blocks find nothing to do and leave after one load).
 template <bool BF16>
 __global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a, int P)
 {
-    const int r = blockIdx.y, hc = blockIdx.x;
+    const int4 owned = a.share_info[blockIdx.x];
+    const int nr = owned.z;
+    if (nr == 0) return;
+    const int r = owned.x, hc = owned.y, base = owned.w;
     const int D = a.head_dim;
     const int G = a.num_q_heads / a.num_kv_heads;
     const int GH = a.heads_per_pass;
     const int passes = G / GH;
     const int HC = a.num_kv_heads * passes;
-    const int base = a.chunk_prefix[r], nr = a.chunk_prefix[r + 1] - base;
-    if (nr == 0) return;                              // not running: row untouched
-    const long long total = (long long)HC * a.chunk_prefix[a.batch];
+    const int4 tot = a.share_info[P];
+    const long long total = ((long long)tot.y << 32) | (unsigned int)tot.x;
     const long long off = (long long)HC * base + (long long)hc * nr;
-    const int w_first = (int)share_of(off, total, P), w_last = (int)share_of(off + nr - 1, total, P);
-    if (w_first == w_last) return;                    // one share held it all and wrote the result
+    const int w_first = blockIdx.x, w_last = (int)share_of(off + nr - 1, total, P);
     const int g = hc / passes;
     const size_t rh0 = (size_t)r * a.num_q_heads + g * G + (hc % passes) * GH;
-    const int idx = blockIdx.z * 256 + threadIdx.x;
+    const int idx = blockIdx.y * 256 + threadIdx.x;
     const bool live = idx < GH * D;
     const int h = live ? idx / D : 0, d = live ? idx % D : 0;
     // The pieces' slots are worked out once per block (64-bit divisions), kMergeList
@@ -776,7 +771,8 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
     const int G = a.num_q_heads / a.num_kv_heads;
     const int HC = a.num_kv_heads * (G / a.heads_per_pass);
     if (a.part_tokens > 0) {
-        dim3 grid((unsigned)((size_t)a.max_parts * HC * a.batch));
+        const long long items = (long long)a.max_parts * HC * a.batch;
+        dim3 grid((unsigned)((items + kWaves - 1) / kWaves));
         hipLaunchKernelGGL(decode_partial<R>, grid, dim3(kThreads), 0, s, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess || a.max_parts == 1) return e;
@@ -784,7 +780,8 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
                            s, a);
         return hipGetLastError();
     }
-    // balanced: as many workgroups as the chip holds at once for this kernel
+    // balanced: as many workgroups as the chip holds at once for this kernel (fewer
+    // if the partial slots of that many wave shares would not fit the workspace)
     static int resident = 0;                          // per instantiation; one device per process
     if (resident == 0) {
         int dev = 0, cus = 0, per_cu = 0;
@@ -796,15 +793,15 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
         if (cus < 1 || per_cu < 1) return hipErrorInvalidValue;
         resident = cus * per_cu;
-        if (resident > kMaxShares) resident = kMaxShares;
     }
+    const int wgs = min(resident, decode_max_shares(a.heads_per_pass, a.head_dim) / kWaves);
     const size_t lds = (size_t)(a.batch + 1) * sizeof(int);
-    hipLaunchKernelGGL(decode_balanced<R>, dim3(resident), dim3(kThreads), lds, s, a);
+    hipLaunchKernelGGL(decode_balanced<R>, dim3(wgs), dim3(kThreads), lds, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int slices = (a.heads_per_pass * a.head_dim + 255) / 256;
-    hipLaunchKernelGGL(decode_merge_balanced<R::kBF16>, dim3(HC, a.batch, slices), dim3(256), 0, s, a,
-                       resident);
+    hipLaunchKernelGGL(decode_merge_balanced<R::kBF16>, dim3(wgs * kWaves, slices), dim3(256), 0, s, a,
+                       wgs * kWaves);
     return hipGetLastError();
 }
 
@@ -822,12 +819,8 @@ hipError_t launch_valu(const DecodeArgs &a, hipStream_t s)
 template <int D>
 hipError_t launch_mfma(const DecodeArgs &a, hipStream_t s)
 {
-    const int gh = a.heads_per_pass;
-    if (gh <= 2) return launch_one<MfmaReducer<D, 2>>(a, s);
-    if (gh <= 4) return launch_one<MfmaReducer<D, 4>>(a, s);
-    if (gh <= 8) return launch_one<MfmaReducer<D, 8>>(a, s);
-    if (gh <= 16) return launch_one<MfmaReducer<D, 16>>(a, s);
-    return hipErrorInvalidValue;
+    if (a.heads_per_pass > 16) return hipErrorInvalidValue;
+    return launch_one<MfmaReducer<D>>(a, s);
 }
 
 }  // namespace
@@ -848,7 +841,13 @@ int decode_heads_per_pass(int bf16, int head_dim, int group)
     return 1;
 }
 
-int decode_max_shares() { return kMaxShares; }
+int decode_max_shares(int heads_per_pass, int head_dim)
+{
+    const size_t per_share = (size_t)2 * heads_per_pass * (head_dim + 2) * sizeof(float);
+    size_t n = kPartialBudget / per_share;
+    if (n > (size_t)kMaxShares) n = kMaxShares;
+    return (int)(n / kWaves) * kWaves;
+}
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
 {

@@ -14,8 +14,8 @@ struct DecodeArgs {
     const int32_t *ctx_lens;     // [batch]
     const uint8_t *running;      // [batch]
     float *partials;          // fixed partitions: [batch][H][max_parts][D + 2];
-                              // balanced: [share][2][heads per group][D + 2]
-    int32_t *chunk_prefix;    // balanced: [batch + 1] running chunk count per request
+                              // balanced: [wave share][2][heads per pass][D + 2]
+    int4 *share_info;         // balanced: [shares + 1] what each share leaves to the merge kernel
     void *out;                // [batch][H][D]
     int32_t batch, max_batch, layer, num_layers, num_q_heads, num_kv_heads, head_dim;
     int32_t block_size, log2_block_size, max_blocks, part_tokens, max_parts;
@@ -30,8 +30,9 @@ int decode_heads_per_pass(int bf16, int head_dim, int group);
 // Nonzero if the geometry's pools use the tiled (MFMA operand) layout.
 int decode_uses_tiled_layout(int bf16, int group);
 
-// Most workgroups ("shares") the balanced scheme launches; sizes its partials.
-int decode_max_shares();
+// Most wavefront shares the balanced scheme uses for a geometry (a multiple of
+// 4); its partials are [shares][2][heads_per_pass][head_dim + 2] floats.
+int decode_max_shares(int heads_per_pass, int head_dim);
 
 // Enqueues one layer of decode attention.  part_tokens == 0 selects the balanced
 // scheme (then max_parts is ignored), part_tokens > 0 fixed partitions; either

@@ -68,9 +68,9 @@ const char *derive(const lamps_config *c, Derived *d)
         d->partial_bytes = (size_t)c->max_batch * c->num_q_heads * d->max_parts * (c->head_dim + 2) * 4;
     } else {
         d->max_parts = 0;
-        d->partial_bytes = (size_t)lamps::decode_max_shares() * 2 * gh * (c->head_dim + 2) * 4;
+        d->partial_bytes = (size_t)lamps::decode_max_shares(gh, c->head_dim) * 2 * gh * (c->head_dim + 2) * 4;
     }
-    d->prefix_bytes = (size_t)(c->max_batch + 1) * sizeof(int32_t);
+    d->prefix_bytes = (size_t)(lamps::decode_max_shares(gh, c->head_dim) + 1) * 16;   // share_info
     if (c->staging_bytes < 0) return "staging_bytes is negative";
     size_t st = c->staging_bytes ? (size_t)c->staging_bytes : (size_t)64 << 20;
     if (c->staging_bytes == 0 && st < d->block_bytes) st = d->block_bytes;
@@ -101,7 +101,7 @@ struct lamps_ctx {
     Derived d;
     char *k_pool, *v_pool;
     float *partials;
-    int32_t *chunk_prefix;
+    int4 *share_info;
     char *stage_out, *stage_in;
     hipStream_t cs, os, is;
 
@@ -342,7 +342,7 @@ int lamps_create(const lamps_config *cfg, void *k_pool, void *v_pool, void *work
     c->v_pool = static_cast<char *>(v_pool);
     char *ws = static_cast<char *>(workspace);
     c->partials = reinterpret_cast<float *>(ws);
-    c->chunk_prefix = reinterpret_cast<int32_t *>(ws + align256(d.partial_bytes));
+    c->share_info = reinterpret_cast<int4 *>(ws + align256(d.partial_bytes));
     c->stage_out = ws + align256(d.partial_bytes) + align256(d.prefix_bytes);
     c->stage_in = c->stage_out + align256(d.staging_bytes);
     c->cs = static_cast<hipStream_t>(compute_stream);
@@ -396,7 +396,7 @@ int lamps_decode_attn(lamps_ctx *c, int32_t layer, int32_t batch, const void *q,
     a.ctx_lens = ctx_lens;
     a.running = running_mask;
     a.partials = c->partials;
-    a.chunk_prefix = c->chunk_prefix;
+    a.share_info = c->share_info;
     a.max_batch = c->cfg.max_batch;
     a.out = out;
     a.batch = batch;
