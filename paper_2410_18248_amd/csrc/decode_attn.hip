@@ -56,6 +56,7 @@ constexpr int kHalves = 2;              // half-chunks per chunk on the 1-2 head
 constexpr float kLowest = -3.0e38f;     // finite stand-in for "no score seen yet"
 constexpr int kMaxShares = 16384;       // most wave shares the balanced scheme ever uses
 constexpr size_t kPartialBudget = (size_t)64 << 20;   // bytes of partial slots it may need
+constexpr int kShareOwner = 1, kShareSlot1 = 2, kShareEmpty = 4;   // flags in share_info[].w
 constexpr int kMergeList = 64;          // pieces whose slots are resolved per pass of the balanced merge
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -583,6 +584,13 @@ __global__ void decode_merge(const DecodeArgs a)
 
 // ---------------------------------------------------------------- balanced shares
 
+// Position x of the flat chunk sequence belongs to the share w with
+// floor(w * total / P) <= x < floor((w + 1) * total / P).
+__device__ __forceinline__ long long share_of(long long x, long long total, int P)
+{
+    return ((x + 1) * P - 1) / total;
+}
+
 // Chunks a running request contributes per (kv head, pass): an empty context
 // still gets one (empty) chunk so that its zero row is written.
 __device__ __forceinline__ int chunks_of(int running, int C, int CT)
@@ -638,16 +646,15 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     // from here on every wave is on its own: no barrier below
     const int share = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(wv);
     const int P = gridDim.x * kWaves;
-    if (tid == 0 && blockIdx.x == 0) {                // the merge kernel reads the total back
-        a.share_info[P] = make_int4((int)(total & 0xFFFFFFFFll), (int)(total >> 32), 0, 0);
-    }
-    // What the merge kernel needs to know about this share: the (request, head)
-    // range it starts but does not finish, if any (only its last range can be one).
+    // What the merge kernel needs to know about this share: whether it is empty,
+    // and the (request, head) range it starts but does not finish, if any (only
+    // its last range can be one): request, head/pass, last share of the range,
+    // and the slot this share's piece went to.
     int4 owned = make_int4(0, 0, 0, 0);
     const long long x_begin = (long long)share * total / P;
     const long long x_end = (long long)(share + 1) * total / P;
     if (x_begin >= x_end) {
-        if (lane == 0) a.share_info[share] = owned;
+        if (lane == 0) a.share_info[share] = make_int4(0, 0, 0, kShareEmpty);
         return;
     }
 
@@ -679,7 +686,9 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
                    else
                        store_partial(slot + (size_t)h * (D + 2), D, d, M, L, A);
                });
-        if (c0 == 0 && len < nr) owned = make_int4(r, hc, nr, base);
+        if (c0 == 0 && len < nr)
+            owned = make_int4(r, hc, (int)share_of(x + nr - 1, total, P),
+                              kShareOwner | (x == x_begin ? 0 : kShareSlot1));
         x += len;
         if (c0 + len == nr && hc == HC - 1) {         // request finished: next one with work
             ++r;
@@ -689,50 +698,37 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     if (lane == 0) a.share_info[share] = owned;
 }
 
-// Position x of the flat chunk sequence belongs to the share w with
-// floor(w * total / P) <= x < floor((w + 1) * total / P).
-__device__ __forceinline__ long long share_of(long long x, long long total, int P)
-{
-    return ((x + 1) * P - 1) / total;
-}
-
 // Merges the pieces of every (request, kv head / pass) that was split over
 // several shares, in share order (= token order).  One block per share and slice
 // of 256 (head, dim) outputs: the share that holds the start of a split range
 // merges it (most blocks find nothing to do and leave after one load).
 template <bool BF16>
-__global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a, int P)
+__global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a)
 {
     const int4 owned = a.share_info[blockIdx.x];
-    const int nr = owned.z;
-    if (nr == 0) return;
-    const int r = owned.x, hc = owned.y, base = owned.w;
+    if (!(owned.w & kShareOwner)) return;
+    const int r = owned.x, hc = owned.y;
     const int D = a.head_dim;
     const int G = a.num_q_heads / a.num_kv_heads;
     const int GH = a.heads_per_pass;
     const int passes = G / GH;
-    const int HC = a.num_kv_heads * passes;
-    const int4 tot = a.share_info[P];
-    const long long total = ((long long)tot.y << 32) | (unsigned int)tot.x;
-    const long long off = (long long)HC * base + (long long)hc * nr;
-    const int w_first = blockIdx.x, w_last = (int)share_of(off + nr - 1, total, P);
+    const int w_first = blockIdx.x, w_last = owned.z;
     const int g = hc / passes;
     const size_t rh0 = (size_t)r * a.num_q_heads + g * G + (hc % passes) * GH;
     const int idx = blockIdx.y * 256 + threadIdx.x;
     const bool live = idx < GH * D;
     const int h = live ? idx / D : 0, d = live ? idx % D : 0;
-    // The pieces' slots are worked out once per block (64-bit divisions), kMergeList
-    // at a time; each list is then reduced eight pieces at a time.
+    // The pieces' slots are looked up once per block, kMergeList at a time; each list
+    // is then reduced eight pieces at a time.
     __shared__ int piece[kMergeList];
     float M = kLowest, L = 0.0f, A = 0.0f;
     for (int w0 = w_first; w0 <= w_last; w0 += kMergeList) {
         const int cnt = min(kMergeList, w_last - w0 + 1);
         __syncthreads();
         if ((int)threadIdx.x < cnt) {
-            const int w = w0 + threadIdx.x;
-            const long long xb = (long long)w * total / P;
-            piece[threadIdx.x] = xb >= (long long)(w + 1) * total / P ? -1      // empty share
-                                                                      : w * 2 + (xb >= off ? 0 : 1);
+            const int w = w0 + threadIdx.x;        // the first share knows its slot; later ones start
+            const int f = w == w_first ? owned.w : a.share_info[w].w;   // inside the range: slot 0
+            piece[threadIdx.x] = (f & kShareEmpty) ? -1 : w * 2 + ((w == w_first && (f & kShareSlot1)) ? 1 : 0);
         }
         __syncthreads();
         for (int i0 = 0; i0 < cnt; i0 += 8) {          // share order = token order
@@ -800,8 +796,7 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int slices = (a.heads_per_pass * a.head_dim + 255) / 256;
-    hipLaunchKernelGGL(decode_merge_balanced<R::kBF16>, dim3(wgs * kWaves, slices), dim3(256), 0, s, a,
-                       wgs * kWaves);
+    hipLaunchKernelGGL(decode_merge_balanced<R::kBF16>, dim3(wgs * kWaves, slices), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
