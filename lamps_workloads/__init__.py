@@ -283,7 +283,7 @@ def workload(cfg, rep=0, num_blocks=None):
                 break
             st[r] = SWAP
             covered += nb[r]
-        return Workload("cfg3-long-gqa-bf16", g, B, ctx, st, part_tokens=512)
+        return Workload("cfg3-long-gqa-bf16", g, B, ctx, st)
     if cfg == 4:
         B = 512
         ctx = ctx_zipf_rank(seed + 1, B, 1.2, 64, 4096)

@@ -215,7 +215,7 @@ def _full_size(cfg, sample_requests, rep=0, part_tokens=None):
     return worst
 
 
-@pytest.mark.parametrize("cfg,sample,part", [(1, 6, None), (2, 8, None), (3, 2, None), (3, 2, 0),
+@pytest.mark.parametrize("cfg,sample,part", [(1, 6, None), (2, 8, None), (3, 2, None), (3, 2, 512),
                                              (1, 4, 512), (2, 6, 1024)])
 def test_full_size_sampled_parity(cfg, sample, part):
     """Configurations 1-3 at full size in the bench's launch configuration
