@@ -249,12 +249,21 @@ struct ValuReducer {
                 if (pb[f] >= 0) {              // wave-uniform: half-chunks past the context are skipped
                     const size_t off = (size_t)pb[f] * block_stride +
                                        (size_t)((t0 + f * HT) & (a.block_size - 1)) * D * ES;
+                    if (t0 + (f + 1) * HT <= t_end) {
 #pragma unroll
-                    for (int i = 0; i < kLoads; ++i)
-                        kx[f * kLoads + i] = load_stream16(kp + off + i * 1024);
+                        for (int i = 0; i < kLoads; ++i)
+                            kx[f * kLoads + i] = load_stream16(kp + off + i * 1024);
 #pragma unroll
-                    for (int i = 0; i < kLoads; ++i)
-                        vx[f * kLoads + i] = load_stream16(vp + off + i * 1024);
+                        for (int i = 0; i < kLoads; ++i)
+                            vx[f * kLoads + i] = load_stream16(vp + off + i * 1024);
+                    } else {                   // the context ends inside: loads wholly past it are skipped too
+#pragma unroll
+                        for (int i = 0; i < kLoads; ++i) {
+                            const bool in = t0 + f * HT + i * TPW < t_end;
+                            kx[f * kLoads + i] = in ? load_stream16(kp + off + i * 1024) : make_uint4(0, 0, 0, 0);
+                            vx[f * kLoads + i] = in ? load_stream16(vp + off + i * 1024) : make_uint4(0, 0, 0, 0);
+                        }
+                    }
                 } else {
 #pragma unroll
                     for (int i = 0; i < kLoads; ++i) {
@@ -805,8 +814,12 @@ hipError_t launch_valu(const DecodeArgs &a, hipStream_t s)
 {
     switch (a.heads_per_pass) {
     case 1: return launch_one<ValuReducer<BF16, LPT, 1, kHalves>>(a, s);
-    case 2: if (!BF16) return launch_one<ValuReducer<BF16, LPT, 2, kHalves>>(a, s); break;
-    case 4: if (!BF16) return launch_one<ValuReducer<BF16, LPT, 4, 1>>(a, s); break;
+    case 2:
+        if constexpr (!BF16) return launch_one<ValuReducer<BF16, LPT, 2, kHalves>>(a, s);
+        break;                                 // grouped bf16 heads take the MFMA path
+    case 4:
+        if constexpr (!BF16) return launch_one<ValuReducer<BF16, LPT, 4, 1>>(a, s);
+        break;
     }
     return hipErrorInvalidValue;
 }
