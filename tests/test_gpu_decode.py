@@ -44,6 +44,14 @@ CASES = [
     ("bf16", 4, 4, 64, 16, 32, [3, 50, 96]),
     ("bf16", 6, 3, 256, 16, 48, [20, 77]),
     ("bf16", 10, 2, 128, 16, 32, [90, 11]),
+    # grouped bf16 heads (matrix-core path): group sizes 2..32, all head dims, larger blocks
+    ("bf16", 8, 2, 64, 16, 32, [1, 16, 17, 100, 0]),
+    ("bf16", 4, 2, 256, 16, 64, [33, 5]),
+    ("bf16", 32, 1, 128, 16, 64, [70, 129]),          # 32 heads per kv head: two passes of 16
+    ("bf16", 6, 2, 128, 64, 128, [63, 64, 65, 200]),
+    ("bf16", 16, 1, 128, 32, 0, [31, 300]),
+    ("bf16", 12, 2, 64, 16, 0, [15, 47, 2]),
+    ("f32", 8, 2, 64, 16, 48, [100, 3, 49]),          # fp32 groups stay on the vector ALUs
 ]
 
 
@@ -255,4 +263,27 @@ def test_cfg4_full_size_layers_sampled():
             ref = oracle.decode_attn(qn[r:r + 1], [k], [v], [C], [1], threads=8)
             assert np.abs(got[r] - ref[0]).max() <= 2e-2, (layer, r)
         assert (got[running == 0] == 3.0).all()
+    rig.close()
+
+
+@pytest.mark.parametrize("dtype,H,Hkv", [("bf16", 4, 4), ("bf16", 8, 2), ("f32", 4, 2)])
+def test_large_batch_of_short_requests(dtype, H, Hkv):
+    """More requests than threads in a workgroup (the chunk-count scan then takes
+    several requests per thread), most of them short, some empty, some paused."""
+    B = 700
+    seed = 909
+    ctx = (W.splitmix64(seed, B) % np.uint64(70)).astype(np.int64)       # 0..69 tokens
+    ctx[::97] = 0
+    running = np.ones(B, dtype=np.uint8)
+    running[::13] = 0
+    geom = W.Geometry(1, H, Hkv, 64 if dtype == "f32" else 128, 16,
+                      int(sum((c + 15) // 16 for c in ctx)) + 3, 5, dtype)
+    rig, table, q, K, V = _setup(seed, geom, ctx.tolist())
+    out = rig.decode(0, q, table, ctx, running, sentinel=2.5)
+    ref = oracle.decode_attn(q, K, V, ctx, running, threads=8)
+    got = to_f64(out)
+    live = running == 1
+    assert np.abs(got[live] - ref[live]).max() <= tol(geom)
+    assert (got[~live] == 2.5).all()
+    assert (got[live & (ctx == 0)] == 0).all()
     rig.close()
