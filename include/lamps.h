@@ -146,6 +146,32 @@ int lamps_decode_attn(lamps_ctx *ctx, int32_t layer, int32_t batch, const void *
                       const int32_t *block_table, const int32_t *ctx_lens,
                       const uint8_t *running_mask, void *out);
 
+/* ---- KV append: the cache grows by one position per iteration (Section 2.2.1) ---- */
+
+/* One layer of one iteration, enqueued on the compute stream; returns at once.
+ * For every request r < batch with running_mask[r] != 0, writes the key and
+ * value vectors of the token being generated, k_new[r] and v_new[r], at cached
+ * position ctx_lens[r] of layer `layer`: slot ctx_lens[r] % block_size of
+ * physical block block_table[r][ctx_lens[r] / block_size], in the pools' tile
+ * layout.  The caller has put an allocated block in that table entry (a new
+ * one whenever ctx_lens[r] is a multiple of block_size; after
+ * lamps_compute_wait_blocks if the block may still be the source of a
+ * swap-out).  With advance != 0, ctx_lens[r] of the running requests is then
+ * incremented on the device (pass it on the last layer of the iteration, and
+ * follow with lamps_decode_attn over the grown cache, or append after
+ * attention -- whether a token attends to itself is the caller's reading of
+ * Section 2.2).  Requests with running_mask[r] == 0 append nothing and keep
+ * their length.  A position outside the table row or a block id outside the
+ * pool writes nothing (device arguments are not validated on the host).
+ *   k_new, v_new  device, [batch][H_kv][d_h] dtype
+ *   block_table   device, int32 [batch][max_blocks_per_req]
+ *   ctx_lens      device, int32 [batch], read and (with advance) written
+ *   running_mask  device, uint8 [batch]
+ * Errors: INVALID (null), RANGE (layer, batch). */
+int lamps_kv_append(lamps_ctx *ctx, int32_t layer, int32_t batch, const void *k_new,
+                    const void *v_new, const int32_t *block_table, int32_t *ctx_lens,
+                    const uint8_t *running_mask, int32_t advance);
+
 /* ---- Swap handling strategy (Section 1; Section 4.2) ---- */
 
 /* Copies the n listed blocks (all layers, keys and values) into host_buf

@@ -8,6 +8,9 @@ imports it, and it never imports the product package.
                   (C source in ``lamps_oracle.c``).
 ``blocks``     -- byte-exact model of the Swap / Discard / Preserve handling
                   strategies (Section 1, Section 4.2) on a block pool.
+``cache``      -- the logical KV cache growing by one position per iteration
+                  (Section 2.2.1), for the append step.
 """
 from .attention import build, decode_attn, max_threads, widen  # noqa: F401
 from .blocks import AllocatorModel, PoolModel, kv_bytes_per_token  # noqa: F401
+from .cache import LogicalCache  # noqa: F401

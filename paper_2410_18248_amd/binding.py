@@ -67,6 +67,7 @@ def load_library():
         "lamps_create": [cfgp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)],
         "lamps_destroy": [vp],
         "lamps_decode_attn": [vp, i32, i32, vp, vp, vp, vp, vp],
+        "lamps_kv_append": [vp, i32, i32, vp, vp, vp, vp, vp, i32],
         "lamps_swap_out": [vp, vp, i32, vp, ctypes.POINTER(u64)],
         "lamps_swap_in": [vp, vp, vp, i32, ctypes.POINTER(u64)],
         "lamps_ticket_query": [vp, u64],
@@ -154,6 +155,11 @@ class Lamps:
     def decode_attn(self, layer, batch, q, block_table, ctx_lens, running_mask, out):
         self._check(self.lib.lamps_decode_attn(self.h, layer, batch, _ptr(q), _ptr(block_table),
                                                _ptr(ctx_lens), _ptr(running_mask), _ptr(out)))
+
+    def kv_append(self, layer, batch, k_new, v_new, block_table, ctx_lens, running_mask, advance):
+        self._check(self.lib.lamps_kv_append(self.h, layer, batch, _ptr(k_new), _ptr(v_new),
+                                             _ptr(block_table), _ptr(ctx_lens), _ptr(running_mask),
+                                             1 if advance else 0))
 
     def swap_out(self, block_ids, host_buf):
         arr, n = _ids(block_ids)

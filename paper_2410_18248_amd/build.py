@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblamps.so")
-SOURCES = ["decode_attn.hip", "block_copy.hip", "lamps.cpp"]
+SOURCES = ["decode_attn.hip", "block_copy.hip", "kv_append.hip", "lamps.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

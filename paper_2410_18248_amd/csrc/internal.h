@@ -39,6 +39,19 @@ int decode_max_shares(int heads_per_pass, int head_dim);
 // way a small merge kernel follows unless no request can be split.
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
 
+struct AppendArgs {
+    const void *k_new, *v_new;   // [batch][H_kv][D]
+    void *k_pool, *v_pool;
+    const int32_t *block_table;  // [batch][max_blocks]
+    int32_t *ctx_lens;           // [batch]; incremented for running requests if advance
+    const uint8_t *running;      // [batch]
+    int32_t batch, layer, num_layers, num_kv_heads, head_dim, block_size, log2_block_size;
+    int32_t max_blocks, num_blocks, bf16, advance;
+};
+
+// Enqueues the append of one new position per running request in one layer.
+hipError_t launch_kv_append(const AppendArgs &a, int tiled, hipStream_t stream);
+
 // Gather: staging image i (key bytes then value bytes of block ids[i]) <- pools.
 // Scatter: the reverse.  `half_bytes` = bytes of one block in one pool, a
 // multiple of 16.  `ids` must be readable by the device.

@@ -417,6 +417,42 @@ int lamps_decode_attn(lamps_ctx *c, int32_t layer, int32_t batch, const void *q,
     return LAMPS_OK;
 }
 
+int lamps_kv_append(lamps_ctx *c, int32_t layer, int32_t batch, const void *k_new,
+                    const void *v_new, const int32_t *block_table, int32_t *ctx_lens,
+                    const uint8_t *running_mask, int32_t advance)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!k_new || !v_new || !block_table || !ctx_lens || !running_mask)
+        return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append: null argument");
+    if (layer < 0 || layer >= c->cfg.num_layers)
+        return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append: layer out of range");
+    if (batch < 0 || batch > c->cfg.max_batch)
+        return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append: batch out of range");
+    if (batch == 0) return LAMPS_OK;
+    lamps::AppendArgs a;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.k_pool = c->k_pool;
+    a.v_pool = c->v_pool;
+    a.block_table = block_table;
+    a.ctx_lens = ctx_lens;
+    a.running = running_mask;
+    a.batch = batch;
+    a.layer = layer;
+    a.num_layers = c->cfg.num_layers;
+    a.num_kv_heads = c->cfg.num_kv_heads;
+    a.head_dim = c->cfg.head_dim;
+    a.block_size = c->cfg.block_size;
+    a.log2_block_size = c->d.log2_bs;
+    a.max_blocks = c->cfg.max_blocks_per_req;
+    a.num_blocks = c->cfg.num_blocks;
+    a.bf16 = c->cfg.dtype == LAMPS_BF16;
+    a.advance = advance != 0;
+    const int tiled = lamps::decode_uses_tiled_layout(a.bf16, c->cfg.num_q_heads / c->cfg.num_kv_heads);
+    LAMPS_HIP(lamps::launch_kv_append(a, tiled, c->cs));
+    return LAMPS_OK;
+}
+
 int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host_buf,
                    uint64_t *ticket)
 {
