@@ -10,7 +10,10 @@ imports it, and it never imports the product package.
                   strategies (Section 1, Section 4.2) on a block pool.
 ``cache``      -- the logical KV cache growing by one position per iteration
                   (Section 2.2.1), for the append step.
+``scheduler``  -- equations (1)-(3), the memory-over-time rank and Algorithm 1
+                  as a plain iteration-level simulation.
 """
 from .attention import build, decode_attn, max_threads, widen  # noqa: F401
 from .blocks import AllocatorModel, PoolModel, kv_bytes_per_token  # noqa: F401
 from .cache import LogicalCache  # noqa: F401
+from . import scheduler  # noqa: F401
