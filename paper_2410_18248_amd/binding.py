@@ -81,10 +81,133 @@ def load_library():
     for name, args in sig.items():
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = args
+    _sched_signatures(lib)
     lib.lamps_last_error.restype = ctypes.c_char_p
     lib.lamps_last_error.argtypes = [vp]
     _lib = lib
     return lib
+
+
+# ---------------------------------------------------------------- scheduler (lamps_sched.h)
+LAMPS_PRESERVE, LAMPS_DISCARD, LAMPS_SWAP, LAMPS_HANDLING_AUTO = 0, 1, 2, -1
+LAMPS_POLICY_FCFS, LAMPS_POLICY_SJF, LAMPS_POLICY_SJF_TOTAL, LAMPS_POLICY_LAMPS, LAMPS_POLICY_FIXED = range(5)
+
+
+class LampsCostModel(ctypes.Structure):
+    _fields_ = [("it_a", ctypes.c_double), ("it_b", ctypes.c_double), ("fwd_a", ctypes.c_double),
+                ("fwd_b", ctypes.c_double), ("sw_a", ctypes.c_double), ("sw_b", ctypes.c_double),
+                ("swap_stalls", ctypes.c_int32), ("unit", ctypes.c_int32)]
+
+
+class LampsSchedConfig(ctypes.Structure):
+    _fields_ = [("policy", ctypes.c_int32), ("max_batch", ctypes.c_int32),
+                ("memory_tokens", ctypes.c_int64), ("starvation_threshold", ctypes.c_int32),
+                ("score_refresh", ctypes.c_int32), ("recompute_chunk", ctypes.c_int64),
+                ("c_other", ctypes.c_double), ("bytes_per_token", ctypes.c_double),
+                ("cost", LampsCostModel)]
+
+
+class LampsSegment(ctypes.Structure):
+    _fields_ = [("n_out", ctypes.c_int32), ("api_duration", ctypes.c_double),
+                ("api_response", ctypes.c_int32), ("handling", ctypes.c_int32)]
+
+
+class LampsBatchEntry(ctypes.Structure):
+    _fields_ = [("id", ctypes.c_int64), ("swap_in", ctypes.c_int64), ("recompute", ctypes.c_int64),
+                ("context", ctypes.c_int64)]
+
+
+class LampsSchedEvent(ctypes.Structure):
+    _fields_ = [("id", ctypes.c_int64), ("what", ctypes.c_int32), ("handling", ctypes.c_int32),
+                ("context", ctypes.c_int64)]
+
+
+def _sched_signatures(lib):
+    d, i32, i64, vp = ctypes.c_double, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+    P = ctypes.POINTER
+    for name, args in (("lamps_waste_preserve", [d, d, d]), ("lamps_waste_discard", [d, d, d, d]),
+                       ("lamps_waste_swap", [d, d, d]),
+                       ("lamps_memory_over_time", [ctypes.c_int, i64, i64, d, i64, i64, d, d, d]),
+                       ("lamps_sched_now", [vp])):
+        getattr(lib, name).restype = d
+        getattr(lib, name).argtypes = args
+    for name, args in (("lamps_handling_strategy", [d, d, d, d, d, d]),
+                       ("lamps_sched_create", [P(LampsSchedConfig), P(vp)]),
+                       ("lamps_sched_destroy", [vp]),
+                       ("lamps_sched_add", [vp, i64, d, i32, P(LampsSegment), i32, d]),
+                       ("lamps_sched_next_batch", [vp, P(LampsBatchEntry), i32, P(i32)]),
+                       ("lamps_sched_commit", [vp, d, P(LampsSchedEvent), i32, P(i32)]),
+                       ("lamps_sched_run", [vp]),
+                       ("lamps_sched_result", [vp, i64, P(d), P(d), P(i32), i32]),
+                       ("lamps_sched_stats", [vp, P(i64), P(i64), P(i64)])):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = args
+
+
+class LampsSched:
+    """One ``lamps_sched``.  Methods carry the C names without the prefix."""
+
+    def __init__(self, cfg):
+        self.lib = load_library()
+        self.cfg = cfg
+        h = ctypes.c_void_p()
+        rc = self.lib.lamps_sched_create(ctypes.byref(cfg), ctypes.byref(h))
+        if rc != 0:
+            raise LampsError(rc, "lamps_sched_create")
+        self.h = h
+        self._batch = (LampsBatchEntry * cfg.max_batch)()
+        self._events = (LampsSchedEvent * cfg.max_batch)()
+
+    def _check(self, rc, what):
+        if rc < 0:
+            raise LampsError(rc, what)
+        return rc
+
+    def destroy(self):
+        if self.h:
+            self.lib.lamps_sched_destroy(self.h)
+            self.h = None
+
+    def add(self, rid, arrival, prompt_tokens, segments, priority=0.0):
+        """segments: [(n_out, api_duration or None, api_response, handling or None), ...]"""
+        arr = (LampsSegment * len(segments))()
+        for k, sg in enumerate(segments):
+            n_out, api, rho = sg[0], sg[1], sg[2]
+            h = sg[3] if len(sg) > 3 and sg[3] is not None else LAMPS_HANDLING_AUTO
+            arr[k] = LampsSegment(n_out, -1.0 if api is None else api, rho, h)
+        self._check(self.lib.lamps_sched_add(self.h, rid, arrival, prompt_tokens, arr, len(segments),
+                                             priority), "lamps_sched_add")
+
+    def next_batch(self):
+        n = ctypes.c_int32()
+        self._check(self.lib.lamps_sched_next_batch(self.h, self._batch, len(self._batch),
+                                                    ctypes.byref(n)), "lamps_sched_next_batch")
+        return [(b.id, b.swap_in, b.recompute, b.context) for b in self._batch[:n.value]]
+
+    def commit(self, iteration_time=-1.0):
+        n = ctypes.c_int32()
+        self._check(self.lib.lamps_sched_commit(self.h, iteration_time, self._events,
+                                                len(self._events), ctypes.byref(n)), "lamps_sched_commit")
+        return [(e.id, e.what, e.handling, e.context) for e in self._events[:n.value]]
+
+    def run(self):
+        self._check(self.lib.lamps_sched_run(self.h), "lamps_sched_run")
+
+    def now(self):
+        return self.lib.lamps_sched_now(self.h)
+
+    def result(self, rid, n_segments=1):
+        c, f = ctypes.c_double(), ctypes.c_double()
+        h = (ctypes.c_int32 * max(n_segments, 1))()
+        self._check(self.lib.lamps_sched_result(self.h, rid, ctypes.byref(c), ctypes.byref(f), h,
+                                                n_segments), "lamps_sched_result")
+        return c.value, f.value, list(h[:n_segments])
+
+    def stats(self):
+        a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+        self._check(self.lib.lamps_sched_stats(self.h, ctypes.byref(a), ctypes.byref(b),
+                                               ctypes.byref(c)), "lamps_sched_stats")
+        return a.value, b.value, c.value
 
 
 def _ptr(x):

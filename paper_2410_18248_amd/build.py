@@ -14,7 +14,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblamps.so")
-SOURCES = ["decode_attn.hip", "block_copy.hip", "kv_append.hip", "lamps.cpp"]
+SOURCES = ["decode_attn.hip", "block_copy.hip", "kv_append.hip", "lamps.cpp", "sched.cpp"]
+# the scheduler's times are compared bit for bit with a plain evaluation of the same formulas:
+# no fused multiply-adds in its host code
+PER_SOURCE = {"sched.cpp": ["-ffp-contract=off"]}
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
@@ -24,7 +27,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
 
 
 def _compile(src, obj, extra):
-    cmd = [HIPCC] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + FLAGS + PER_SOURCE.get(src, []) + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
     subprocess.check_call(cmd)
     return obj
 
