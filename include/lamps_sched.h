@@ -40,8 +40,9 @@
  *   - An iteration in which a request recomputes context or processes an API
  *     response yields no new token for it.
  *   - Rank ties: earlier arrival, then lower id.
- *   - If nothing can run and nothing is pending, the worst-ranked request
- *     that holds memory is discarded (it recomputes later).
+ *   - If nothing can run while waiting requests hold memory, the worst-ranked
+ *     of them is discarded (it recomputes later); if none holds memory the
+ *     engine idles until the next arrival or API return.
  */
 #ifndef LAMPS_SCHED_H
 #define LAMPS_SCHED_H
@@ -147,8 +148,9 @@ int lamps_sched_add(lamps_sched *s, int64_t id, double arrival, int32_t prompt_t
 
 /* Steps 1-6 of an iteration of Algorithm 1 at the current time: arrivals and
  * finished API calls enter the waiting queue, scores, sort, batch formation,
- * starvation counters.  If nothing can run, time moves to the next arrival or
- * API return (or the worst-ranked holder is discarded) and the steps repeat.
+ * starvation counters.  If nothing can run, the worst-ranked waiting request
+ * that holds memory is discarded, or, if none does, time moves to the next
+ * arrival or API return; then the steps repeat.
  * Writes the batch (<= cap entries; cap >= max_batch) and *n.  *n == 0 means
  * every request has finished.  Errors: INVALID, RANGE (cap too small), NOMEM
  * (a request needs more memory than the whole budget). */

@@ -30,10 +30,11 @@ notes):
     an API response produces no new token for it (the worked example counts
     R2's post-API part as 2 units "including recomputation").
   * Ties in the rank go to the earlier arrival, then the lower id.
-  * If nothing can run and nothing is pending (all memory is held by
-    half-finished requests that each need more), the worst-ranked request that
-    holds memory is discarded and recomputes later, as the substrate the paper
-    builds on does when it runs out of blocks.
+  * If nothing can run while waiting requests hold memory (each needs more
+    than is free), the worst-ranked of them is discarded and recomputes later,
+    as the substrate the paper builds on does when it runs out of blocks; if no
+    waiting request holds memory the engine idles until the next arrival or
+    API return (the idle unit of the worked example).
 """
 PRESERVE, DISCARD, SWAP = 0, 1, 2
 FCFS, SJF, SJF_TOTAL, LAMPS, FIXED = 0, 1, 2, 3, 4
@@ -241,23 +242,24 @@ class Simulator:
                     r.prioritized = True
                     r.starv = 0
             if not batch:
+                # Nothing fits.  If memory is held by waiting requests none of which can grow
+                # (Section 4.3: "when memory is full, jobs are either discarded and recomputed
+                # when memory becomes available, or ..."), the worst-ranked holder is discarded;
+                # otherwise the engine idles until the next arrival or API return.
+                victims = [r for r in reversed(waiting) if r.held > 0]
+                if victims:
+                    v = victims[0]
+                    v.held = 0
+                    v.pending_swapin = 0
+                    v.pending_recompute = v.ctx
+                    v.started = False
+                    v.score = None
+                    self.preemptions += 1
+                    continue
                 nxt = [r.api_end for r in reqs if r.state == IN_API]
                 nxt += [r.arrival for r in reqs if r.state == NEW]
-                if nxt:
-                    self.now = max(self.now, min(nxt))
-                    continue
-                # Memory is full of half-finished requests and none of them can grow
-                # (Section 4.3: "when memory is full, jobs are either discarded and recomputed
-                # when memory becomes available, or ..."): the worst-ranked holder is discarded.
-                victims = [r for r in reversed(waiting) if r.held > 0]
-                assert victims, "a request needs more memory than the whole budget"
-                v = victims[0]
-                v.held = 0
-                v.pending_swapin = 0
-                v.pending_recompute = v.ctx
-                v.started = False
-                v.score = None
-                self.preemptions += 1
+                assert nxt, "a request needs more memory than the whole budget"
+                self.now = max(self.now, min(nxt))
                 continue
             # execute the batch: one iteration
             recomputed = swapped = 0

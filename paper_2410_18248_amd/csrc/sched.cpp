@@ -327,34 +327,34 @@ int lamps_sched_next_batch(lamps_sched *s, lamps_batch_entry *out, int32_t cap, 
             }
         }
         if (!s->batch.empty()) break;
-        // nothing fits: wait for the next arrival or API return ...
-        bool have = false;
-        double nxt = 0.0;
-        for (size_t k : s->in_api)
-            if (!have || s->reqs[k].api_end < nxt) nxt = s->reqs[k].api_end, have = true;
-        if (s->next_new < s->reqs.size() && (!have || s->reqs[s->next_new].arrival < nxt))
-            nxt = s->reqs[s->next_new].arrival, have = true;
-        if (have) {
-            s->now = std::max(s->now, nxt);
-            continue;
-        }
-        // ... or, if memory is full of half-finished requests none of which can grow
+        // Nothing fits.  If memory is held by waiting requests none of which can grow
         // (Section 4.3: "when memory is full, jobs are either discarded and recomputed ..."),
-        // discard the worst-ranked holder
+        // the worst-ranked holder is discarded; otherwise the engine idles until the next
+        // arrival or API return.
         Req *victim = nullptr;
         for (size_t k = s->waiting.size(); k-- > 0;)
             if (s->reqs[s->waiting[k]].held > 0) {
                 victim = &s->reqs[s->waiting[k]];
                 break;
             }
-        if (!victim) return LAMPS_ERR_NOMEM;
-        s->total_held -= victim->held;
-        victim->held = 0;
-        victim->pending_swapin = 0;
-        victim->pending_recompute = victim->ctx;
-        victim->started = false;
-        victim->has_score = false;
-        ++s->preemptions;
+        if (victim) {
+            s->total_held -= victim->held;
+            victim->held = 0;
+            victim->pending_swapin = 0;
+            victim->pending_recompute = victim->ctx;
+            victim->started = false;
+            victim->has_score = false;
+            ++s->preemptions;
+            continue;
+        }
+        bool have = false;
+        double nxt = 0.0;
+        for (size_t k : s->in_api)
+            if (!have || s->reqs[k].api_end < nxt) nxt = s->reqs[k].api_end, have = true;
+        if (s->next_new < s->reqs.size() && (!have || s->reqs[s->next_new].arrival < nxt))
+            nxt = s->reqs[s->next_new].arrival, have = true;
+        if (!have) return LAMPS_ERR_NOMEM;
+        s->now = std::max(s->now, nxt);
     }
     *n = (int32_t)s->batch.size();
     for (int32_t i = 0; i < *n; ++i) {

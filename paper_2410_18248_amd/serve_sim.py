@@ -3,7 +3,7 @@
 over a synthetic API-augmented request trace, with the engine's times measured
 on the GPU through the library's own decode and swap calls.
 
-    python -m paper_2410_18248_amd.serve_sim [--requests 400] [--rates 1,1.25,1.5,2] [--memory-gb 40]
+    python -m paper_2410_18248_amd.serve_sim [--requests 600] [--rates 2,4,6,8] [--memory-gb 40]
 
 What is measured and what is assumed
   * iteration time = weights + attention.  Attention per context token (it_b)
@@ -174,8 +174,8 @@ def run_policy(policy, trace, cost, memory_tokens, max_batch, c_other, M, starva
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--requests", type=int, default=400)
-    ap.add_argument("--rates", default="1.0,1.25,1.5,2.0", help="arrival rates to run, requests per second")
+    ap.add_argument("--requests", type=int, default=600)
+    ap.add_argument("--rates", default="2,4,6,8", help="arrival rates to run, requests per second")
     ap.add_argument("--memory-gb", type=float, default=40.0,
                     help="GPU memory for weights + KV cache (the paper limits its GPUs to 40 GB)")
     ap.add_argument("--max-batch", type=int, default=256)
