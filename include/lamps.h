@@ -172,6 +172,37 @@ int lamps_kv_append(lamps_ctx *ctx, int32_t layer, int32_t batch, const void *k_
                     const void *v_new, const int32_t *block_table, int32_t *ctx_lens,
                     const uint8_t *running_mask, int32_t advance);
 
+/* ---- several new tokens per request: Discard's recompute, prompts, API responses ---- */
+
+/* The new tokens of request r < n_req are rows q_start[r] .. q_start[r+1]-1 of
+ * the token-major arrays below and sit at the LAST positions of its context:
+ * row q_start[r] + i is cached position ctx_lens[r] - n_r + i, n_r =
+ * q_start[r+1] - q_start[r], with ctx_lens already counting the new tokens.
+ * q_start[0] == 0 and q_start[n_req] == total_tokens (total_tokens is given on
+ * the host because it sizes the launch; rows past q_start[n_req] are ignored).
+ *   q_start      device, int32 [n_req + 1], non-decreasing
+ *   block_table  device, int32 [n_req][max_blocks_per_req], covering ctx_lens
+ *   ctx_lens     device, int32 [n_req]
+ * Both calls enqueue on the compute stream and return at once.
+ * Errors: INVALID (null), RANGE (layer, n_req > max_batch, negative sizes). */
+
+/* Writes the keys and values of the new tokens into the paged cache of `layer`
+ * (Section 4.2: a discarded context is recomputed into blocks the caller has
+ * allocated again; after lamps_compute_wait_blocks if they may still be the
+ * source of a swap-out).  k_new, v_new: device, [total_tokens][H_kv][d_h]. */
+int lamps_kv_append_tokens(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t total_tokens,
+                           const void *k_new, const void *v_new, const int32_t *q_start,
+                           const int32_t *block_table, const int32_t *ctx_lens);
+/* Attention of every new token over the cached positions up to and including
+ * its own (the Section 2.2 equation per token; the new tokens' keys and values
+ * must already be in the cache):
+ *   out[n][h][:] = softmax(q[n][h] . K_r[0..p]^T * scale) . V_r[0..p],  p the position of row n.
+ * q, out: device, [total_tokens][H][d_h] dtype.  fp32 accumulation, bf16 output
+ * rounded to nearest even, results independent of block placement. */
+int lamps_prefill_attn(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t total_tokens,
+                       const void *q, const int32_t *q_start, const int32_t *block_table,
+                       const int32_t *ctx_lens, void *out);
+
 /* ---- Swap handling strategy (Section 1; Section 4.2) ---- */
 
 /* Copies the n listed blocks (all layers, keys and values) into host_buf

@@ -13,7 +13,7 @@ imports it, and it never imports the product package.
 ``scheduler``  -- equations (1)-(3), the memory-over-time rank and Algorithm 1
                   as a plain iteration-level simulation.
 """
-from .attention import build, decode_attn, max_threads, widen  # noqa: F401
+from .attention import build, decode_attn, max_threads, prefill_attn, widen  # noqa: F401
 from .blocks import AllocatorModel, PoolModel, kv_bytes_per_token  # noqa: F401
 from .cache import LogicalCache  # noqa: F401
 from . import scheduler  # noqa: F401

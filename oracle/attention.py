@@ -111,3 +111,31 @@ def decode_attn(q, K, V, ctx_lens, running, scale=None, out=None, threads=1):
     if rc != 0:
         raise RuntimeError("lamps_oracle_decode_attn failed (rc=%d)" % rc)
     return out
+
+
+def prefill_attn(q, K, V, q_start, ctx_lens, scale=None, threads=1):
+    """Attention for several new tokens per request at once (the recompute of a
+    discarded context, a prompt, an API response): the Section 2.2 equation for
+    each new token over the cached positions up to and including its own.
+
+    q        [total][H][D], the new tokens of request r are rows
+             q_start[r] .. q_start[r+1]-1 and sit at the LAST positions of its
+             sequence: row q_start[r]+i is position ctx_lens[r] - n_r + i
+    K, V     lists; K[r] is the logical sequence [ctx_lens[r]][H_kv][D], new
+             tokens included
+    Returns float64 [total][H][D].  Every row is an independent evaluation of
+    the decode equation with its own context length."""
+    q = np.ascontiguousarray(q)
+    Ks, Vs, ctx = [], [], []
+    for r in range(len(ctx_lens)):
+        n = int(q_start[r + 1]) - int(q_start[r])
+        assert 0 <= n <= int(ctx_lens[r])
+        k, v = np.ascontiguousarray(K[r]), np.ascontiguousarray(V[r])
+        for i in range(n):
+            Ks.append(k)
+            Vs.append(v)
+            ctx.append(int(ctx_lens[r]) - n + i + 1)
+    assert len(ctx) == q.shape[0] == int(q_start[len(ctx_lens)])
+    if not ctx:
+        return np.zeros(q.shape, dtype=np.float64)
+    return decode_attn(q, Ks, Vs, ctx, np.ones(len(ctx), dtype=np.uint8), scale=scale, threads=threads)

@@ -68,6 +68,8 @@ def load_library():
         "lamps_destroy": [vp],
         "lamps_decode_attn": [vp, i32, i32, vp, vp, vp, vp, vp],
         "lamps_kv_append": [vp, i32, i32, vp, vp, vp, vp, vp, i32],
+        "lamps_kv_append_tokens": [vp, i32, i32, i32, vp, vp, vp, vp, vp],
+        "lamps_prefill_attn": [vp, i32, i32, i32, vp, vp, vp, vp, vp],
         "lamps_swap_out": [vp, vp, i32, vp, ctypes.POINTER(u64)],
         "lamps_swap_in": [vp, vp, vp, i32, ctypes.POINTER(u64)],
         "lamps_ticket_query": [vp, u64],
@@ -283,6 +285,16 @@ class Lamps:
         self._check(self.lib.lamps_kv_append(self.h, layer, batch, _ptr(k_new), _ptr(v_new),
                                              _ptr(block_table), _ptr(ctx_lens), _ptr(running_mask),
                                              1 if advance else 0))
+
+    def kv_append_tokens(self, layer, n_req, total_tokens, k_new, v_new, q_start, block_table, ctx_lens):
+        self._check(self.lib.lamps_kv_append_tokens(self.h, layer, n_req, total_tokens, _ptr(k_new),
+                                                    _ptr(v_new), _ptr(q_start), _ptr(block_table),
+                                                    _ptr(ctx_lens)))
+
+    def prefill_attn(self, layer, n_req, total_tokens, q, q_start, block_table, ctx_lens, out):
+        self._check(self.lib.lamps_prefill_attn(self.h, layer, n_req, total_tokens, _ptr(q),
+                                                _ptr(q_start), _ptr(block_table), _ptr(ctx_lens),
+                                                _ptr(out)))
 
     def swap_out(self, block_ids, host_buf):
         arr, n = _ids(block_ids)

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblamps.so")
-SOURCES = ["decode_attn.hip", "block_copy.hip", "kv_append.hip", "lamps.cpp", "sched.cpp"]
+SOURCES = ["decode_attn.hip", "block_copy.hip", "kv_append.hip", "prefill_attn.hip", "lamps.cpp", "sched.cpp"]
 # the scheduler's times are compared bit for bit with a plain evaluation of the same formulas:
 # no fused multiply-adds in its host code
 PER_SOURCE = {"sched.cpp": ["-ffp-contract=off"]}

@@ -44,13 +44,26 @@ struct AppendArgs {
     void *k_pool, *v_pool;
     const int32_t *block_table;  // [batch][max_blocks]
     int32_t *ctx_lens;           // [batch]; incremented for running requests if advance
-    const uint8_t *running;      // [batch]
+    const uint8_t *running;      // [batch] (decode form)
+    const int32_t *q_start;      // [batch + 1] (token form): first new-token row of each request
     int32_t batch, layer, num_layers, num_kv_heads, head_dim, block_size, log2_block_size;
     int32_t max_blocks, num_blocks, bf16, advance;
 };
 
 // Enqueues the append of one new position per running request in one layer.
 hipError_t launch_kv_append(const AppendArgs &a, int tiled, hipStream_t stream);
+// Enqueues the append of total_tokens new tokens, q_start[r + 1] - q_start[r] of them at the end
+// of request r's context.
+hipError_t launch_kv_append_tokens(const AppendArgs &a, int total_tokens, int tiled, hipStream_t stream);
+
+struct PrefillArgs {
+    DecodeArgs d;                // q and out are [total_tokens][H][D]; batch = number of requests
+    const int32_t *q_start;      // [batch + 1]
+    int32_t total_tokens;
+};
+// Enqueues attention for the new tokens of every request over its paged cache, each token over
+// the positions up to and including its own.
+hipError_t launch_prefill(const PrefillArgs &a, hipStream_t stream);
 
 // Gather: staging image i (key bytes then value bytes of block ids[i]) <- pools.
 // Scatter: the reverse.  `half_bytes` = bytes of one block in one pool, a

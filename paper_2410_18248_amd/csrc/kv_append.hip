@@ -10,9 +10,10 @@
 // kernels read (plain or tiled, see lamps.h).  Requests outside the running
 // batch (Algorithm 1) append nothing.
 //
-// One workgroup per request.  All threads read the request's context length,
-// meet at a barrier, then scatter; with `advance` thread 0 stores length + 1
-// after the barrier, so nobody can read the new value.  A position outside the
+// One workgroup per request (decode) or per token (many tokens at once).  In
+// the decode form all threads read the request's context length, meet at a
+// barrier, then scatter; with `advance` thread 0 stores length + 1 after the
+// barrier, so nobody can read the new value.  A position outside the
 // block-table row, or a block id outside the pool, writes nothing.
 #include <hip/hip_runtime.h>
 
@@ -23,23 +24,20 @@ namespace {
 
 constexpr int kAppendThreads = 256;
 
+// Writes the key and value vectors kn, vn ([H_kv][D]) of one token at cached
+// position t of request r.  Called by a whole workgroup.  A position outside the
+// block-table row, or a block id outside the pool, writes nothing.
 template <typename T, bool TILED>
-__global__ __launch_bounds__(kAppendThreads) void kv_append(const AppendArgs a)
+__device__ __forceinline__ bool scatter_token(const AppendArgs &a, int r, int t, const T *kn, const T *vn)
 {
-    const int r = blockIdx.x;
-    if (!a.running[r]) return;                        // uniform over the workgroup
-    const int t = a.ctx_lens[r];
-    __syncthreads();
     const int D = a.head_dim, Hkv = a.num_kv_heads, bs = a.block_size;
     const int lb = t >> a.log2_block_size, slot = t & (bs - 1);
-    if (t < 0 || lb >= a.max_blocks) return;
+    if (t < 0 || lb >= a.max_blocks) return false;
     const int block = a.block_table[(size_t)r * a.max_blocks + lb];
-    if (block < 0 || block >= a.num_blocks) return;
+    if (block < 0 || block >= a.num_blocks) return false;
     const size_t tile = (size_t)bs * D;
     T *kt = static_cast<T *>(a.k_pool) + (((size_t)block * a.num_layers + a.layer) * Hkv) * tile;
     T *vt = static_cast<T *>(a.v_pool) + (((size_t)block * a.num_layers + a.layer) * Hkv) * tile;
-    const T *kn = static_cast<const T *>(a.k_new) + (size_t)r * Hkv * D;
-    const T *vn = static_cast<const T *>(a.v_new) + (size_t)r * Hkv * D;
     for (int i = threadIdx.x; i < Hkv * D; i += kAppendThreads) {
         const int g = i / D, d = i - g * D;
         size_t ko, vo;
@@ -55,7 +53,43 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append(const AppendArgs a)
         kt[g * tile + ko] = kn[i];
         vt[g * tile + vo] = vn[i];
     }
-    if (a.advance && threadIdx.x == 0) a.ctx_lens[r] = t + 1;
+    return true;
+}
+
+template <typename T, bool TILED>
+__global__ __launch_bounds__(kAppendThreads) void kv_append(const AppendArgs a)
+{
+    const int r = blockIdx.x;
+    if (!a.running[r]) return;                        // uniform over the workgroup
+    const int t = a.ctx_lens[r];
+    __syncthreads();
+    const size_t row = (size_t)r * a.num_kv_heads * a.head_dim;
+    const bool ok = scatter_token<T, TILED>(a, r, t, static_cast<const T *>(a.k_new) + row,
+                                            static_cast<const T *>(a.v_new) + row);
+    if (ok && a.advance && threadIdx.x == 0) a.ctx_lens[r] = t + 1;
+}
+
+// Several new tokens per request (a prompt, a recomputed context, an API
+// response): token row n of k_new / v_new belongs to the request r with
+// q_start[r] <= n < q_start[r + 1] and goes to position
+// ctx_lens[r] - (q_start[r + 1] - q_start[r]) + (n - q_start[r]), ctx_lens
+// already counting the new tokens.  One workgroup per token.
+template <typename T, bool TILED>
+__global__ __launch_bounds__(kAppendThreads) void kv_append_tokens(const AppendArgs a)
+{
+    const int n = blockIdx.x;
+    int lo = 0, hi = a.batch;                         // last r with q_start[r] <= n
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (a.q_start[mid] <= n) lo = mid; else hi = mid;
+    }
+    const int r = lo;
+    const int first = a.q_start[r], count = a.q_start[r + 1] - first;
+    if (n >= first + count) return;                   // q_start[batch] is less than the grid
+    const int t = a.ctx_lens[r] - count + (n - first);
+    const size_t row = (size_t)n * a.num_kv_heads * a.head_dim;
+    scatter_token<T, TILED>(a, r, t, static_cast<const T *>(a.k_new) + row,
+                            static_cast<const T *>(a.v_new) + row);
 }
 
 }  // namespace
@@ -71,6 +105,21 @@ hipError_t launch_kv_append(const AppendArgs &a, int tiled, hipStream_t stream)
             hipLaunchKernelGGL((kv_append<uint16_t, false>), grid, block, 0, stream, a);
     } else {
         hipLaunchKernelGGL((kv_append<float, false>), grid, block, 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_append_tokens(const AppendArgs &a, int total_tokens, int tiled, hipStream_t stream)
+{
+    if (a.batch == 0 || total_tokens == 0) return hipSuccess;
+    dim3 grid((unsigned)total_tokens), block(kAppendThreads);
+    if (a.bf16) {
+        if (tiled)
+            hipLaunchKernelGGL((kv_append_tokens<uint16_t, true>), grid, block, 0, stream, a);
+        else
+            hipLaunchKernelGGL((kv_append_tokens<uint16_t, false>), grid, block, 0, stream, a);
+    } else {
+        hipLaunchKernelGGL((kv_append_tokens<float, false>), grid, block, 0, stream, a);
     }
     return hipGetLastError();
 }

@@ -123,6 +123,37 @@ struct lamps_ctx {
 
 namespace {
 
+void fill_decode_args(lamps_ctx *c, lamps::DecodeArgs *pa, int32_t layer, int32_t batch, const void *q,
+                      const int32_t *block_table, const int32_t *ctx_lens, const uint8_t *running_mask,
+                      void *out)
+{
+    lamps::DecodeArgs &a = *pa;
+    a.q = q;
+    a.k_pool = c->k_pool;
+    a.v_pool = c->v_pool;
+    a.block_table = block_table;
+    a.ctx_lens = ctx_lens;
+    a.running = running_mask;
+    a.partials = c->partials;
+    a.share_info = c->share_info;
+    a.max_batch = c->cfg.max_batch;
+    a.out = out;
+    a.batch = batch;
+    a.layer = layer;
+    a.num_layers = c->cfg.num_layers;
+    a.num_q_heads = c->cfg.num_q_heads;
+    a.num_kv_heads = c->cfg.num_kv_heads;
+    a.head_dim = c->cfg.head_dim;
+    a.block_size = c->cfg.block_size;
+    a.log2_block_size = c->d.log2_bs;
+    a.max_blocks = c->cfg.max_blocks_per_req;
+    a.part_tokens = c->d.part_tokens;
+    a.max_parts = c->d.max_parts;
+    a.bf16 = c->cfg.dtype == LAMPS_BF16;
+    a.heads_per_pass = lamps::decode_heads_per_pass(a.bf16, a.head_dim, a.num_q_heads / a.num_kv_heads);
+    a.scale_log2e = c->d.scale_log2e;
+}
+
 int fail(lamps_ctx *c, int code, const std::string &msg)
 {
     if (c) c->err = msg;
@@ -389,30 +420,7 @@ int lamps_decode_attn(lamps_ctx *c, int32_t layer, int32_t batch, const void *q,
         return fail(c, LAMPS_ERR_RANGE, "lamps_decode_attn: batch out of range");
     if (batch == 0) return LAMPS_OK;
     lamps::DecodeArgs a;
-    a.q = q;
-    a.k_pool = c->k_pool;
-    a.v_pool = c->v_pool;
-    a.block_table = block_table;
-    a.ctx_lens = ctx_lens;
-    a.running = running_mask;
-    a.partials = c->partials;
-    a.share_info = c->share_info;
-    a.max_batch = c->cfg.max_batch;
-    a.out = out;
-    a.batch = batch;
-    a.layer = layer;
-    a.num_layers = c->cfg.num_layers;
-    a.num_q_heads = c->cfg.num_q_heads;
-    a.num_kv_heads = c->cfg.num_kv_heads;
-    a.head_dim = c->cfg.head_dim;
-    a.block_size = c->cfg.block_size;
-    a.log2_block_size = c->d.log2_bs;
-    a.max_blocks = c->cfg.max_blocks_per_req;
-    a.part_tokens = c->d.part_tokens;
-    a.max_parts = c->d.max_parts;
-    a.bf16 = c->cfg.dtype == LAMPS_BF16;
-    a.heads_per_pass = lamps::decode_heads_per_pass(a.bf16, a.head_dim, a.num_q_heads / a.num_kv_heads);
-    a.scale_log2e = c->d.scale_log2e;
+    fill_decode_args(c, &a, layer, batch, q, block_table, ctx_lens, running_mask, out);
     LAMPS_HIP(lamps::launch_decode(a, c->cs));
     return LAMPS_OK;
 }
@@ -437,6 +445,7 @@ int lamps_kv_append(lamps_ctx *c, int32_t layer, int32_t batch, const void *k_ne
     a.block_table = block_table;
     a.ctx_lens = ctx_lens;
     a.running = running_mask;
+    a.q_start = nullptr;
     a.batch = batch;
     a.layer = layer;
     a.num_layers = c->cfg.num_layers;
@@ -450,6 +459,63 @@ int lamps_kv_append(lamps_ctx *c, int32_t layer, int32_t batch, const void *k_ne
     a.advance = advance != 0;
     const int tiled = lamps::decode_uses_tiled_layout(a.bf16, c->cfg.num_q_heads / c->cfg.num_kv_heads);
     LAMPS_HIP(lamps::launch_kv_append(a, tiled, c->cs));
+    return LAMPS_OK;
+}
+
+int lamps_kv_append_tokens(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t total_tokens,
+                           const void *k_new, const void *v_new, const int32_t *q_start,
+                           const int32_t *block_table, const int32_t *ctx_lens)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!k_new || !v_new || !q_start || !block_table || !ctx_lens)
+        return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append_tokens: null argument");
+    if (layer < 0 || layer >= c->cfg.num_layers)
+        return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append_tokens: layer out of range");
+    if (n_req < 0 || n_req > c->cfg.max_batch || total_tokens < 0)
+        return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append_tokens: n_req / total_tokens out of range");
+    if (n_req == 0 || total_tokens == 0) return LAMPS_OK;
+    lamps::AppendArgs a;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.k_pool = c->k_pool;
+    a.v_pool = c->v_pool;
+    a.block_table = block_table;
+    a.ctx_lens = const_cast<int32_t *>(ctx_lens);     // the token form only reads it
+    a.running = nullptr;
+    a.q_start = q_start;
+    a.batch = n_req;
+    a.layer = layer;
+    a.num_layers = c->cfg.num_layers;
+    a.num_kv_heads = c->cfg.num_kv_heads;
+    a.head_dim = c->cfg.head_dim;
+    a.block_size = c->cfg.block_size;
+    a.log2_block_size = c->d.log2_bs;
+    a.max_blocks = c->cfg.max_blocks_per_req;
+    a.num_blocks = c->cfg.num_blocks;
+    a.bf16 = c->cfg.dtype == LAMPS_BF16;
+    a.advance = 0;
+    const int tiled = lamps::decode_uses_tiled_layout(a.bf16, c->cfg.num_q_heads / c->cfg.num_kv_heads);
+    LAMPS_HIP(lamps::launch_kv_append_tokens(a, total_tokens, tiled, c->cs));
+    return LAMPS_OK;
+}
+
+int lamps_prefill_attn(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t total_tokens, const void *q,
+                       const int32_t *q_start, const int32_t *block_table, const int32_t *ctx_lens,
+                       void *out)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!q || !q_start || !block_table || !ctx_lens || !out)
+        return fail(c, LAMPS_ERR_INVALID, "lamps_prefill_attn: null argument");
+    if (layer < 0 || layer >= c->cfg.num_layers)
+        return fail(c, LAMPS_ERR_RANGE, "lamps_prefill_attn: layer out of range");
+    if (n_req < 0 || n_req > c->cfg.max_batch || total_tokens < 0)
+        return fail(c, LAMPS_ERR_RANGE, "lamps_prefill_attn: n_req / total_tokens out of range");
+    if (n_req == 0 || total_tokens == 0) return LAMPS_OK;
+    lamps::PrefillArgs p;
+    fill_decode_args(c, &p.d, layer, n_req, q, block_table, ctx_lens, nullptr, out);
+    p.q_start = q_start;
+    p.total_tokens = total_tokens;
+    LAMPS_HIP(lamps::launch_prefill(p, c->cs));
     return LAMPS_OK;
 }
 

@@ -1,0 +1,123 @@
+"""GPU parity for lamps_kv_append_tokens and lamps_prefill_attn (Discard's recompute,
+prompts, API responses: several new tokens per request, each attending to the cached
+positions up to its own): appended pools bit-exact against the harness' pager, attention
+against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import lamps_workloads as W
+import oracle
+import paper_2410_18248_amd as P
+from rig import Rig, n2t, to_f64, tol
+
+pytestmark = pytest.mark.gpu
+
+#        dtype  H  Hkv D    bs  (context, new tokens) per request
+CASES = [
+    ("f32", 4, 4, 64, 16, [(40, 40), (17, 3), (64, 1), (9, 0), (33, 33)]),
+    ("f32", 8, 2, 32, 16, [(50, 50), (20, 7)]),
+    ("bf16", 4, 4, 128, 16, [(130, 130), (47, 5), (16, 16), (1, 1)]),
+    ("bf16", 8, 2, 128, 16, [(130, 130), (47, 5), (16, 16), (1, 1), (200, 64)]),     # tiled layout
+    ("bf16", 8, 2, 64, 32, [(95, 95), (64, 33)]),
+    ("bf16", 16, 1, 256, 16, [(70, 70), (31, 2)]),
+    ("bf16", 32, 1, 128, 16, [(45, 45), (20, 3)]),                                   # 32 heads per kv head
+    ("bf16", 2, 2, 64, 64, [(150, 150)]),
+]
+
+
+def _setup(dtype, H, Hkv, D, bs, reqs, seed):
+    ctx = [c for c, _ in reqs]
+    new = [n for _, n in reqs]
+    nb = sum((c + bs - 1) // bs for c in ctx)
+    geom = W.Geometry(1, H, Hkv, D, bs, nb + 4, max((c + bs - 1) // bs for c in ctx), dtype)
+    rig = Rig(geom, len(reqs))
+    perm = W.permutation(seed, geom.num_blocks)
+    table, _ = W.deal_block_table(perm, ctx, geom)
+    K, V = zip(*[W.logical_kv(seed + 17 * r, geom, c) for r, c in enumerate(ctx)])
+    # what was cached before: everything but the new tokens
+    rig.page_requests(0, table, [K[r][:c - n] for r, (c, n) in enumerate(reqs)],
+                      [V[r][:c - n] for r, (c, n) in enumerate(reqs)])
+    q_start = np.concatenate([[0], np.cumsum(new)]).astype(np.int32)
+    return geom, rig, table, K, V, ctx, new, q_start
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,D,bs,reqs", CASES)
+def test_append_tokens_then_prefill_attention(dtype, H, Hkv, D, bs, reqs):
+    seed = 9000 + D + bs + H
+    geom, rig, table, K, V, ctx, new, q_start = _setup(dtype, H, Hkv, D, bs, reqs, seed)
+    total = int(q_start[-1])
+    dev = rig.dev
+    k_new = np.concatenate([K[r][c - n:] for r, (c, n) in enumerate(reqs)])
+    v_new = np.concatenate([V[r][c - n:] for r, (c, n) in enumerate(reqs)])
+    q = W.queries(seed + 5, geom, total)
+    td = torch.as_tensor(table, device=dev)
+    cd = torch.as_tensor(np.asarray(ctx, dtype=np.int32), device=dev)
+    sd = torch.as_tensor(q_start, device=dev)
+    out = torch.full((total, H, D), 7.0, dtype=rig.tdtype, device=dev)
+    with torch.cuda.stream(rig.compute):
+        kd, vd, qd = n2t(k_new, dev), n2t(v_new, dev), n2t(q, dev)
+        rig.lamps.kv_append_tokens(0, len(reqs), total, kd, vd, sd, td, cd)
+        rig.lamps.prefill_attn(0, len(reqs), total, qd, sd, td, cd, out)
+    rig.compute.synchronize()
+    # the cache now holds the full sequences, and nothing else changed
+    kp = np.full(geom.pool_shape, W.poison(geom), dtype=geom.np_dtype)
+    vp = kp.copy()
+    for r in range(len(reqs)):
+        W.page(kp, 0, table[r], K[r], rig.k_index)
+        W.page(vp, 0, table[r], V[r], rig.v_index)
+    got_k, got_v = rig.host_pools()
+    assert got_k.tobytes() == kp.tobytes() and got_v.tobytes() == vp.tobytes()
+    ref = oracle.prefill_attn(q, K, V, q_start, ctx, threads=8)
+    got = to_f64(out)
+    assert np.abs(got - ref).max() <= tol(geom)
+    # a single new token is a decode step (another summation order: not the same bits)
+    for r, (c, n) in enumerate(reqs):
+        if n == 1:
+            one = rig.decode(0, q[q_start[r]:q_start[r] + 1], table[r:r + 1], [c], [1])
+            assert np.abs(to_f64(one)[0] - got[q_start[r]]).max() <= (1e-5 if dtype == "f32" else 2e-2)
+    rig.close()
+
+
+def test_prefill_is_independent_of_block_placement():
+    reqs = [(77, 77), (40, 9)]
+    outs = []
+    for seed in (1, 2):                                 # two different random placements
+        geom, rig, table, K, V, ctx, new, q_start = _setup("bf16", 8, 2, 128, 16, reqs, 500)
+        perm = W.permutation(seed, geom.num_blocks)
+        table, _ = W.deal_block_table(perm, ctx, geom)
+        rig.k_pool.fill_(float("nan"))
+        rig.v_pool.fill_(float("nan"))
+        rig.page_requests(0, table, K, V)
+        total = int(q_start[-1])
+        q = W.queries(77, geom, total)
+        dev = rig.dev
+        out = torch.zeros((total, 8, 128), dtype=rig.tdtype, device=dev)
+        with torch.cuda.stream(rig.compute):
+            rig.lamps.prefill_attn(0, 2, total, n2t(q, dev), torch.as_tensor(q_start, device=dev),
+                                   torch.as_tensor(table, device=dev),
+                                   torch.as_tensor(np.asarray(ctx, dtype=np.int32), device=dev), out)
+        rig.compute.synchronize()
+        outs.append(out.clone())
+        rig.close()
+    assert torch.equal(outs[0], outs[1])
+
+
+def test_prefill_rejects_bad_host_arguments():
+    geom = W.Geometry(2, 4, 4, 64, 16, 8, 2, "f32")
+    rig = Rig(geom, 2)
+    x = torch.zeros(8, device=rig.dev)
+    for call in (rig.lamps.prefill_attn, ):
+        with pytest.raises(P.LampsError) as e:
+            call(2, 1, 1, x, x, x, x, x)
+        assert e.value.status == -2
+        with pytest.raises(P.LampsError) as e:
+            call(0, 3, 1, x, x, x, x, x)
+        assert e.value.status == -2
+        with pytest.raises(P.LampsError) as e:
+            call(0, 1, 1, None, x, x, x, x)
+        assert e.value.status == -1
+    with pytest.raises(P.LampsError) as e:
+        rig.lamps.kv_append_tokens(0, 1, -1, x, x, x, x, x)
+    assert e.value.status == -2
+    rig.close()

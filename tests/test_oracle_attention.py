@@ -104,3 +104,45 @@ def test_planted_mistake_is_caught(mistake):
     assert not _run(ALL, fn), "battery accepted a wrong implementation: " + mistake
     # the pins that do not re-type the formula catch it on their own
     assert not _run(NON_BRUTE, fn), "only brute force caught: " + mistake
+
+
+# ---------------------------------------------------------------- several new tokens at once
+def _causal_torch(q, K, V, n_new):
+    """softmax(mask(q K^T / sqrt(D))) V in float64 with torch, new tokens last."""
+    import torch
+    C, Hkv, D = K.shape
+    H = q.shape[1]
+    G = H // Hkv
+    qt = torch.from_numpy(q.astype(np.float64))                       # [n][H][D]
+    Kt = torch.from_numpy(K.astype(np.float64)).repeat_interleave(G, dim=1)   # [C][H][D]
+    Vt = torch.from_numpy(V.astype(np.float64)).repeat_interleave(G, dim=1)
+    s = torch.einsum("nhd,chd->hnc", qt, Kt) / np.sqrt(D)
+    pos = torch.arange(C - n_new, C)[:, None]
+    s = s.masked_fill(torch.arange(C)[None, :] > pos, float("-inf"))
+    return torch.einsum("hnc,chd->nhd", torch.softmax(s, dim=-1), Vt).numpy()
+
+
+def test_prefill_equals_masked_dense_attention_in_torch():
+    import oracle
+    g = W.Geometry(1, 4, 2, 16, 16, 8, 8, "f32")
+    ctx, new = [37, 5, 20], [9, 5, 1]
+    K, V = zip(*[W.logical_kv(70 + r, g, c) for r, c in enumerate(ctx)])
+    q_start = np.concatenate([[0], np.cumsum(new)])
+    q = W.queries(71, g, int(q_start[-1]))
+    got = oracle.prefill_attn(q, K, V, q_start, ctx)
+    for r in range(3):
+        want = _causal_torch(q[q_start[r]:q_start[r + 1]], K[r], V[r], new[r])
+        assert np.abs(got[q_start[r]:q_start[r + 1]] - want).max() < 1e-12
+
+
+def test_prefill_rows_are_decode_steps_and_first_token_sees_only_itself():
+    import oracle
+    g = W.Geometry(1, 2, 2, 8, 16, 8, 8, "f32")
+    K, V = W.logical_kv(80, g, 12)
+    q = W.queries(81, g, 12)
+    full = oracle.prefill_attn(q, [K], [V], [0, 12], [12])            # the whole sequence is new
+    assert np.array_equal(full[0], V[0].astype(np.float64))           # position 0: softmax over one key
+    last = oracle.decode_attn(q[11:12], [K], [V], [12], [1])
+    assert np.array_equal(full[11], last[0])
+    tail = oracle.prefill_attn(q[8:], [K], [V], [0, 4], [12])         # only the last four are new
+    assert np.array_equal(tail, full[8:])
