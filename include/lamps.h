@@ -198,10 +198,15 @@ int lamps_kv_append_tokens(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t
  * must already be in the cache):
  *   out[n][h][:] = softmax(q[n][h] . K_r[0..p]^T * scale) . V_r[0..p],  p the position of row n.
  * q, out: device, [total_tokens][H][d_h] dtype.  fp32 accumulation, bf16 output
- * rounded to nearest even, results independent of block placement. */
+ * rounded to nearest even, results independent of block placement.
+ * max_new_tokens: an upper bound, known on the host, of the new tokens of any one
+ * request (it sizes the launch; 0 = unknown, total_tokens is used).  bf16 with at
+ * most 64 query heads per kv head runs on the matrix cores (weights rounded to
+ * bf16 before the second product); other geometries, and any geometry when
+ * max_new_tokens < 0, run one wavefront per new token with fp32 weights. */
 int lamps_prefill_attn(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t total_tokens,
-                       const void *q, const int32_t *q_start, const int32_t *block_table,
-                       const int32_t *ctx_lens, void *out);
+                       int32_t max_new_tokens, const void *q, const int32_t *q_start,
+                       const int32_t *block_table, const int32_t *ctx_lens, void *out);
 
 /* ---- Swap handling strategy (Section 1; Section 4.2) ---- */
 

@@ -69,7 +69,7 @@ def load_library():
         "lamps_decode_attn": [vp, i32, i32, vp, vp, vp, vp, vp],
         "lamps_kv_append": [vp, i32, i32, vp, vp, vp, vp, vp, i32],
         "lamps_kv_append_tokens": [vp, i32, i32, i32, vp, vp, vp, vp, vp],
-        "lamps_prefill_attn": [vp, i32, i32, i32, vp, vp, vp, vp, vp],
+        "lamps_prefill_attn": [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp],
         "lamps_swap_out": [vp, vp, i32, vp, ctypes.POINTER(u64)],
         "lamps_swap_in": [vp, vp, vp, i32, ctypes.POINTER(u64)],
         "lamps_ticket_query": [vp, u64],
@@ -291,8 +291,9 @@ class Lamps:
                                                     _ptr(v_new), _ptr(q_start), _ptr(block_table),
                                                     _ptr(ctx_lens)))
 
-    def prefill_attn(self, layer, n_req, total_tokens, q, q_start, block_table, ctx_lens, out):
-        self._check(self.lib.lamps_prefill_attn(self.h, layer, n_req, total_tokens, _ptr(q),
+    def prefill_attn(self, layer, n_req, total_tokens, q, q_start, block_table, ctx_lens, out,
+                     max_new_tokens=0):
+        self._check(self.lib.lamps_prefill_attn(self.h, layer, n_req, total_tokens, max_new_tokens, _ptr(q),
                                                 _ptr(q_start), _ptr(block_table), _ptr(ctx_lens),
                                                 _ptr(out)))
 

@@ -60,6 +60,8 @@ struct PrefillArgs {
     DecodeArgs d;                // q and out are [total_tokens][H][D]; batch = number of requests
     const int32_t *q_start;      // [batch + 1]
     int32_t total_tokens;
+    int32_t max_new_tokens;      // upper bound of q_start[r + 1] - q_start[r]
+    int32_t force_rows;          // use the one-wavefront-per-token kernel whatever the geometry
 };
 // Enqueues attention for the new tokens of every request over its paged cache, each token over
 // the positions up to and including its own.

@@ -499,9 +499,9 @@ int lamps_kv_append_tokens(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t t
     return LAMPS_OK;
 }
 
-int lamps_prefill_attn(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t total_tokens, const void *q,
-                       const int32_t *q_start, const int32_t *block_table, const int32_t *ctx_lens,
-                       void *out)
+int lamps_prefill_attn(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t total_tokens,
+                       int32_t max_new_tokens, const void *q, const int32_t *q_start,
+                       const int32_t *block_table, const int32_t *ctx_lens, void *out)
 {
     if (!c) return LAMPS_ERR_INVALID;
     if (!q || !q_start || !block_table || !ctx_lens || !out)
@@ -515,6 +515,8 @@ int lamps_prefill_attn(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t total
     fill_decode_args(c, &p.d, layer, n_req, q, block_table, ctx_lens, nullptr, out);
     p.q_start = q_start;
     p.total_tokens = total_tokens;
+    p.max_new_tokens = max_new_tokens > 0 && max_new_tokens < total_tokens ? max_new_tokens : total_tokens;
+    p.force_rows = max_new_tokens < 0;
     LAMPS_HIP(lamps::launch_prefill(p, c->cs));
     return LAMPS_OK;
 }

@@ -52,6 +52,262 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
     });
 }
 
+// ---------------------------------------------------------------- matrix cores
+
+// bf16, up to 64 query heads per kv head.  With many new tokens per request both
+// products of the Section 2.2 equation are real contractions: for one kv head,
+// the (token, head-of-group) pairs are the columns of a query matrix, and every
+// 32 cached positions cost 2 D/32 + D/16 MFMAs (16x16x32) per 16 columns.
+//
+// One workgroup = one (request, kv head, tile of new tokens); its four waves each
+// own kCols = 64 columns (kCols / G tokens x G heads) as blocks of 16.  K and V
+// are streamed 32 positions at a time: all 256 threads load the next stage from
+// the paged pools into registers while the current one, in LDS, is consumed;
+// every wave reads each K / V operand from LDS once per stage and uses it for
+// its four column blocks.  Scores come out transposed (lane: four consecutive
+// positions of one column), which is the operand layout the second product
+// wants for the weights, so nothing is shuffled between the two; the positions of
+// a stage's two 16-position halves share one 32-deep MFMA (the contraction index
+// may be permuted as long as both operands agree).
+//
+// LDS holds the pool tiles as they are (tiled layout: 16-byte runs are operands
+// already) or, for the plain layout, rows padded by 16 bytes so that the 16 rows
+// of a K operand fall in different banks; V operands of the plain layout are
+// gathered with 16-bit LDS reads (the transposition a row-major V needs).
+constexpr int kMaxCols = 64;             // columns per wave (32 at head_dim 256: accumulators fill the registers)
+constexpr int kStage = 32;               // cached positions per LDS stage
+
+typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
+
+template <int D, bool TILED, int kCols>
+__global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
+{
+    constexpr int kColBlocks = kCols / 16;
+    constexpr int NK = D / 32;                       // score MFMAs per 16 positions
+    constexpr int NS = D / 16;                       // 16-dim slabs of the output
+    constexpr int U = D * 2;                         // 16-byte units of one 16-position sub-tile
+    constexpr int LPT = (2 * U) / kThreads;          // units per thread, pool and stage
+    constexpr int ROWB = D * 2 + 16;                 // plain layout: padded row, bytes
+    constexpr int SUBB = TILED ? 16 * D * 2 : 16 * ROWB;
+    static_assert(LPT >= 1 && (2 * U) % kThreads == 0, "head_dim");
+    __shared__ __align__(16) char lds_k[2 * SUBB];
+    __shared__ __align__(16) char lds_v[2 * SUBB];
+
+    const DecodeArgs &a = p.d;
+    const int r = blockIdx.z, g = blockIdx.y;
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int TW = kCols / G;                        // new tokens per wave (G <= kCols)
+    const int WT = kWaves * TW;                      // ... per workgroup
+    const int first = p.q_start[r], n_new = p.q_start[r + 1] - first;
+    const int tile = gridDim.x - 1 - blockIdx.x;     // the longest tiles start first
+    if (tile * WT >= n_new) return;
+    const int C = a.ctx_lens[r];
+    const int base_pos = C - n_new;                  // position of the request's first new token
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int j = lane & 15, qd = lane >> 4;
+
+    // this lane's column in each block: (token, head), its position, its q slices
+    int pos[kColBlocks];                             // -1: no such column
+    size_t orow[kColBlocks];                         // element offset of its output row
+    bf16x8 qb[kColBlocks][NK];
+    int wave_maxpos = -1;
+#pragma unroll
+    for (int b = 0; b < kColBlocks; ++b) {
+        const int c = b * 16 + j;
+        const int tl = c / G, hd = c - tl * G;
+        const int tok = tile * WT + wv * TW + tl;
+        const bool ok = c < TW * G && tok < n_new;
+        pos[b] = ok ? base_pos + tok : -1;
+        orow[b] = ((size_t)(first + (ok ? tok : 0)) * a.num_q_heads + g * G + hd) * D;
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            uint4 t = make_uint4(0, 0, 0, 0);
+            if (ok) t = *reinterpret_cast<const uint4 *>(static_cast<const char *>(a.q) + (orow[b] + 32 * i + 8 * qd) * 2);
+            qb[b][i] = __builtin_bit_cast(bf16x8, t);
+        }
+        wave_maxpos = max(wave_maxpos, pos[b]);
+    }
+#pragma unroll
+    for (int dlt = 32; dlt >= 1; dlt >>= 1) wave_maxpos = max(wave_maxpos, __shfl_xor(wave_maxpos, dlt));
+    const int wg_maxpos = base_pos + min(n_new, (tile + 1) * WT) - 1;
+    const int n_stages = wg_maxpos / kStage + 1;
+
+    float m[kColBlocks], l[kColBlocks];
+    f32x4 o[kColBlocks][NS];                          // out^T: dims 16 s + 4 qd + e, this lane's column
+#pragma unroll
+    for (int b = 0; b < kColBlocks; ++b) {
+        m[b] = kLowest;
+        l[b] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) o[b][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int32_t *table = a.block_table + (size_t)r * a.max_blocks;
+    const size_t tile_bytes = (size_t)a.block_size * D * 2;
+    const size_t block_stride = (size_t)a.num_layers * a.num_kv_heads * tile_bytes;
+    const size_t head_off = ((size_t)a.layer * a.num_kv_heads + g) * tile_bytes;
+    const char *kp = static_cast<const char *>(a.k_pool) + head_off;
+    const char *vp = static_cast<const char *>(a.v_pool) + head_off;
+
+    // stage st -> registers: unit x of the stage is sub-tile x / U, 16-byte unit x % U of it
+    uint4 kreg[LPT], vreg[LPT];
+    auto fetch = [&](int st) {
+#pragma unroll
+        for (int k = 0; k < LPT; ++k) {
+            const int x = tid + kThreads * k;
+            const int t = st * kStage + 16 * (x / U);
+            kreg[k] = vreg[k] = make_uint4(0, 0, 0, 0);
+            if (st < n_stages && t <= wg_maxpos) {
+                const size_t off = (size_t)table[t >> a.log2_block_size] * block_stride +
+                                   (size_t)((t & (a.block_size - 1)) >> 4) * (16 * D * 2) + (size_t)(x % U) * 16;
+                kreg[k] = *reinterpret_cast<const uint4 *>(kp + off);
+                vreg[k] = *reinterpret_cast<const uint4 *>(vp + off);
+            }
+        }
+    };
+    // registers -> LDS; value slots at or past the context's end are zeroed (they may hold
+    // anything, and a zero weight does not silence a NaN)
+    auto stash = [&](int st) {
+#pragma unroll
+        for (int k = 0; k < LPT; ++k) {
+            const int x = tid + kThreads * k;
+            const int u = x / U, unit = x % U;
+            const int t = st * kStage + 16 * u;
+            uint4 v = vreg[k];
+            size_t where;
+            if (TILED) {
+                where = (size_t)u * SUBB + (size_t)unit * 16;
+                const int valid = C - (t + 4 * ((unit >> 4) & 3));     // of the unit's four positions
+                if (valid < 4) {
+                    const uint32_t m01 = valid >= 2 ? 0xFFFFFFFFu : (valid == 1 ? 0x0000FFFFu : 0u);
+                    const uint32_t m23 = valid >= 4 ? 0xFFFFFFFFu : (valid == 3 ? 0x0000FFFFu : 0u);
+                    v.x &= m01; v.z &= m01;
+                    v.y &= m23; v.w &= m23;
+                }
+            } else {
+                const int row = unit / (D / 8), c16 = unit % (D / 8);
+                where = (size_t)u * SUBB + (size_t)row * ROWB + (size_t)c16 * 16;
+                if (t + row >= C) v = make_uint4(0, 0, 0, 0);
+            }
+            *reinterpret_cast<uint4 *>(lds_k + where) = kreg[k];
+            *reinterpret_cast<uint4 *>(lds_v + where) = v;
+        }
+    };
+
+    fetch(0);
+    for (int st = 0; st < n_stages; ++st) {
+        __syncthreads();                              // everyone is done with the previous stage
+        stash(st);
+        __syncthreads();
+        fetch(st + 1);                                // in flight while this stage is consumed
+        const int t0 = st * kStage;
+        if (t0 > wave_maxpos) continue;               // wave-uniform: nothing here for this wave's columns
+
+        // operands of the stage, read once for the four column blocks
+        bf16x8 ka[2][NK];                             // K rows: position t0 + 16 u + j, dims 32 i + 8 qd ..
+        bf16x8 va[NS];                                // V^T rows: dim 16 s + j, positions 4 qd .. (both halves)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < NK; ++i) {
+                const size_t where = TILED ? (size_t)u * SUBB + (size_t)((4 * i + qd) * 16 + j) * 16
+                                           : (size_t)u * SUBB + (size_t)j * ROWB + (size_t)(32 * i + 8 * qd) * 2;
+                ka[u][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(lds_k + where));
+            }
+        if (TILED) {
+#pragma unroll
+            for (int i = 0; i < NS / 2; ++i) {
+                const size_t where = (size_t)((i * 4 + qd) * 16 + j) * 16;
+                const uint4 v0 = *reinterpret_cast<const uint4 *>(lds_v + where);
+                const uint4 v1 = *reinterpret_cast<const uint4 *>(lds_v + SUBB + where);
+                va[2 * i] = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
+                va[2 * i + 1] = __builtin_bit_cast(bf16x8, make_uint4(v0.z, v0.w, v1.z, v1.w));
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                u16x8 t;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    t[e] = *reinterpret_cast<const unsigned short *>(
+                        lds_v + (size_t)(e >> 2) * SUBB + (size_t)(4 * qd + (e & 3)) * ROWB + (size_t)(16 * s + j) * 2);
+                va[s] = __builtin_bit_cast(bf16x8, t);
+            }
+        }
+
+#pragma unroll
+        for (int b = 0; b < kColBlocks; ++b) {
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};   // positions t0 (+16) + 4 qd + e
+#pragma unroll
+            for (int i = 0; i < NK; ++i) {
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][i], qb[b][i], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][i], qb[b][i], s1, 0, 0, 0);
+            }
+            float sc[8];
+            float mx = kLowest;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int t = t0 + 16 * (e >> 2) + 4 * qd + (e & 3);
+                const float x = (e < 4 ? s0[e] : s1[e - 4]) * a.scale_log2e;
+                sc[e] = t <= pos[b] ? x : -INFINITY;    // a token sees the positions up to its own
+                mx = fmaxf(mx, sc[e]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float mn = fmaxf(m[b], mx);
+            const float f = fast_exp2(m[b] - mn);
+            m[b] = mn;
+            float ps = 0.0f;
+            bf16x8 pw;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float w = fast_exp2(sc[e] - mn);
+                ps += w;
+                pw[e] = (__bf16)w;
+            }
+            l[b] = l[b] * f + ps;
+            if (__any(f != 1.0f)) {                   // the running max moved somewhere in the wave
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[b][s][e] *= f;
+            }
+#pragma unroll
+            for (int s = 0; s < NS; ++s) o[b][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[s], pw, o[b][s], 0, 0, 0);
+        }
+    }
+
+#pragma unroll
+    for (int b = 0; b < kColBlocks; ++b) {
+        float lt = l[b];                              // kept per position group: add the four
+        lt += __shfl_xor(lt, 16);
+        lt += __shfl_xor(lt, 32);
+        if (pos[b] < 0) continue;
+        const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
+        uint16_t *dst = static_cast<uint16_t *>(a.out) + orow[b];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            uint2 w;
+            w.x = (uint32_t)to_bf16_rne(o[b][s][0] * inv) | ((uint32_t)to_bf16_rne(o[b][s][1] * inv) << 16);
+            w.y = (uint32_t)to_bf16_rne(o[b][s][2] * inv) | ((uint32_t)to_bf16_rne(o[b][s][3] * inv) << 16);
+            *reinterpret_cast<uint2 *>(dst + 16 * s + 4 * qd) = w;
+        }
+    }
+}
+
+template <int D, bool TILED>
+hipError_t launch_mfma_prefill(const PrefillArgs &p, hipStream_t s)
+{
+    constexpr int kCols = D > 128 ? 32 : kMaxCols;
+    const int G = p.d.num_q_heads / p.d.num_kv_heads;
+    const int WT = kWaves * (kCols / G);
+    const int tiles = (p.max_new_tokens + WT - 1) / WT;
+    if (tiles < 1 || p.d.num_kv_heads > 65535 || p.d.batch > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((prefill_mfma<D, TILED, kCols>), dim3((unsigned)tiles, (unsigned)p.d.num_kv_heads, (unsigned)p.d.batch),
+                       dim3(kThreads), 0, s, p);
+    return hipGetLastError();
+}
+
 template <typename R>
 hipError_t launch_rows(const PrefillArgs &p, hipStream_t s)
 {
@@ -87,6 +343,12 @@ hipError_t launch_prefill(const PrefillArgs &p, hipStream_t stream)
     if (a.heads_per_pass != decode_heads_per_pass(a.bf16, a.head_dim, G) || a.heads_per_pass == 0)
         return hipErrorInvalidValue;
     const int lpt = a.head_dim * (a.bf16 ? 2 : 4) / 16;
+    if (a.bf16 && G <= (a.head_dim > 128 ? 32 : kMaxCols) && !p.force_rows) {     // matrix cores
+        const bool tiled = decode_uses_tiled_layout(a.bf16, G);
+        if (a.head_dim == 64) return tiled ? launch_mfma_prefill<64, true>(p, stream) : launch_mfma_prefill<64, false>(p, stream);
+        if (a.head_dim == 128) return tiled ? launch_mfma_prefill<128, true>(p, stream) : launch_mfma_prefill<128, false>(p, stream);
+        if (a.head_dim == 256) return tiled ? launch_mfma_prefill<256, true>(p, stream) : launch_mfma_prefill<256, false>(p, stream);
+    }
     if (decode_uses_tiled_layout(a.bf16, G)) {
         if (a.heads_per_pass > 16) return hipErrorInvalidValue;
         if (a.head_dim == 64) return launch_rows<MfmaReducer<64>>(p, stream);

@@ -23,6 +23,10 @@ CASES = [
     ("bf16", 16, 1, 256, 16, [(70, 70), (31, 2)]),
     ("bf16", 32, 1, 128, 16, [(45, 45), (20, 3)]),                                   # 32 heads per kv head
     ("bf16", 2, 2, 64, 64, [(150, 150)]),
+    ("bf16", 4, 4, 128, 16, [(700, 700), (300, 37)]),                                # several q tiles and stages
+    ("bf16", 8, 2, 128, 16, [(333, 333), (500, 100)]),
+    ("bf16", 6, 2, 128, 16, [(100, 100), (77, 10)]),                                 # group of 3
+    ("bf16", 4, 4, 256, 16, [(90, 90), (50, 6)]),
 ]
 
 
@@ -42,8 +46,10 @@ def _setup(dtype, H, Hkv, D, bs, reqs, seed):
     return geom, rig, table, K, V, ctx, new, q_start
 
 
+@pytest.mark.parametrize("rows_kernel", [False, True])
 @pytest.mark.parametrize("dtype,H,Hkv,D,bs,reqs", CASES)
-def test_append_tokens_then_prefill_attention(dtype, H, Hkv, D, bs, reqs):
+def test_append_tokens_then_prefill_attention(dtype, H, Hkv, D, bs, reqs, rows_kernel):
+    """Both kernels: matrix cores where the geometry allows (bf16), and one wavefront per token."""
     seed = 9000 + D + bs + H
     geom, rig, table, K, V, ctx, new, q_start = _setup(dtype, H, Hkv, D, bs, reqs, seed)
     total = int(q_start[-1])
@@ -58,7 +64,8 @@ def test_append_tokens_then_prefill_attention(dtype, H, Hkv, D, bs, reqs):
     with torch.cuda.stream(rig.compute):
         kd, vd, qd = n2t(k_new, dev), n2t(v_new, dev), n2t(q, dev)
         rig.lamps.kv_append_tokens(0, len(reqs), total, kd, vd, sd, td, cd)
-        rig.lamps.prefill_attn(0, len(reqs), total, qd, sd, td, cd, out)
+        rig.lamps.prefill_attn(0, len(reqs), total, qd, sd, td, cd, out,
+                               max_new_tokens=-1 if rows_kernel else max(new))
     rig.compute.synchronize()
     # the cache now holds the full sequences, and nothing else changed
     kp = np.full(geom.pool_shape, W.poison(geom), dtype=geom.np_dtype)
