@@ -52,6 +52,9 @@ def parse():
                          "traffic, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--geom", default="",
                     help="diagnostic: override geometry, e.g. H=8,Hkv=8,bs=32,B=64,MB=128,NB=50000")
+    ap.add_argument("--prefill", default="",
+                    help="measure lamps_prefill_attn instead (Discard's recompute): "
+                         "'H,Hkv,D,requests,tokens[,cached]', e.g. 40,40,128,4,4096")
     ap.add_argument("--table", choices=["random", "sequential"], default="random",
                     help="physical placement of the blocks (sequential is a diagnostic)")
     return ap.parse_args()
@@ -283,6 +286,102 @@ def cpu_baseline(job):
             "max_abs_err_gpu_vs_oracle": err}
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0    # MI355X published dense bf16 matrix peak
+
+
+def prefill_bench(a):
+    """lamps_kv_append_tokens + lamps_prefill_attn for `requests` requests of `tokens` new tokens
+    each on top of `cached` old ones (0 = a discarded context recomputed from scratch), one layer,
+    bf16.  Bound by the matrix cores: flops = 4 * D * H * (query, key) pairs."""
+    import torch
+
+    import lamps_workloads as W
+    import oracle
+    import paper_2410_18248_amd as P
+    f = [int(x) for x in a.prefill.split(",")]
+    H, Hkv, D, n_req, n_new = f[:5]
+    cached = f[5] if len(f) > 5 else 0
+    bs = 16
+    C = cached + n_new
+    per = (C + bs - 1) // bs
+    nb = n_req * per + 8
+    dev = torch.device("cuda:0")
+    cfg = P.LampsConfig(1, H, Hkv, D, bs, nb, per, n_req, P.LAMPS_BF16, 0.0, 0, 0)
+    g = W.Geometry(1, H, Hkv, D, bs, nb, per, "bf16")
+    gen = torch.Generator(device=dev).manual_seed(W.config_seed(5))
+    k_pool = torch.empty(g.pool_shape, dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+    v_pool = torch.empty(g.pool_shape, dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+    ws = torch.empty(P.lamps_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+    cs = torch.cuda.Stream(dev)
+    torch.cuda.synchronize()
+    lam = P.Lamps(cfg, k_pool, v_pool, ws, cs.cuda_stream, cs.cuda_stream, cs.cuda_stream)
+    lam.alloc_blocks(nb)
+    perm = W.permutation(W.config_seed(5) + 1, nb)
+    table, _ = W.deal_block_table(perm, [C] * n_req, g)
+    td = torch.as_tensor(table, device=dev)
+    cd = torch.full((n_req,), C, dtype=torch.int32, device=dev)
+    sd = torch.arange(0, (n_req + 1) * n_new, n_new, dtype=torch.int32, device=dev)
+    total = n_req * n_new
+    q = torch.empty((total, H, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+    kn = torch.empty((total, Hkv, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+    vn = torch.empty((total, Hkv, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+    out = torch.empty_like(q)
+    steps = a.steps if a.steps > 0 else 20
+    warmup = a.warmup if a.warmup >= 0 else 3
+
+    def run(k, append):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(cs)
+        for _ in range(k):
+            if append:
+                lam.kv_append_tokens(0, n_req, total, kn, vn, sd, td, cd)
+            lam.prefill_attn(0, n_req, total, q, sd, td, cd, out, max_new_tokens=n_new)
+        e1.record(cs)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, e0.elapsed_time(e1) * 1e-3
+    run(warmup, True)
+    wall, dev_s = run(steps, True)
+    _, attn_s = run(steps, False)
+    pairs = n_req * sum(cached + i + 1 for i in range(n_new))
+    flops = 4.0 * D * H * pairs
+    achieved = flops / (attn_s / steps) / 1e12
+    # parity on sampled rows against the oracle (un-paged by the harness)
+    k_index, v_index = g.tile_index_maps()
+
+    def logical(pool, index_map, r):
+        ids = torch.as_tensor(table[r, :per].astype(np.int64), device=dev)
+        x = pool[ids, 0].cpu().view(torch.int16).numpy().view(np.uint16)
+        return W.tiles_to_logical(x, index_map, C)
+    rows = sorted(set([0, 1, n_new // 2, n_new - 1]))
+    K, V = logical(k_pool, k_index, 0), logical(v_pool, v_index, 0)
+    qh = q[:n_new].cpu().view(torch.int16).numpy().view(np.uint16)
+    got = out[:n_new].cpu().to(torch.float64).numpy()
+    t0 = time.perf_counter()
+    ref = oracle.decode_attn(qh[rows], [K] * len(rows), [V] * len(rows), [cached + i + 1 for i in rows],
+                             [1] * len(rows), threads=len(os.sched_getaffinity(0)))
+    cpu_s = time.perf_counter() - t0
+    err = float(np.abs(got[rows] - ref).max())
+    cpu_pairs = sum(cached + i + 1 for i in rows)
+    line = {"metric": "prefill-attention tokens/s (Discard's recompute, one layer)",
+            "value": total * steps / wall, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": wall / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "prefill-%dx%d-new-on-%d-cached-H%d-Hkv%d-D%d" % (n_req, n_new, cached, H, Hkv, D)},
+            "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "prefill_mfma",
+                         "algorithmic_flops_per_launch": flops, "kernel_us": attn_s / steps * 1e6,
+                         "append_plus_attention_us": dev_s / steps * 1e6},
+            "cpu_baseline": {"value": cpu_pairs / cpu_s * (total / pairs), "unit": "tokens/s",
+                             "cores": len(os.sched_getaffinity(0)), "kind": "oracle",
+                             "sample": "%d rows of request 0 (%d query-key pairs, %.2f s), scaled by pairs per token"
+                                       % (len(rows), cpu_pairs, cpu_s),
+                             "max_abs_err_gpu_vs_oracle": err}}
+    lam.destroy()
+    print(json.dumps(line))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -293,6 +392,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if a.prefill:
+        prefill_bench(a)
+        return
     job = Job(a.config, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom)
     with_swap = not a.no_swap
 

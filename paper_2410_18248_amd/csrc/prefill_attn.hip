@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
 // 32 cached positions cost 2 D/32 + D/16 MFMAs (16x16x32) per 16 columns.
 //
 // One workgroup = one (request, kv head, tile of new tokens); its four waves each
-// own kCols = 64 columns (kCols / G tokens x G heads) as blocks of 16.  K and V
+// own kCols = 32 columns (kCols / G tokens x G heads) as blocks of 16.  K and V
 // are streamed 32 positions at a time: all 256 threads load the next stage from
 // the paged pools into registers while the current one, in LDS, is consumed;
 // every wave reads each K / V operand from LDS once per stage and uses it for
@@ -70,12 +70,15 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
 // a stage's two 16-position halves share one 32-deep MFMA (the contraction index
 // may be permuted as long as both operands agree).
 //
-// LDS holds the pool tiles as they are (tiled layout: 16-byte runs are operands
-// already) or, for the plain layout, rows padded by 16 bytes so that the 16 rows
-// of a K operand fall in different banks; V operands of the plain layout are
-// gathered with 16-bit LDS reads (the transposition a row-major V needs).
-constexpr int kMaxCols = 64;             // columns per wave (32 at head_dim 256: accumulators fill the registers)
+// LDS holds the pool tiles as they are for the tiled layout (16-byte runs are
+// operands already).  For the plain layout K rows are padded by 16 bytes so that
+// the 16 rows of a K operand fall in different banks, and V -- whose row-major
+// order would need a transposition at every operand read -- is scattered into
+// the tiled order once, 16 bits at a time, when the stage is written to LDS.
+constexpr int kMaxCols = 32;             // columns per wave: two blocks of 16 keep a wave under 256 registers,
+                                         // so two workgroups share a CU and cover each other's stalls
 constexpr int kStage = 32;               // cached positions per LDS stage
+constexpr float kSlack = 8.0f;           // log2 of the largest weight before the reference moves
 
 typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
 
@@ -88,10 +91,13 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
     constexpr int U = D * 2;                         // 16-byte units of one 16-position sub-tile
     constexpr int LPT = (2 * U) / kThreads;          // units per thread, pool and stage
     constexpr int ROWB = D * 2 + 16;                 // plain layout: padded row, bytes
-    constexpr int SUBB = TILED ? 16 * D * 2 : 16 * ROWB;
+    constexpr int SUBB = TILED ? 16 * D * 2 : 16 * ROWB;   // K sub-tile in LDS
+    // V sub-tile in LDS: always the tiled order, each 1 KiB group of 32 dims shifted by 16
+    // bytes so that the scattered 16-bit writes of the plain layout spread over the banks
+    constexpr int SUBV = 16 * D * 2 + (D / 32) * 16;
     static_assert(LPT >= 1 && (2 * U) % kThreads == 0, "head_dim");
     __shared__ __align__(16) char lds_k[2 * SUBB];
-    __shared__ __align__(16) char lds_v[2 * SUBB];
+    __shared__ __align__(16) char lds_v[2 * SUBV];
 
     const DecodeArgs &a = p.d;
     const int r = blockIdx.z, g = blockIdx.y;
@@ -110,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
     int pos[kColBlocks];                             // -1: no such column
     size_t orow[kColBlocks];                         // element offset of its output row
     bf16x8 qb[kColBlocks][NK];
-    int wave_maxpos = -1;
+    int wave_maxpos = -1, wave_minpos = 0x7fffffff;  // over the wave's valid columns
 #pragma unroll
     for (int b = 0; b < kColBlocks; ++b) {
         const int c = b * 16 + j;
@@ -126,9 +132,13 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
             qb[b][i] = __builtin_bit_cast(bf16x8, t);
         }
         wave_maxpos = max(wave_maxpos, pos[b]);
+        if (ok) wave_minpos = min(wave_minpos, pos[b]);
     }
 #pragma unroll
-    for (int dlt = 32; dlt >= 1; dlt >>= 1) wave_maxpos = max(wave_maxpos, __shfl_xor(wave_maxpos, dlt));
+    for (int dlt = 32; dlt >= 1; dlt >>= 1) {
+        wave_maxpos = max(wave_maxpos, __shfl_xor(wave_maxpos, dlt));
+        wave_minpos = min(wave_minpos, __shfl_xor(wave_minpos, dlt));
+    }
     const int wg_maxpos = base_pos + min(n_new, (tile + 1) * WT) - 1;
     const int n_stages = wg_maxpos / kStage + 1;
 
@@ -174,9 +184,8 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
             const int u = x / U, unit = x % U;
             const int t = st * kStage + 16 * u;
             uint4 v = vreg[k];
-            size_t where;
             if (TILED) {
-                where = (size_t)u * SUBB + (size_t)unit * 16;
+                const size_t where = (size_t)u * SUBB + (size_t)unit * 16;
                 const int valid = C - (t + 4 * ((unit >> 4) & 3));     // of the unit's four positions
                 if (valid < 4) {
                     const uint32_t m01 = valid >= 2 ? 0xFFFFFFFFu : (valid == 1 ? 0x0000FFFFu : 0u);
@@ -184,13 +193,23 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
                     v.x &= m01; v.z &= m01;
                     v.y &= m23; v.w &= m23;
                 }
+                *reinterpret_cast<uint4 *>(lds_k + where) = kreg[k];
+                *reinterpret_cast<uint4 *>(lds_v + (size_t)u * SUBV + (size_t)unit * 16 + (size_t)(unit >> 6) * 16) = v;
             } else {
-                const int row = unit / (D / 8), c16 = unit % (D / 8);
-                where = (size_t)u * SUBB + (size_t)row * ROWB + (size_t)c16 * 16;
+                const int row = unit / (D / 8), c16 = unit % (D / 8);     // position t + row, dims 8 c16 ..
+                *reinterpret_cast<uint4 *>(lds_k + (size_t)u * SUBB + (size_t)row * ROWB + (size_t)c16 * 16) = kreg[k];
                 if (t + row >= C) v = make_uint4(0, 0, 0, 0);
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                // element (row, d) of the sub-tile goes where the tiled layout of lamps.h puts it
+                uint16_t *dst = reinterpret_cast<uint16_t *>(lds_v + (size_t)u * SUBV);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int d = 8 * c16 + e;
+                    const int at = ((((d >> 5) * 4 + (row >> 2)) * 16 + (d & 15)) * 2 + ((d & 31) >> 4)) * 4 + (row & 3) +
+                                   (d >> 5) * 8;
+                    dst[at] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                }
             }
-            *reinterpret_cast<uint4 *>(lds_k + where) = kreg[k];
-            *reinterpret_cast<uint4 *>(lds_v + where) = v;
         }
     };
 
@@ -203,77 +222,82 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
         const int t0 = st * kStage;
         if (t0 > wave_maxpos) continue;               // wave-uniform: nothing here for this wave's columns
 
-        // operands of the stage, read once for the four column blocks
-        bf16x8 ka[2][NK];                             // K rows: position t0 + 16 u + j, dims 32 i + 8 qd ..
-        bf16x8 va[NS];                                // V^T rows: dim 16 s + j, positions 4 qd .. (both halves)
+        // Operand-major order: every K / V operand is read from LDS once and used at once
+        // for all column blocks (independent MFMAs back to back, few operand registers
+        // alive), so the accumulators can stay in the accumulation registers for the
+        // whole loop and only the scores and weights pass through the vector ALUs.
+        f32x4 sc0[kColBlocks], sc1[kColBlocks];        // positions t0 (+16) + 4 qd + e of the lane's column
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int b = 0; b < kColBlocks; ++b) sc0[b] = sc1[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < NK; ++i) {
-                const size_t where = TILED ? (size_t)u * SUBB + (size_t)((4 * i + qd) * 16 + j) * 16
-                                           : (size_t)u * SUBB + (size_t)j * ROWB + (size_t)(32 * i + 8 * qd) * 2;
-                ka[u][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(lds_k + where));
-            }
-        if (TILED) {
+        for (int i = 0; i < NK; ++i) {
+            // K rows: position t0 + 16 u + j, dims 32 i + 8 qd ..
+            const size_t where = TILED ? (size_t)((4 * i + qd) * 16 + j) * 16
+                                       : (size_t)j * ROWB + (size_t)(32 * i + 8 * qd) * 2;
+            const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(lds_k + where));
+            const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(lds_k + SUBB + where));
 #pragma unroll
-            for (int i = 0; i < NS / 2; ++i) {
-                const size_t where = (size_t)((i * 4 + qd) * 16 + j) * 16;
-                const uint4 v0 = *reinterpret_cast<const uint4 *>(lds_v + where);
-                const uint4 v1 = *reinterpret_cast<const uint4 *>(lds_v + SUBB + where);
-                va[2 * i] = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
-                va[2 * i + 1] = __builtin_bit_cast(bf16x8, make_uint4(v0.z, v0.w, v1.z, v1.w));
-            }
-        } else {
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                u16x8 t;
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    t[e] = *reinterpret_cast<const unsigned short *>(
-                        lds_v + (size_t)(e >> 2) * SUBB + (size_t)(4 * qd + (e & 3)) * ROWB + (size_t)(16 * s + j) * 2);
-                va[s] = __builtin_bit_cast(bf16x8, t);
+            for (int b = 0; b < kColBlocks; ++b) {
+                sc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qb[b][i], sc0[b], 0, 0, 0);
+                sc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qb[b][i], sc1[b], 0, 0, 0);
             }
         }
 
+        bf16x8 pw[kColBlocks];                         // weights, transposed: the second product's operand
+        const bool all_visible = t0 + kStage - 1 <= wave_minpos;   // wave-uniform
 #pragma unroll
         for (int b = 0; b < kColBlocks; ++b) {
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};   // positions t0 (+16) + 4 qd + e
-#pragma unroll
-            for (int i = 0; i < NK; ++i) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][i], qb[b][i], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][i], qb[b][i], s1, 0, 0, 0);
-            }
-            float sc[8];
-            float mx = kLowest;
+            float sc[8];                              // raw scores; scale_log2e > 0 is applied in the exponent
+            float mx = -INFINITY;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
+                const float x = e < 4 ? sc0[b][e] : sc1[b][e - 4];
                 const int t = t0 + 16 * (e >> 2) + 4 * qd + (e & 3);
-                const float x = (e < 4 ? s0[e] : s1[e - 4]) * a.scale_log2e;
-                sc[e] = t <= pos[b] ? x : -INFINITY;    // a token sees the positions up to its own
+                sc[e] = (all_visible || t <= pos[b]) ? x : -INFINITY;   // a token sees the positions up to its own
                 mx = fmaxf(mx, sc[e]);
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float mn = fmaxf(m[b], mx);
-            const float f = fast_exp2(m[b] - mn);
-            m[b] = mn;
-            float ps = 0.0f;
-            bf16x8 pw;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float w = fast_exp2(sc[e] - mn);
-                ps += w;
-                pw[e] = (__bf16)w;
-            }
-            l[b] = l[b] * f + ps;
-            if (__any(f != 1.0f)) {                   // the running max moved somewhere in the wave
+            mx *= a.scale_log2e;
+            // The reference point of the exponentials follows the running maximum lazily:
+            // it moves only when a score exceeds it by more than kSlack, so weights stay
+            // below 2^kSlack, the four lanes that share a column compare notes only then,
+            // and the accumulators (which live in accumulation registers the vector ALUs
+            // cannot touch without moving them) are rescaled a handful of times per column.
+            float f = 1.0f;
+            if (__any(mx - m[b] > kSlack)) {          // wave-uniform, rare after the first stages
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float mn = mx - m[b] > kSlack ? mx : m[b];
+                f = fast_exp2(m[b] - mn);
+                m[b] = mn;
 #pragma unroll
                 for (int s = 0; s < NS; ++s)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o[b][s][e] *= f;
             }
+            const float mn = m[b];
+            float ps = 0.0f;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) o[b][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[s], pw, o[b][s], 0, 0, 0);
+            for (int e = 0; e < 8; ++e) {
+                const float w = fast_exp2(fmaf(sc[e], a.scale_log2e, -mn));
+                ps += w;
+                pw[b][e] = (__bf16)w;
+            }
+            l[b] = l[b] * f + ps;
+        }
+
+#pragma unroll
+        for (int i = 0; i < NS / 2; ++i) {
+            // V^T rows: dims 32 i + j (x, y) and 32 i + 16 + j (z, w), positions 4 qd .. of each half
+            const size_t where = (size_t)((i * 4 + qd) * 16 + j) * 16 + (size_t)i * 16;
+            const uint4 v0 = *reinterpret_cast<const uint4 *>(lds_v + where);
+            const uint4 v1 = *reinterpret_cast<const uint4 *>(lds_v + SUBV + where);
+            const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
+            const bf16x8 vb = __builtin_bit_cast(bf16x8, make_uint4(v0.z, v0.w, v1.z, v1.w));
+#pragma unroll
+            for (int b = 0; b < kColBlocks; ++b) {
+                o[b][2 * i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pw[b], o[b][2 * i], 0, 0, 0);
+                o[b][2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, pw[b], o[b][2 * i + 1], 0, 0, 0);
+            }
         }
     }
 
@@ -298,7 +322,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
 template <int D, bool TILED>
 hipError_t launch_mfma_prefill(const PrefillArgs &p, hipStream_t s)
 {
-    constexpr int kCols = D > 128 ? 32 : kMaxCols;
+    constexpr int kCols = kMaxCols;
     const int G = p.d.num_q_heads / p.d.num_kv_heads;
     const int WT = kWaves * (kCols / G);
     const int tiles = (p.max_new_tokens + WT - 1) / WT;
@@ -343,7 +367,7 @@ hipError_t launch_prefill(const PrefillArgs &p, hipStream_t stream)
     if (a.heads_per_pass != decode_heads_per_pass(a.bf16, a.head_dim, G) || a.heads_per_pass == 0)
         return hipErrorInvalidValue;
     const int lpt = a.head_dim * (a.bf16 ? 2 : 4) / 16;
-    if (a.bf16 && G <= (a.head_dim > 128 ? 32 : kMaxCols) && !p.force_rows) {     // matrix cores
+    if (a.bf16 && G <= kMaxCols && !p.force_rows) {     // matrix cores
         const bool tiled = decode_uses_tiled_layout(a.bf16, G);
         if (a.head_dim == 64) return tiled ? launch_mfma_prefill<64, true>(p, stream) : launch_mfma_prefill<64, false>(p, stream);
         if (a.head_dim == 128) return tiled ? launch_mfma_prefill<128, true>(p, stream) : launch_mfma_prefill<128, false>(p, stream);
