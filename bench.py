@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--part-tokens", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-swap", action="store_true", help="decode only (for profiling)")
+    ap.add_argument("--staging-mib", type=int, default=0, help="lamps_config.staging_bytes in MiB (0 = default)")
+    ap.add_argument("--direct-copy-bytes", type=int, default=0,
+                    help="lamps_config.direct_copy_bytes (0 = staged through the gather kernels, the default)")
     ap.add_argument("--ctx-override", type=int, default=0,
                     help="diagnostic: give every request this context length")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -64,7 +67,7 @@ class Job:
     """Device-resident state of one benchmark workload."""
 
     def __init__(self, cfg_id, rotations, part_tokens, table_kind="random", ctx_override=0,
-                 geom_override=""):
+                 geom_override="", direct_copy_bytes=0, staging_mib=0):
         import torch
 
         import lamps_workloads as W
@@ -101,7 +104,7 @@ class Job:
         self.cfg = P.LampsConfig(g.num_layers, g.num_q_heads, g.num_kv_heads, g.head_dim,
                                  g.block_size, g.num_blocks, g.max_blocks_per_req, wl.batch,
                                  P.LAMPS_BF16 if g.dtype == "bf16" else P.LAMPS_F32, 0.0,
-                                 part_tokens, 0)
+                                 part_tokens, staging_mib << 20, direct_copy_bytes)
         tdt = torch.bfloat16 if g.dtype == "bf16" else torch.float32
         seed = W.config_seed(cfg_id)
         gen = torch.Generator(device=dev).manual_seed(seed)
@@ -395,7 +398,7 @@ def main():
     if a.prefill:
         prefill_bench(a)
         return
-    job = Job(a.config, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom)
+    job = Job(a.config, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom, a.direct_copy_bytes, a.staging_mib)
     with_swap = not a.no_swap
 
     # calibrate: one short train to size the run

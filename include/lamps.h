@@ -92,6 +92,12 @@ typedef struct {
                                    partitions of this many tokens, multiple of
                                    block_size                                        */
     int64_t staging_bytes;      /* device staging per swap direction; 0 => default   */
+    int64_t direct_copy_bytes;  /* a block whose share of ONE pool (all layers) is at
+                                   least this large is swapped as two plain copies
+                                   between the pools and the host buffer: no gather
+                                   kernel, no staging, nothing runs on the compute
+                                   units.  0 or < 0 => never (the default: on this
+                                   hardware the staged path is the faster one)       */
 } lamps_config;
 
 /* ---- sizes (pure functions of the config; return 0 on an invalid config) ---- */
@@ -215,7 +221,8 @@ int lamps_prefill_attn(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t tot
  * completes) on the swap-out stream: blocks are gathered into contiguous
  * device staging, then moved by hipMemcpyAsync.  The copy is ordered after all
  * compute-stream work enqueued before this call and after earlier swap-ins
- * into the same blocks.  The pool is not modified and the blocks stay
+ * into the same blocks.  Large blocks (direct_copy_bytes) skip the gather: each
+ * is two hipMemcpyAsync straight from the pools, same host image.  The pool is not modified and the blocks stay
  * allocated; the caller frees them afterwards with lamps_free_blocks.  The
  * library remembers the unfinished copy per block, so that a later swap-in
  * into a re-allocated block, or lamps_compute_wait_blocks, is ordered behind

@@ -32,7 +32,8 @@ class LampsConfig(ctypes.Structure):
                 ("block_size", ctypes.c_int32), ("num_blocks", ctypes.c_int32),
                 ("max_blocks_per_req", ctypes.c_int32), ("max_batch", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
-                ("part_tokens", ctypes.c_int32), ("staging_bytes", ctypes.c_int64)]
+                ("part_tokens", ctypes.c_int32), ("staging_bytes", ctypes.c_int64),
+                ("direct_copy_bytes", ctypes.c_int64)]
 
 
 def lib_path():

@@ -30,6 +30,7 @@ struct Derived {
     size_t elem = 0, half_bytes = 0, block_bytes = 0, pool_bytes = 0;
     size_t partial_bytes = 0, prefix_bytes = 0, staging_bytes = 0, workspace_bytes = 0;
     int part_tokens = 0, max_parts = 0, log2_bs = 0, blocks_per_chunk = 0;
+    bool direct_copy = false;           // blocks are large enough to be copied one by one, unstaged
     float scale_log2e = 0.f;
 };
 
@@ -82,6 +83,7 @@ const char *derive(const lamps_config *c, Derived *d)
     d->staging_bytes = bpc * d->block_bytes;
     d->workspace_bytes = align256(d->partial_bytes) + align256(d->prefix_bytes) +
                          2 * align256(d->staging_bytes);
+    d->direct_copy = c->direct_copy_bytes > 0 && (int64_t)d->half_bytes >= c->direct_copy_bytes;
     const float scale = c->softmax_scale != 0.f ? c->softmax_scale : 1.0f / std::sqrt((float)c->head_dim);
     d->scale_log2e = scale * 1.4426950408889634f;
     return nullptr;
@@ -533,8 +535,10 @@ int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host
     retire_finished(c);
     int32_t *ids = nullptr;
     size_t slots = 0;
-    if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
-    if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
+    if (!c->d.direct_copy) {                        // the gather kernel reads the ids from the pinned ring
+        if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
+        if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
+    }
     hipEvent_t ev;
     if ((rc = new_event(c, &ev)) != LAMPS_OK) return rc;
 
@@ -546,6 +550,16 @@ int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host
     const size_t total = (size_t)n * c->d.block_bytes;
     if ((rc = wait_host_overlap(c, c->os, host, host + total, false)) != LAMPS_OK) return rc;
 
+    if (c->d.direct_copy) {
+        // each block is two long contiguous runs: the copy engines take them as they are
+        for (int32_t i = 0; i < n; ++i) {
+            const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
+            LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes, c->k_pool + at, c->d.half_bytes,
+                                     hipMemcpyDeviceToHost, c->os));
+            LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes + c->d.half_bytes, c->v_pool + at,
+                                     c->d.half_bytes, hipMemcpyDeviceToHost, c->os));
+        }
+    } else
     for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
         const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
         LAMPS_HIP(lamps::launch_gather(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
@@ -573,8 +587,10 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
     retire_finished(c);
     int32_t *ids = nullptr;
     size_t slots = 0;
-    if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
-    if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
+    if (!c->d.direct_copy) {
+        if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
+        if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
+    }
     hipEvent_t ev;
     if ((rc = new_event(c, &ev)) != LAMPS_OK) return rc;
 
@@ -587,6 +603,15 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
     const size_t total = (size_t)n * c->d.block_bytes;
     if ((rc = wait_host_overlap(c, c->is, host, host + total, true)) != LAMPS_OK) return rc;
 
+    if (c->d.direct_copy) {
+        for (int32_t i = 0; i < n; ++i) {
+            const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
+            LAMPS_HIP(hipMemcpyAsync(c->k_pool + at, host + (size_t)i * c->d.block_bytes, c->d.half_bytes,
+                                     hipMemcpyHostToDevice, c->is));
+            LAMPS_HIP(hipMemcpyAsync(c->v_pool + at, host + (size_t)i * c->d.block_bytes + c->d.half_bytes,
+                                     c->d.half_bytes, hipMemcpyHostToDevice, c->is));
+        }
+    } else
     for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
         const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
         LAMPS_HIP(hipMemcpyAsync(c->stage_in, host + (size_t)done * c->d.block_bytes,

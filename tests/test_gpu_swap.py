@@ -34,12 +34,14 @@ def _pinned(n):
     return torch.empty(max(n, 1), dtype=torch.uint8).pin_memory()
 
 
+@pytest.mark.parametrize("direct", [-1, 1])      # staged through the gather kernels / plain copies per block
 @pytest.mark.parametrize("dtype,L,Hkv,D,bs,staging_blocks", [
     ("f32", 1, 8, 64, 16, 0), ("bf16", 3, 2, 128, 16, 4), ("bf16", 2, 4, 128, 32, 1)])
-def test_swap_out_image_and_round_trip(dtype, L, Hkv, D, bs, staging_blocks):
+def test_swap_out_image_and_round_trip(dtype, L, Hkv, D, bs, staging_blocks, direct):
     geom = W.Geometry(L, Hkv, Hkv, D, bs, 48, 8, dtype)
     bb = 2 * geom.block_half_bytes
-    rig = Rig(geom, max_batch=2, staging_bytes=staging_blocks * bb)     # small staging: several chunks
+    rig = Rig(geom, max_batch=2, staging_bytes=staging_blocks * bb,     # small staging: several chunks
+              direct_copy_bytes=direct)
     lam = rig.lamps
     assert P.lamps_block_bytes(rig.cfg) == bb
     _fill_random(rig, 11)
@@ -138,10 +140,11 @@ def test_compute_stream_writer_is_ordered_by_compute_wait_blocks():
     rig.close()
 
 
-def test_swap_in_right_behind_swap_out_through_one_buffer():
+@pytest.mark.parametrize("direct", [-1, 1])
+def test_swap_in_right_behind_swap_out_through_one_buffer(direct):
     geom = W.Geometry(4, 8, 8, 128, 16, 128, 8, "bf16")
     bb = 2 * geom.block_half_bytes
-    rig = Rig(geom, max_batch=1)
+    rig = Rig(geom, max_batch=1, direct_copy_bytes=direct)
     lam = rig.lamps
     _fill_random(rig, 31)
     model = _model(rig)
