@@ -169,7 +169,7 @@ int lamps_decode_attn(lamps_ctx *ctx, int32_t layer, int32_t batch, const void *
  * Section 2.2).  Requests with running_mask[r] == 0 append nothing and keep
  * their length.  A position outside the table row or a block id outside the
  * pool writes nothing (device arguments are not validated on the host).
- *   k_new, v_new  device, [batch][H_kv][d_h] dtype
+ *   k_new, v_new  device, [batch][H_kv][d_h] dtype, 16-byte aligned
  *   block_table   device, int32 [batch][max_blocks_per_req]
  *   ctx_lens      device, int32 [batch], read and (with advance) written
  *   running_mask  device, uint8 [batch]
@@ -195,7 +195,8 @@ int lamps_kv_append(lamps_ctx *ctx, int32_t layer, int32_t batch, const void *k_
 /* Writes the keys and values of the new tokens into the paged cache of `layer`
  * (Section 4.2: a discarded context is recomputed into blocks the caller has
  * allocated again; after lamps_compute_wait_blocks if they may still be the
- * source of a swap-out).  k_new, v_new: device, [total_tokens][H_kv][d_h]. */
+ * source of a swap-out).  k_new, v_new: device, [total_tokens][H_kv][d_h],
+ * 16-byte aligned. */
 int lamps_kv_append_tokens(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t total_tokens,
                            const void *k_new, const void *v_new, const int32_t *q_start,
                            const int32_t *block_table, const int32_t *ctx_lens);
@@ -203,7 +204,7 @@ int lamps_kv_append_tokens(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t
  * its own (the Section 2.2 equation per token; the new tokens' keys and values
  * must already be in the cache):
  *   out[n][h][:] = softmax(q[n][h] . K_r[0..p]^T * scale) . V_r[0..p],  p the position of row n.
- * q, out: device, [total_tokens][H][d_h] dtype.  fp32 accumulation, bf16 output
+ * q, out: device, [total_tokens][H][d_h] dtype, 16-byte aligned.  fp32 accumulation, bf16 output
  * rounded to nearest even, results independent of block placement.
  * max_new_tokens: an upper bound, known on the host, of the new tokens of any one
  * request (it sizes the launch; 0 = unknown, total_tokens is used).  bf16 with at

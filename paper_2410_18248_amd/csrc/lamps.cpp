@@ -434,6 +434,8 @@ int lamps_kv_append(lamps_ctx *c, int32_t layer, int32_t batch, const void *k_ne
     if (!c) return LAMPS_ERR_INVALID;
     if (!k_new || !v_new || !block_table || !ctx_lens || !running_mask)
         return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append: null argument");
+    if (((uintptr_t)k_new | (uintptr_t)v_new) & 15)
+        return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append: k_new and v_new must be 16-byte aligned");
     if (layer < 0 || layer >= c->cfg.num_layers)
         return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append: layer out of range");
     if (batch < 0 || batch > c->cfg.max_batch)
@@ -471,6 +473,8 @@ int lamps_kv_append_tokens(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t t
     if (!c) return LAMPS_ERR_INVALID;
     if (!k_new || !v_new || !q_start || !block_table || !ctx_lens)
         return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append_tokens: null argument");
+    if (((uintptr_t)k_new | (uintptr_t)v_new) & 15)
+        return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append_tokens: k_new and v_new must be 16-byte aligned");
     if (layer < 0 || layer >= c->cfg.num_layers)
         return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append_tokens: layer out of range");
     if (n_req < 0 || n_req > c->cfg.max_batch || total_tokens < 0)
@@ -508,6 +512,8 @@ int lamps_prefill_attn(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t total
     if (!c) return LAMPS_ERR_INVALID;
     if (!q || !q_start || !block_table || !ctx_lens || !out)
         return fail(c, LAMPS_ERR_INVALID, "lamps_prefill_attn: null argument");
+    if (((uintptr_t)q | (uintptr_t)out) & 15)
+        return fail(c, LAMPS_ERR_INVALID, "lamps_prefill_attn: q and out must be 16-byte aligned");
     if (layer < 0 || layer >= c->cfg.num_layers)
         return fail(c, LAMPS_ERR_RANGE, "lamps_prefill_attn: layer out of range");
     if (n_req < 0 || n_req > c->cfg.max_batch || total_tokens < 0)
