@@ -163,6 +163,11 @@ int lamps_sched_next_batch(lamps_sched *s, lamps_batch_entry *batch, int32_t cap
  * Errors: INVALID (no batch pending), RANGE. */
 int lamps_sched_commit(lamps_sched *s, double iteration_time, lamps_sched_event *events,
                        int32_t cap, int32_t *n);
+/* Requests that lamps_sched_next_batch discarded because nothing fitted (their
+ * cache is to be dropped; they recompute it when they run again), oldest first;
+ * each is reported once.  Writes at most cap ids and *n.  A caller that executes
+ * the iterations for real drains this after every lamps_sched_next_batch. */
+int lamps_sched_take_discards(lamps_sched *s, int64_t *ids, int32_t cap, int32_t *n);
 /* next_batch / commit on the cost model until every request has finished. */
 int lamps_sched_run(lamps_sched *s);
 

@@ -140,6 +140,7 @@ def _sched_signatures(lib):
                        ("lamps_sched_add", [vp, i64, d, i32, P(LampsSegment), i32, d]),
                        ("lamps_sched_next_batch", [vp, P(LampsBatchEntry), i32, P(i32)]),
                        ("lamps_sched_commit", [vp, d, P(LampsSchedEvent), i32, P(i32)]),
+                       ("lamps_sched_take_discards", [vp, P(i64), i32, P(i32)]),
                        ("lamps_sched_run", [vp]),
                        ("lamps_sched_result", [vp, i64, P(d), P(d), P(i32), i32]),
                        ("lamps_sched_stats", [vp, P(i64), P(i64), P(i64)])):
@@ -192,6 +193,17 @@ class LampsSched:
         self._check(self.lib.lamps_sched_commit(self.h, iteration_time, self._events,
                                                 len(self._events), ctypes.byref(n)), "lamps_sched_commit")
         return [(e.id, e.what, e.handling, e.context) for e in self._events[:n.value]]
+
+    def take_discards(self):
+        out = []
+        buf = (ctypes.c_int64 * 64)()
+        while True:
+            n = ctypes.c_int32()
+            self._check(self.lib.lamps_sched_take_discards(self.h, buf, 64, ctypes.byref(n)),
+                        "lamps_sched_take_discards")
+            out += list(buf[:n.value])
+            if n.value < 64:
+                return out
 
     def run(self):
         self._check(self.lib.lamps_sched_run(self.h), "lamps_sched_run")

@@ -70,6 +70,7 @@ struct lamps_sched {
     double now = 0.0;
     int64_t iteration = 0, total_held = 0, peak = 0, preemptions = 0;
     bool batch_pending = false;
+    std::vector<int64_t> discarded;     // requests discarded for lack of memory, not yet reported
 
     // Section 4.2: the handling strategy of a segment's API call is fixed, from the
     // predicted context at the call and the call's duration, before the segment runs.
@@ -345,6 +346,7 @@ int lamps_sched_next_batch(lamps_sched *s, lamps_batch_entry *out, int32_t cap, 
             victim->started = false;
             victim->has_score = false;
             ++s->preemptions;
+            s->discarded.push_back(victim->id);
             continue;
         }
         bool have = false;
@@ -467,6 +469,16 @@ int lamps_sched_run(lamps_sched *s)
         rc = lamps_sched_commit(s, -1.0, e.data(), (int32_t)e.size(), &ne);
         if (rc != LAMPS_OK) return rc;
     }
+}
+
+int lamps_sched_take_discards(lamps_sched *s, int64_t *ids, int32_t cap, int32_t *n)
+{
+    if (!s || !n || cap < 0 || (cap > 0 && !ids)) return LAMPS_ERR_INVALID;
+    const size_t take = std::min<size_t>(s->discarded.size(), (size_t)cap);
+    for (size_t i = 0; i < take; ++i) ids[i] = s->discarded[i];
+    s->discarded.erase(s->discarded.begin(), s->discarded.begin() + take);
+    *n = (int32_t)take;
+    return LAMPS_OK;
 }
 
 double lamps_sched_now(const lamps_sched *s) { return s ? s->now : -1.0; }
