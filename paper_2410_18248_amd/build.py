@@ -17,7 +17,10 @@ LIB = os.path.join(HERE, "liblamps.so")
 SOURCES = ["decode_attn.hip", "block_copy.hip", "kv_append.hip", "prefill_attn.hip", "lamps.cpp", "sched.cpp"]
 # the scheduler's times are compared bit for bit with a plain evaluation of the same formulas:
 # no fused multiply-adds in its host code
-PER_SOURCE = {"sched.cpp": ["-ffp-contract=off"]}
+PER_SOURCE = {"sched.cpp": ["-ffp-contract=off"],
+              # the prefill kernel rescales its MFMA accumulators on the vector ALUs now and then;
+              # with the accumulators in ordinary vector registers that needs no register moves
+              "prefill_attn.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

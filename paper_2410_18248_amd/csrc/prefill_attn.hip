@@ -54,36 +54,54 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
 
 // ---------------------------------------------------------------- matrix cores
 
-// bf16, up to 64 query heads per kv head.  With many new tokens per request both
+// bf16, up to 32 query heads per kv head.  With many new tokens per request both
 // products of the Section 2.2 equation are real contractions: for one kv head,
 // the (token, head-of-group) pairs are the columns of a query matrix, and every
-// 32 cached positions cost 2 D/32 + D/16 MFMAs (16x16x32) per 16 columns.
+// 32 cached positions cost 2 D/32 + D/16 + 1 MFMAs (16x16x32) per 16 columns.
 //
 // One workgroup = one (request, kv head, tile of new tokens); its four waves each
 // own kCols = 32 columns (kCols / G tokens x G heads) as blocks of 16.  K and V
-// are streamed 32 positions at a time: all 256 threads load the next stage from
-// the paged pools into registers while the current one, in LDS, is consumed;
-// every wave reads each K / V operand from LDS once per stage and uses it for
-// its four column blocks.  Scores come out transposed (lane: four consecutive
-// positions of one column), which is the operand layout the second product
-// wants for the weights, so nothing is shuffled between the two; the positions of
-// a stage's two 16-position halves share one 32-deep MFMA (the contraction index
-// may be permuted as long as both operands agree).
+// are streamed 32 positions at a time through LDS: all 256 threads load stage
+// s + 2 from the paged pools into registers and write stage s + 1 to LDS while
+// stage s is consumed (two LDS buffers, one barrier per stage; one buffer and two
+// barriers where two do not fit).  Every wave reads each K / V operand from LDS
+// once per stage and uses it for both column blocks.  Scores come out transposed
+// (lane: four consecutive positions of one column), which is the operand layout
+// the second product wants for the weights, so nothing is shuffled between the
+// two; the positions of a stage's two 16-position halves share one 32-deep MFMA
+// (the contraction index may be permuted as long as both operands agree).
 //
-// LDS holds the pool tiles as they are for the tiled layout (16-byte runs are
-// operands already).  For the plain layout K rows are padded by 16 bytes so that
-// the 16 rows of a K operand fall in different banks, and V -- whose row-major
-// order would need a transposition at every operand read -- is scattered into
-// the tiled order once, 16 bits at a time, when the stage is written to LDS.
+// The vector ALUs are the scarce unit here (an exponential costs as much issue
+// time as a quarter of an MFMA), so everything that is not the softmax itself is
+// kept off them: block-table entries and tile addresses are wave-uniform and go
+// through the scalar unit, the causal mask is applied only in the stages that
+// straddle a column's own position, the weights' sums come from one more MFMA
+// against a vector of ones (they accumulate, like the outputs, in accumulation
+// registers and need no cross-lane sum at the end), and V is laid out in LDS so
+// that one 16-byte read is one operand.
+//
+// LDS layouts of a stage.  K: the pool tiles as they are for the tiled layout
+// (16-byte runs are operands already); rows padded by 16 bytes for the plain
+// layout, so that the 16 rows of an operand fall in different banks.  V: two
+// planes (dims 32 i + j and 32 i + 16 + j); unit ((i * 4 + qd) * 16 + j) of a
+// plane holds, for its dim, positions 4 qd .. 4 qd + 3 of the first and of the
+// second 16-position half: the 8-deep operand of the second product.  The tiled
+// pool layout supplies this as two 8-byte halves of a 16-byte unit; the plain
+// layout -- row-major, which would need a transposition at every operand read --
+// is scattered 16 bits at a time when the stage is written.  Every 1 KiB group
+// (one i) is shifted by 16 bytes and the planes are 64 bytes apart modulo 256, which
+// spreads those scattered writes over the banks.
 constexpr int kMaxCols = 32;             // columns per wave: two blocks of 16 keep a wave under 256 registers,
                                          // so two workgroups share a CU and cover each other's stalls
 constexpr int kStage = 32;               // cached positions per LDS stage
 constexpr float kSlack = 8.0f;           // log2 of the largest weight before the reference moves
+constexpr int kPlanePad = 256 + 64;      // room for the per-group shifts; plane stride = 64 mod 256
 
 typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
+typedef __attribute__((address_space(4))) const int32_t *table_ptr;   // read-only: scalar loads
 
 template <int D, bool TILED, int kCols>
-__global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
+__global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, const int tiles)
 {
     constexpr int kColBlocks = kCols / 16;
     constexpr int NK = D / 32;                       // score MFMAs per 16 positions
@@ -92,20 +110,26 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
     constexpr int LPT = (2 * U) / kThreads;          // units per thread, pool and stage
     constexpr int ROWB = D * 2 + 16;                 // plain layout: padded row, bytes
     constexpr int SUBB = TILED ? 16 * D * 2 : 16 * ROWB;   // K sub-tile in LDS
-    // V sub-tile in LDS: always the tiled order, each 1 KiB group of 32 dims shifted by 16
-    // bytes so that the scattered 16-bit writes of the plain layout spread over the banks
-    constexpr int SUBV = 16 * D * 2 + (D / 32) * 16;
-    static_assert(LPT >= 1 && (2 * U) % kThreads == 0, "head_dim");
-    __shared__ __align__(16) char lds_k[2 * SUBB];
-    __shared__ __align__(16) char lds_v[2 * SUBV];
+    constexpr int PLANE = U * 16 + kPlanePad;        // one V plane of a stage
+    constexpr int VOFF = 2 * SUBB;                   // V planes follow the two K sub-tiles
+    constexpr int STAGE = VOFF + 2 * PLANE;
+    constexpr int NB = 2 * STAGE <= 40 * 1024 ? 2 : 1;     // stage buffers
+    static_assert(LPT >= 1 && (2 * U) % kThreads == 0 && U % 64 == 0, "head_dim");
+    __shared__ __align__(16) char lds[NB * STAGE];
 
     const DecodeArgs &a = p.d;
-    const int r = blockIdx.z, g = blockIdx.y;
+    // All tiles of one (request, kv head) run on one XCD (workgroups are dealt to the 8 XCDs
+    // round-robin in launch order), so its K/V stream is fetched into one L2 and shared there;
+    // consecutive kv heads go to different XCDs; the longest tiles of a pair start first.
+    const int slot = blockIdx.x >> 3;
+    const int pair = (blockIdx.x & 7) + 8 * (slot / tiles);
+    if (pair >= a.num_kv_heads * a.batch) return;
+    const int tile = tiles - 1 - slot % tiles;
+    const int r = pair / a.num_kv_heads, g = pair - r * a.num_kv_heads;
     const int G = a.num_q_heads / a.num_kv_heads;
     const int TW = kCols / G;                        // new tokens per wave (G <= kCols)
     const int WT = kWaves * TW;                      // ... per workgroup
     const int first = p.q_start[r], n_new = p.q_start[r + 1] - first;
-    const int tile = gridDim.x - 1 - blockIdx.x;     // the longest tiles start first
     if (tile * WT >= n_new) return;
     const int C = a.ctx_lens[r];
     const int base_pos = C - n_new;                  // position of the request's first new token
@@ -139,103 +163,102 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
         wave_maxpos = max(wave_maxpos, __shfl_xor(wave_maxpos, dlt));
         wave_minpos = min(wave_minpos, __shfl_xor(wave_minpos, dlt));
     }
+    wave_maxpos = __builtin_amdgcn_readfirstlane(wave_maxpos);
+    wave_minpos = __builtin_amdgcn_readfirstlane(wave_minpos);
     const int wg_maxpos = base_pos + min(n_new, (tile + 1) * WT) - 1;
     const int n_stages = wg_maxpos / kStage + 1;
 
-    float m[kColBlocks], l[kColBlocks];
+    float m[kColBlocks];
     f32x4 o[kColBlocks][NS];                          // out^T: dims 16 s + 4 qd + e, this lane's column
+    f32x4 l[kColBlocks];                              // the column's sum of weights, four copies
 #pragma unroll
     for (int b = 0; b < kColBlocks; ++b) {
         m[b] = kLowest;
-        l[b] = 0.0f;
+        l[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < NS; ++s) o[b][s] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
 
-    const int32_t *table = a.block_table + (size_t)r * a.max_blocks;
+    const table_ptr table = (table_ptr)(uintptr_t)(a.block_table + (size_t)r * a.max_blocks);
     const size_t tile_bytes = (size_t)a.block_size * D * 2;
     const size_t block_stride = (size_t)a.num_layers * a.num_kv_heads * tile_bytes;
     const size_t head_off = ((size_t)a.layer * a.num_kv_heads + g) * tile_bytes;
     const char *kp = static_cast<const char *>(a.k_pool) + head_off;
     const char *vp = static_cast<const char *>(a.v_pool) + head_off;
 
-    // stage st -> registers: unit x of the stage is sub-tile x / U, 16-byte unit x % U of it
+    // Unit k of this thread: sub-tile sub(k) (wave-uniform) of the stage, 16-byte unit unit(k) of it.
+    auto sub = [&](int k) { return D >= 128 ? (k * kThreads) / U : __builtin_amdgcn_readfirstlane(tid / U); };
+    auto unit_of = [&](int k) { return D >= 128 ? tid + (k * kThreads) % U : tid % U; };
+
+    // stage st -> registers.  Sub-tiles past the workgroup's last position are not loaded: the
+    // registers keep what they held (finite: zero at first, cache contents later), and every
+    // column's weight for those positions is zero.
     uint4 kreg[LPT], vreg[LPT];
+#pragma unroll
+    for (int k = 0; k < LPT; ++k) kreg[k] = vreg[k] = make_uint4(0, 0, 0, 0);
     auto fetch = [&](int st) {
 #pragma unroll
         for (int k = 0; k < LPT; ++k) {
-            const int x = tid + kThreads * k;
-            const int t = st * kStage + 16 * (x / U);
-            kreg[k] = vreg[k] = make_uint4(0, 0, 0, 0);
-            if (st < n_stages && t <= wg_maxpos) {
+            const int t = st * kStage + 16 * sub(k);  // wave-uniform: the table entry and the tile address are scalar
+            if (t <= wg_maxpos) {
                 const size_t off = (size_t)table[t >> a.log2_block_size] * block_stride +
-                                   (size_t)((t & (a.block_size - 1)) >> 4) * (16 * D * 2) + (size_t)(x % U) * 16;
-                kreg[k] = *reinterpret_cast<const uint4 *>(kp + off);
-                vreg[k] = *reinterpret_cast<const uint4 *>(vp + off);
+                                   (size_t)((t & (a.block_size - 1)) >> 4) * (16 * D * 2);
+                kreg[k] = *reinterpret_cast<const uint4 *>(kp + off + (size_t)unit_of(k) * 16);
+                vreg[k] = *reinterpret_cast<const uint4 *>(vp + off + (size_t)unit_of(k) * 16);
             }
         }
     };
-    // registers -> LDS; value slots at or past the context's end are zeroed (they may hold
-    // anything, and a zero weight does not silence a NaN)
-    auto stash = [&](int st) {
+    // registers -> LDS buffer `buf`; value slots at or past the context's end are zeroed (they
+    // may hold anything, and a zero weight does not silence a NaN)
+    auto stash = [&](int st, char *buf) {
+        const bool tail = st * kStage + kStage > C;   // only the context's last stage has such slots
 #pragma unroll
         for (int k = 0; k < LPT; ++k) {
-            const int x = tid + kThreads * k;
-            const int u = x / U, unit = x % U;
+            const int u = sub(k), unit = unit_of(k);
             const int t = st * kStage + 16 * u;
             uint4 v = vreg[k];
             if (TILED) {
-                const size_t where = (size_t)u * SUBB + (size_t)unit * 16;
-                const int valid = C - (t + 4 * ((unit >> 4) & 3));     // of the unit's four positions
-                if (valid < 4) {
+                if (tail) {
+                    const int valid = C - (t + 4 * ((unit >> 4) & 3));     // of the unit's four positions
                     const uint32_t m01 = valid >= 2 ? 0xFFFFFFFFu : (valid == 1 ? 0x0000FFFFu : 0u);
                     const uint32_t m23 = valid >= 4 ? 0xFFFFFFFFu : (valid == 3 ? 0x0000FFFFu : 0u);
                     v.x &= m01; v.z &= m01;
                     v.y &= m23; v.w &= m23;
                 }
-                *reinterpret_cast<uint4 *>(lds_k + where) = kreg[k];
-                *reinterpret_cast<uint4 *>(lds_v + (size_t)u * SUBV + (size_t)unit * 16 + (size_t)(unit >> 6) * 16) = v;
+                *reinterpret_cast<uint4 *>(buf + u * SUBB + unit * 16) = kreg[k];
+                char *dst = buf + VOFF + unit * 16 + (unit >> 6) * 16 + u * 8;
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(v.x, v.y);
+                *reinterpret_cast<uint2 *>(dst + PLANE) = make_uint2(v.z, v.w);
             } else {
                 const int row = unit / (D / 8), c16 = unit % (D / 8);     // position t + row, dims 8 c16 ..
-                *reinterpret_cast<uint4 *>(lds_k + (size_t)u * SUBB + (size_t)row * ROWB + (size_t)c16 * 16) = kreg[k];
-                if (t + row >= C) v = make_uint4(0, 0, 0, 0);
+                *reinterpret_cast<uint4 *>(buf + u * SUBB + row * ROWB + c16 * 16) = kreg[k];
+                if (tail && t + row >= C) v = make_uint4(0, 0, 0, 0);
                 const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-                // element (row, d) of the sub-tile goes where the tiled layout of lamps.h puts it
-                uint16_t *dst = reinterpret_cast<uint16_t *>(lds_v + (size_t)u * SUBV);
+                // dims 8 c16 .. 8 c16 + 7 lie in one 16-dim half of one 32-dim group
+                uint16_t *dst = reinterpret_cast<uint16_t *>(buf + VOFF + ((c16 >> 1) & 1) * PLANE + (c16 >> 2) * (1024 + 16) +
+                                                            (row >> 2) * 256 + (c16 & 1) * 128 + u * 8 + (row & 3) * 2);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int d = 8 * c16 + e;
-                    const int at = ((((d >> 5) * 4 + (row >> 2)) * 16 + (d & 15)) * 2 + ((d & 31) >> 4)) * 4 + (row & 3) +
-                                   (d >> 5) * 8;
-                    dst[at] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-                }
+                for (int e = 0; e < 8; ++e) dst[e * 8] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
             }
         }
     };
 
-    fetch(0);
-    for (int st = 0; st < n_stages; ++st) {
-        __syncthreads();                              // everyone is done with the previous stage
-        stash(st);
-        __syncthreads();
-        fetch(st + 1);                                // in flight while this stage is consumed
-        const int t0 = st * kStage;
-        if (t0 > wave_maxpos) continue;               // wave-uniform: nothing here for this wave's columns
+    // per-lane operand offsets in a stage buffer
+    const int koff = TILED ? qd * 256 + j * 16 : j * ROWB + qd * 16;   // + i * (TILED ? 1024 : 64), + SUBB for the second half
+    const int voff = VOFF + (qd * 16 + j) * 16;                        // + i * (1024 + 16), + PLANE for dims 16 + j
 
+    auto consume = [&](const char *buf, int t0) {
         // Operand-major order: every K / V operand is read from LDS once and used at once
-        // for all column blocks (independent MFMAs back to back, few operand registers
-        // alive), so the accumulators can stay in the accumulation registers for the
-        // whole loop and only the scores and weights pass through the vector ALUs.
+        // for both column blocks (independent MFMAs back to back, few operand registers alive).
         f32x4 sc0[kColBlocks], sc1[kColBlocks];        // positions t0 (+16) + 4 qd + e of the lane's column
 #pragma unroll
         for (int b = 0; b < kColBlocks; ++b) sc0[b] = sc1[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < NK; ++i) {
-            // K rows: position t0 + 16 u + j, dims 32 i + 8 qd ..
-            const size_t where = TILED ? (size_t)((4 * i + qd) * 16 + j) * 16
-                                       : (size_t)j * ROWB + (size_t)(32 * i + 8 * qd) * 2;
-            const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(lds_k + where));
-            const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(lds_k + SUBB + where));
+            const char *at = buf + koff + i * (TILED ? 1024 : 64);
+            const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(at));
+            const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(at + SUBB));
 #pragma unroll
             for (int b = 0; b < kColBlocks; ++b) {
                 sc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qb[b][i], sc0[b], 0, 0, 0);
@@ -244,69 +267,88 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p)
         }
 
         bf16x8 pw[kColBlocks];                         // weights, transposed: the second product's operand
-        const bool all_visible = t0 + kStage - 1 <= wave_minpos;   // wave-uniform
+        const bool masked = t0 + kStage - 1 > wave_minpos;   // wave-uniform: some column does not see the whole stage
 #pragma unroll
         for (int b = 0; b < kColBlocks; ++b) {
             float sc[8];                              // raw scores; scale_log2e > 0 is applied in the exponent
-            float mx = -INFINITY;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float x = e < 4 ? sc0[b][e] : sc1[b][e - 4];
-                const int t = t0 + 16 * (e >> 2) + 4 * qd + (e & 3);
-                sc[e] = (all_visible || t <= pos[b]) ? x : -INFINITY;   // a token sees the positions up to its own
-                mx = fmaxf(mx, sc[e]);
+            for (int e = 0; e < 8; ++e) sc[e] = e < 4 ? sc0[b][e] : sc1[b][e - 4];
+            if (masked) {                             // a token sees the positions up to its own
+                const int lim = pos[b] - t0 - 4 * qd;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (16 * (e >> 2) + (e & 3) > lim) sc[e] = -INFINITY;
             }
+            float mx = sc[0];                         // median with +inf = maximum, without fmaxf's NaN quieting moves
+#pragma unroll
+            for (int e = 1; e < 8; ++e) mx = __builtin_amdgcn_fmed3f(mx, sc[e], INFINITY);
             mx *= a.scale_log2e;
             // The reference point of the exponentials follows the running maximum lazily:
             // it moves only when a score exceeds it by more than kSlack, so weights stay
             // below 2^kSlack, the four lanes that share a column compare notes only then,
             // and the accumulators (which live in accumulation registers the vector ALUs
             // cannot touch without moving them) are rescaled a handful of times per column.
-            float f = 1.0f;
             if (__any(mx - m[b] > kSlack)) {          // wave-uniform, rare after the first stages
                 mx = fmaxf(mx, __shfl_xor(mx, 16));
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
                 const float mn = mx - m[b] > kSlack ? mx : m[b];
-                f = fast_exp2(m[b] - mn);
+                const float f = fast_exp2(m[b] - mn);
                 m[b] = mn;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) l[b][e] *= f;
 #pragma unroll
                 for (int s = 0; s < NS; ++s)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o[b][s][e] *= f;
             }
             const float mn = m[b];
-            float ps = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float w = fast_exp2(fmaf(sc[e], a.scale_log2e, -mn));
-                ps += w;
-                pw[b][e] = (__bf16)w;
-            }
-            l[b] = l[b] * f + ps;
+            for (int e = 0; e < 8; ++e) pw[b][e] = (__bf16)fast_exp2(fmaf(sc[e], a.scale_log2e, -mn));
         }
+#pragma unroll
+        for (int b = 0; b < kColBlocks; ++b) l[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pw[b], l[b], 0, 0, 0);
 
 #pragma unroll
         for (int i = 0; i < NS / 2; ++i) {
-            // V^T rows: dims 32 i + j (x, y) and 32 i + 16 + j (z, w), positions 4 qd .. of each half
-            const size_t where = (size_t)((i * 4 + qd) * 16 + j) * 16 + (size_t)i * 16;
-            const uint4 v0 = *reinterpret_cast<const uint4 *>(lds_v + where);
-            const uint4 v1 = *reinterpret_cast<const uint4 *>(lds_v + SUBV + where);
-            const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
-            const bf16x8 vb = __builtin_bit_cast(bf16x8, make_uint4(v0.z, v0.w, v1.z, v1.w));
+            // V^T rows: dims 32 i + j and 32 i + 16 + j, positions 4 qd .. of both halves
+            const char *at = buf + voff + i * (1024 + 16);
+            const bf16x8 va = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(at));
+            const bf16x8 vb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(at + PLANE));
 #pragma unroll
             for (int b = 0; b < kColBlocks; ++b) {
                 o[b][2 * i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pw[b], o[b][2 * i], 0, 0, 0);
                 o[b][2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, pw[b], o[b][2 * i + 1], 0, 0, 0);
             }
         }
+    };
+
+    if constexpr (NB == 2) {
+        fetch(0);
+        stash(0, lds);
+        fetch(1);
+        __syncthreads();
+        for (int st = 0; st < n_stages; ++st) {
+            char *cur = lds + (st & 1) * STAGE;
+            if (st + 1 < n_stages) stash(st + 1, lds + ((st + 1) & 1) * STAGE);   // nobody reads that buffer now
+            fetch(st + 2);                            // in flight while this stage is consumed
+            if (st * kStage <= wave_maxpos) consume(cur, st * kStage);   // wave-uniform
+            __syncthreads();                          // stage st + 1 is written, stage st is read
+        }
+    } else {
+        fetch(0);
+        for (int st = 0; st < n_stages; ++st) {
+            __syncthreads();                          // everyone is done with the previous stage
+            stash(st, lds);
+            __syncthreads();
+            fetch(st + 1);
+            if (st * kStage <= wave_maxpos) consume(lds, st * kStage);
+        }
     }
 
 #pragma unroll
     for (int b = 0; b < kColBlocks; ++b) {
-        float lt = l[b];                              // kept per position group: add the four
-        lt += __shfl_xor(lt, 16);
-        lt += __shfl_xor(lt, 32);
         if (pos[b] < 0) continue;
+        const float lt = l[b][0];
         const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
         uint16_t *dst = static_cast<uint16_t *>(a.out) + orow[b];
 #pragma unroll
@@ -325,10 +367,10 @@ hipError_t launch_mfma_prefill(const PrefillArgs &p, hipStream_t s)
     constexpr int kCols = kMaxCols;
     const int G = p.d.num_q_heads / p.d.num_kv_heads;
     const int WT = kWaves * (kCols / G);
-    const int tiles = (p.max_new_tokens + WT - 1) / WT;
-    if (tiles < 1 || p.d.num_kv_heads > 65535 || p.d.batch > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((prefill_mfma<D, TILED, kCols>), dim3((unsigned)tiles, (unsigned)p.d.num_kv_heads, (unsigned)p.d.batch),
-                       dim3(kThreads), 0, s, p);
+    const long long tiles = (p.max_new_tokens + WT - 1) / WT;
+    const long long pairs8 = ((long long)p.d.num_kv_heads * p.d.batch + 7) / 8 * 8;
+    if (tiles < 1 || tiles * pairs8 > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((prefill_mfma<D, TILED, kCols>), dim3((unsigned)(tiles * pairs8)), dim3(kThreads), 0, s, p, (int)tiles);
     return hipGetLastError();
 }
 
