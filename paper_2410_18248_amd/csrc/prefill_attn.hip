@@ -71,33 +71,34 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
 // two; the positions of a stage's two 16-position halves share one 32-deep MFMA
 // (the contraction index may be permuted as long as both operands agree).
 //
-// The vector ALUs are the scarce unit here (an exponential costs as much issue
-// time as a quarter of an MFMA), so everything that is not the softmax itself is
-// kept off them: block-table entries and tile addresses are wave-uniform and go
-// through the scalar unit, the causal mask is applied only in the stages that
-// straddle a column's own position, the weights' sums come from one more MFMA
-// against a vector of ones (they accumulate, like the outputs, in accumulation
-// registers and need no cross-lane sum at the end), and V is laid out in LDS so
-// that one 16-byte read is one operand.
+// The loop is software-pipelined around its one barrier: a stage's V operands are
+// read from LDS before its scores are computed and used after the barrier, the
+// next stage's K operands are read right after the barrier and used at the top of
+// the next iteration, so LDS latency is behind MFMA or softmax work both times.
 //
-// LDS layouts of a stage.  K: the pool tiles as they are for the tiled layout
-// (16-byte runs are operands already); rows padded by 16 bytes for the plain
-// layout, so that the 16 rows of an operand fall in different banks.  V: two
-// planes (dims 32 i + j and 32 i + 16 + j); unit ((i * 4 + qd) * 16 + j) of a
-// plane holds, for its dim, positions 4 qd .. 4 qd + 3 of the first and of the
-// second 16-position half: the 8-deep operand of the second product.  The tiled
-// pool layout supplies this as two 8-byte halves of a 16-byte unit; the plain
-// layout -- row-major, which would need a transposition at every operand read --
-// is scattered 16 bits at a time when the stage is written.  Every 1 KiB group
-// (one i) is shifted by 16 bytes and the planes are 64 bytes apart modulo 256, which
-// spreads those scattered writes over the banks.
+// The vector ALUs are the scarce unit (an exponential costs as much issue time as
+// a quarter of an MFMA), so everything that is not the softmax itself is kept off
+// them: block-table entries are looked up one stage ahead through the scalar
+// unit, the causal mask is applied only in the stages that straddle a column's own
+// position, the weights' sums come from one more MFMA against a vector of ones
+// (they accumulate, like the outputs, in registers and need no cross-lane sum at
+// the end), and V reaches the second product without any shuffling in registers.
+//
+// LDS layouts of a stage.  Tiled pool layout: K tiles as they are (16-byte runs
+// are operands already); V in two planes (dims 32 i + j and 32 i + 16 + j), where
+// unit ((i * 4 + qd) * 16 + j) of a plane holds, for its dim, positions
+// 4 qd .. 4 qd + 3 of the first and of the second 16-position half -- the 8-deep
+// operand -- written as the two 8-byte halves of the pool's 16-byte units.  Plain
+// layout: K and V row-major, K rows padded by 16 bytes (the 16 rows of an operand
+// fall in different banks), V rows by 32; V^T operands come out of the transposing
+// LDS read of gfx950 (ds_read_b64_tr_b16: the 16 lanes of a group read four rows
+// of 16 dims, lane j receives dim j of the four rows).
 constexpr int kMaxCols = 32;             // columns per wave: two blocks of 16 keep a wave under 256 registers,
                                          // so two workgroups share a CU and cover each other's stalls
 constexpr int kStage = 32;               // cached positions per LDS stage
 constexpr float kSlack = 8.0f;           // log2 of the largest weight before the reference moves
-constexpr int kPlanePad = 256 + 64;      // room for the per-group shifts; plane stride = 64 mod 256
 
-typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((address_space(4))) const int32_t *table_ptr;   // read-only: scalar loads
 
 template <int D, bool TILED, int kCols>
@@ -108,13 +109,14 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
     constexpr int NS = D / 16;                       // 16-dim slabs of the output
     constexpr int U = D * 2;                         // 16-byte units of one 16-position sub-tile
     constexpr int LPT = (2 * U) / kThreads;          // units per thread, pool and stage
-    constexpr int ROWB = D * 2 + 16;                 // plain layout: padded row, bytes
+    constexpr int ROWB = D * 2 + 16;                 // plain layout: padded K row, bytes
+    constexpr int ROWV = D * 2 + 32;                 // plain layout: padded V row
     constexpr int SUBB = TILED ? 16 * D * 2 : 16 * ROWB;   // K sub-tile in LDS
-    constexpr int PLANE = U * 16 + kPlanePad;        // one V plane of a stage
-    constexpr int VOFF = 2 * SUBB;                   // V planes follow the two K sub-tiles
-    constexpr int STAGE = VOFF + 2 * PLANE;
+    constexpr int PLANE = U * 16;                    // tiled layout: one V plane of a stage
+    constexpr int VOFF = 2 * SUBB;                   // V follows the two K sub-tiles
+    constexpr int STAGE = VOFF + (TILED ? 2 * PLANE : 32 * ROWV);
     constexpr int NB = 2 * STAGE <= 40 * 1024 ? 2 : 1;     // stage buffers
-    static_assert(LPT >= 1 && (2 * U) % kThreads == 0 && U % 64 == 0, "head_dim");
+    static_assert(LPT >= 1 && (2 * U) % kThreads == 0, "head_dim");
     __shared__ __align__(16) char lds[NB * STAGE];
 
     const DecodeArgs &a = p.d;
@@ -187,25 +189,40 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
     const char *kp = static_cast<const char *>(a.k_pool) + head_off;
     const char *vp = static_cast<const char *>(a.v_pool) + head_off;
 
-    // Unit k of this thread: sub-tile sub(k) (wave-uniform) of the stage, 16-byte unit unit(k) of it.
-    auto sub = [&](int k) { return D >= 128 ? (k * kThreads) / U : __builtin_amdgcn_readfirstlane(tid / U); };
-    auto unit_of = [&](int k) { return D >= 128 ? tid + (k * kThreads) % U : tid % U; };
+    // Unit k of this thread: 16-byte unit unit_of(k) of the stage's sub-tile sub_of(k).  Sixteen
+    // consecutive lanes take sixteen consecutive units of one sub-tile, the next sixteen the same
+    // units of the other sub-tile: global loads stay coalesced (256-byte runs) and the two halves
+    // of a V operand are written to LDS by neighbouring half-groups, into one contiguous run.
+    auto sub_of = [&](int k) { return ((tid + kThreads * k) >> 4) & 1; };
+    auto unit_of = [&](int k) { const int x = tid + kThreads * k; return (x & 15) | ((x >> 5) << 4); };
 
-    // stage st -> registers.  Sub-tiles past the workgroup's last position are not loaded: the
+    // Block-table entries of a stage's two sub-tiles: wave-uniform, through the scalar unit, and
+    // looked up one iteration before the loads that use them so that nobody waits for them.
+    int e0, e1;
+    auto lookup = [&](int st) {
+        e0 = table[min(st * kStage, wg_maxpos) >> a.log2_block_size];
+        e1 = table[min(st * kStage + 16, wg_maxpos) >> a.log2_block_size];
+    };
+    // Byte offset (from kp / vp) of the sub-tile that starts at position t in block `entry`;
+    // -1 past the workgroup's last position.
+    auto where = [&](int t, int entry) {
+        return t <= wg_maxpos ? (long long)((size_t)entry * block_stride + (size_t)((t & (a.block_size - 1)) >> 4) * (16 * D * 2))
+                              : -1LL;
+    };
+    // A stage -> registers.  Sub-tiles past the workgroup's last position are not loaded: the
     // registers keep what they held (finite: zero at first, cache contents later), and every
     // column's weight for those positions is zero.
     uint4 kreg[LPT], vreg[LPT];
 #pragma unroll
     for (int k = 0; k < LPT; ++k) kreg[k] = vreg[k] = make_uint4(0, 0, 0, 0);
     auto fetch = [&](int st) {
+        const long long at0 = where(st * kStage, e0), at1 = where(st * kStage + 16, e1);
 #pragma unroll
         for (int k = 0; k < LPT; ++k) {
-            const int t = st * kStage + 16 * sub(k);  // wave-uniform: the table entry and the tile address are scalar
-            if (t <= wg_maxpos) {
-                const size_t off = (size_t)table[t >> a.log2_block_size] * block_stride +
-                                   (size_t)((t & (a.block_size - 1)) >> 4) * (16 * D * 2);
-                kreg[k] = *reinterpret_cast<const uint4 *>(kp + off + (size_t)unit_of(k) * 16);
-                vreg[k] = *reinterpret_cast<const uint4 *>(vp + off + (size_t)unit_of(k) * 16);
+            const long long off = sub_of(k) ? at1 : at0;
+            if (off >= 0) {
+                kreg[k] = *reinterpret_cast<const uint4 *>(kp + off + unit_of(k) * 16);
+                vreg[k] = *reinterpret_cast<const uint4 *>(vp + off + unit_of(k) * 16);
             }
         }
     };
@@ -215,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
         const bool tail = st * kStage + kStage > C;   // only the context's last stage has such slots
 #pragma unroll
         for (int k = 0; k < LPT; ++k) {
-            const int u = sub(k), unit = unit_of(k);
+            const int u = sub_of(k), unit = unit_of(k);
             const int t = st * kStage + 16 * u;
             uint4 v = vreg[k];
             if (TILED) {
@@ -227,46 +244,62 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
                     v.y &= m23; v.w &= m23;
                 }
                 *reinterpret_cast<uint4 *>(buf + u * SUBB + unit * 16) = kreg[k];
-                char *dst = buf + VOFF + unit * 16 + (unit >> 6) * 16 + u * 8;
+                char *dst = buf + VOFF + unit * 16 + u * 8;
                 *reinterpret_cast<uint2 *>(dst) = make_uint2(v.x, v.y);
                 *reinterpret_cast<uint2 *>(dst + PLANE) = make_uint2(v.z, v.w);
             } else {
                 const int row = unit / (D / 8), c16 = unit % (D / 8);     // position t + row, dims 8 c16 ..
-                *reinterpret_cast<uint4 *>(buf + u * SUBB + row * ROWB + c16 * 16) = kreg[k];
                 if (tail && t + row >= C) v = make_uint4(0, 0, 0, 0);
-                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-                // dims 8 c16 .. 8 c16 + 7 lie in one 16-dim half of one 32-dim group
-                uint16_t *dst = reinterpret_cast<uint16_t *>(buf + VOFF + ((c16 >> 1) & 1) * PLANE + (c16 >> 2) * (1024 + 16) +
-                                                            (row >> 2) * 256 + (c16 & 1) * 128 + u * 8 + (row & 3) * 2);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) dst[e * 8] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                *reinterpret_cast<uint4 *>(buf + u * SUBB + row * ROWB + c16 * 16) = kreg[k];
+                *reinterpret_cast<uint4 *>(buf + VOFF + (16 * u + row) * ROWV + c16 * 16) = v;
             }
         }
     };
 
     // per-lane operand offsets in a stage buffer
     const int koff = TILED ? qd * 256 + j * 16 : j * ROWB + qd * 16;   // + i * (TILED ? 1024 : 64), + SUBB for the second half
-    const int voff = VOFF + (qd * 16 + j) * 16;                        // + i * (1024 + 16), + PLANE for dims 16 + j
+    const int voff = VOFF + (TILED ? (qd * 16 + j) * 16                // + i * 1024, + PLANE for dims 16 + j
+                                   : (4 * qd + (j >> 2)) * ROWV + (j & 3) * 8);   // + s * 32, + 16 * ROWV for the second half
 
-    auto consume = [&](const char *buf, int t0) {
-        // Operand-major order: every K / V operand is read from LDS once and used at once
-        // for both column blocks (independent MFMAs back to back, few operand registers alive).
-        f32x4 sc0[kColBlocks], sc1[kColBlocks];        // positions t0 (+16) + 4 qd + e of the lane's column
+    bf16x8 kop[NK][2];                                // K rows: position (16 h +) j, dims 32 i + 8 qd ..
+    bf16x8 vop[NS];                                   // V^T rows: dim 16 s + j, positions 4 qd .. of both halves
+    auto read_k = [&](const char *buf) {
+#pragma unroll
+        for (int i = 0; i < NK; ++i)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                kop[i][h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + koff + i * (TILED ? 1024 : 64) + h * SUBB));
+    };
+    auto read_v = [&](const char *buf) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (TILED) {
+                vop[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + voff + (s >> 1) * 1024 + (s & 1) * PLANE));
+            } else {
+                typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
+                const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + voff + s * 32));
+                const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + voff + s * 32 + 16 * ROWV));
+                vop[s] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+        }
+    };
+
+    f32x4 sc0[kColBlocks], sc1[kColBlocks];            // scores: positions t0 (+16) + 4 qd + e of the lane's column
+    bf16x8 pw[kColBlocks];                             // weights, transposed: the second product's operand
+    // Operand-major order: every K / V operand is used at once for both column blocks
+    // (independent MFMAs back to back).
+    auto scores = [&]() {
 #pragma unroll
         for (int b = 0; b < kColBlocks; ++b) sc0[b] = sc1[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < NK; ++i) {
-            const char *at = buf + koff + i * (TILED ? 1024 : 64);
-            const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(at));
-            const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(at + SUBB));
+        for (int i = 0; i < NK; ++i)
 #pragma unroll
             for (int b = 0; b < kColBlocks; ++b) {
-                sc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qb[b][i], sc0[b], 0, 0, 0);
-                sc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qb[b][i], sc1[b], 0, 0, 0);
+                sc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[i][0], qb[b][i], sc0[b], 0, 0, 0);
+                sc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[i][1], qb[b][i], sc1[b], 0, 0, 0);
             }
-        }
-
-        bf16x8 pw[kColBlocks];                         // weights, transposed: the second product's operand
+    };
+    auto softmax = [&](int t0) {
         const bool masked = t0 + kStage - 1 > wave_minpos;   // wave-uniform: some column does not see the whole stage
 #pragma unroll
         for (int b = 0; b < kColBlocks; ++b) {
@@ -286,8 +319,7 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
             // The reference point of the exponentials follows the running maximum lazily:
             // it moves only when a score exceeds it by more than kSlack, so weights stay
             // below 2^kSlack, the four lanes that share a column compare notes only then,
-            // and the accumulators (which live in accumulation registers the vector ALUs
-            // cannot touch without moving them) are rescaled a handful of times per column.
+            // and the accumulators are rescaled a handful of times per column.
             if (__any(mx - m[b] > kSlack)) {          // wave-uniform, rare after the first stages
                 mx = fmaxf(mx, __shfl_xor(mx, 16));
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -305,43 +337,54 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
 #pragma unroll
             for (int e = 0; e < 8; ++e) pw[b][e] = (__bf16)fast_exp2(fmaf(sc[e], a.scale_log2e, -mn));
         }
+    };
+    auto accumulate = [&]() {
 #pragma unroll
         for (int b = 0; b < kColBlocks; ++b) l[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pw[b], l[b], 0, 0, 0);
-
 #pragma unroll
-        for (int i = 0; i < NS / 2; ++i) {
-            // V^T rows: dims 32 i + j and 32 i + 16 + j, positions 4 qd .. of both halves
-            const char *at = buf + voff + i * (1024 + 16);
-            const bf16x8 va = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(at));
-            const bf16x8 vb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(at + PLANE));
+        for (int s = 0; s < NS; ++s)
 #pragma unroll
-            for (int b = 0; b < kColBlocks; ++b) {
-                o[b][2 * i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pw[b], o[b][2 * i], 0, 0, 0);
-                o[b][2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, pw[b], o[b][2 * i + 1], 0, 0, 0);
-            }
-        }
+            for (int b = 0; b < kColBlocks; ++b) o[b][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[s], pw[b], o[b][s], 0, 0, 0);
     };
 
+    lookup(0);
+    fetch(0);
     if constexpr (NB == 2) {
-        fetch(0);
         stash(0, lds);
+        lookup(1);
         fetch(1);
+        lookup(2);
         __syncthreads();
+        read_k(lds);
         for (int st = 0; st < n_stages; ++st) {
-            char *cur = lds + (st & 1) * STAGE;
-            if (st + 1 < n_stages) stash(st + 1, lds + ((st + 1) & 1) * STAGE);   // nobody reads that buffer now
-            fetch(st + 2);                            // in flight while this stage is consumed
-            if (st * kStage <= wave_maxpos) consume(cur, st * kStage);   // wave-uniform
-            __syncthreads();                          // stage st + 1 is written, stage st is read
+            char *cur = lds + (st & 1) * STAGE, *nxt = lds + ((st + 1) & 1) * STAGE;
+            const bool live = st * kStage <= wave_maxpos;   // wave-uniform: this wave's columns see the stage
+            if (live) {
+                read_v(cur);                          // needed after the barrier
+                scores();
+            }
+            if (st + 1 < n_stages) stash(st + 1, nxt);    // nobody reads that buffer now
+            fetch(st + 2);                            // in flight for a whole iteration
+            lookup(st + 3);
+            if (live) softmax(st * kStage);
+            __syncthreads();                          // stage st + 1 is in LDS, stage st's operands are in registers
+            if (st + 1 < n_stages) read_k(nxt);       // needed at the top of the next iteration
+            if (live) accumulate();
         }
     } else {
-        fetch(0);
         for (int st = 0; st < n_stages; ++st) {
             __syncthreads();                          // everyone is done with the previous stage
             stash(st, lds);
             __syncthreads();
+            lookup(st + 1);
             fetch(st + 1);
-            if (st * kStage <= wave_maxpos) consume(lds, st * kStage);
+            if (st * kStage <= wave_maxpos) {
+                read_k(lds);
+                read_v(lds);
+                scores();
+                softmax(st * kStage);
+                accumulate();
+            }
         }
     }
 
