@@ -100,6 +100,95 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_tokens(const AppendA
                             static_cast<const T *>(a.v_new) + row);
 }
 
+// The same for the tiled layout (bf16), where the 16-byte unit of a value tile is four
+// consecutive positions of two dims: one token alone can only write it 16 bits at a time.
+// One workgroup per (request, 16-position sub-tile that holds new tokens, kv head): keys are
+// copied 16 bytes at a time as above; for values a thread takes four consecutive positions
+// and 2 x 2 dims, transposes them in registers and stores two whole units; only the
+// positions of a quad that is not entirely new -- at most one at each end of a request's
+// range -- fall back to 16-bit stores.
+// Workgroup w belongs to the last request r with (q_start[r] >> 4) + 2 r <= w: request r
+// touches at most (count >> 4) + 2 sub-tiles, and the keys of consecutive requests are at
+// least that far apart.
+__global__ __launch_bounds__(kAppendThreads) void kv_append_tokens_tiled(const AppendArgs a)
+{
+    typedef uint16_t T;
+    const int w = blockIdx.x;
+    int lo = 0, hi = a.batch;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((a.q_start[mid] >> 4) + 2 * mid <= w) lo = mid; else hi = mid;
+    }
+    const int r = lo;
+    const int first = a.q_start[r], count = a.q_start[r + 1] - first;
+    const int p0 = a.ctx_lens[r] - count;             // position of the request's first new token
+    if (count <= 0 || p0 < 0) return;
+    const int sub = (p0 >> 4) + (w - ((first >> 4) + 2 * r));     // sub-tile of the request's context
+    const int t_lo = max(p0, sub * 16), t_hi = min(p0 + count, sub * 16 + 16);
+    if (t_lo >= t_hi) return;
+    const int D = a.head_dim, Hkv = a.num_kv_heads, bs = a.block_size;
+    const int lb = (sub * 16) >> a.log2_block_size;
+    if (lb >= a.max_blocks) return;
+    const int block = a.block_table[(size_t)r * a.max_blocks + lb];
+    if (block < 0 || block >= a.num_blocks) return;
+    const size_t tile = (size_t)bs * D;
+    const size_t at = (((size_t)block * a.num_layers + a.layer) * Hkv) * tile + (size_t)(((sub * 16) & (bs - 1)) >> 4) * 16 * D;
+    T *kt = static_cast<T *>(a.k_pool) + at;
+    T *vt = static_cast<T *>(a.v_pool) + at;
+    const T *kn = static_cast<const T *>(a.k_new), *vn = static_cast<const T *>(a.v_new);
+    const int row = Hkv * D;                          // elements of one token's keys (or values)
+
+    const int g = blockIdx.y;                         // kv head
+    kt += g * tile; vt += g * tile;
+    kn += g * D; vn += g * D;
+
+    const int c8 = D / 8;                             // keys: (position, 8 dims) -> one 16-byte unit
+    for (int i = threadIdx.x; i < (t_hi - t_lo) * c8; i += kAppendThreads) {
+        const int c = i % c8, t = t_lo + i / c8;
+        *reinterpret_cast<uint4 *>(kt + (size_t)(c * 16 + (t & 15)) * 8) =
+            *reinterpret_cast<const uint4 *>(kn + (size_t)(first + (t - p0)) * row + c * 8);
+    }
+
+    // values: (quad of positions, 32-dim group, dims 2 j, 2 j + 1 of its first 16 and of its last 16)
+    for (int i = threadIdx.x; i < 4 * (D / 32) * 8; i += kAppendThreads) {
+        const int j = i & 7, i32 = (i >> 3) % (D / 32), q = i / (8 * (D / 32));
+        const int t0 = sub * 16 + 4 * q;              // the quad's first position
+        if (t0 + 4 <= t_lo || t0 >= t_hi) continue;
+        const int d0 = 32 * i32 + 2 * j;
+        T *dst = vt + (size_t)((i32 * 4 + q) * 16 + 2 * j) * 8;   // unit of dim d0; dim d0 + 1's follows
+        if (t0 >= t_lo && t0 + 4 <= t_hi) {
+            uint32_t lo2[4], hi2[4];                  // [position]: dims d0, d0 + 1 and d0 + 16, d0 + 17
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const T *src = vn + (size_t)(first + (t0 + k - p0)) * row + d0;
+                lo2[k] = *reinterpret_cast<const uint32_t *>(src);
+                hi2[k] = *reinterpret_cast<const uint32_t *>(src + 16);
+            }
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int sh = 16 * e;
+                uint4 u;
+                u.x = ((lo2[0] >> sh) & 0xFFFFu) | ((lo2[1] >> sh) << 16);
+                u.y = ((lo2[2] >> sh) & 0xFFFFu) | ((lo2[3] >> sh) << 16);
+                u.z = ((hi2[0] >> sh) & 0xFFFFu) | ((hi2[1] >> sh) << 16);
+                u.w = ((hi2[2] >> sh) & 0xFFFFu) | ((hi2[3] >> sh) << 16);
+                *reinterpret_cast<uint4 *>(dst + e * 8) = u;
+            }
+        } else {
+            for (int k = 0; k < 4; ++k) {
+                const int t = t0 + k;
+                if (t < t_lo || t >= t_hi) continue;
+                const T *src = vn + (size_t)(first + (t - p0)) * row + d0;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    dst[e * 8 + k] = src[e];
+                    dst[e * 8 + 4 + k] = src[16 + e];
+                }
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_kv_append(const AppendArgs &a, int tiled, hipStream_t stream)
@@ -123,7 +212,8 @@ hipError_t launch_kv_append_tokens(const AppendArgs &a, int total_tokens, int ti
     dim3 grid((unsigned)total_tokens), block(kAppendThreads);
     if (a.bf16) {
         if (tiled)
-            hipLaunchKernelGGL((kv_append_tokens<uint16_t, true>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL(kv_append_tokens_tiled, dim3((unsigned)((total_tokens >> 4) + 2 * a.batch), (unsigned)a.num_kv_heads),
+                               block, 0, stream, a);
         else
             hipLaunchKernelGGL((kv_append_tokens<uint16_t, false>), grid, block, 0, stream, a);
     } else {
