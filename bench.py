@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--part-tokens", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-swap", action="store_true", help="decode only (for profiling)")
+    ap.add_argument("--swap-layered", default="", metavar="L,Hkv,D,blocks",
+                    help="measure the layer-major swap-in of one request instead of the decode step")
     ap.add_argument("--staging-mib", type=int, default=0, help="lamps_config.staging_bytes in MiB (0 = default)")
     ap.add_argument("--direct-copy-bytes", type=int, default=0,
                     help="lamps_config.direct_copy_bytes (0 = staged through the gather kernels, the default)")
@@ -292,6 +294,69 @@ def cpu_baseline(job):
 MFMA_BF16_PEAK_TFLOPS = 2500.0    # MI355X published dense bf16 matrix peak
 
 
+def swap_layered_bench(a):
+    """Layer-major swap against the block-major one for one returning request: `blocks` blocks of a
+    cache with L layers of Hkv kv heads of D (bf16, 16-token blocks).  Reports the rates of both and
+    how long the compute stream waits before the attention of layer 0, of the middle layer and of
+    the last layer may start (lamps_compute_wait_layer against lamps_compute_wait)."""
+    import torch
+
+    import paper_2410_18248_amd as P
+    L, Hkv, D, blocks = [int(x) for x in a.swap_layered.split(",")]
+    nb = blocks + 8
+    dev = torch.device("cuda:0")
+    cfg = P.LampsConfig(L, Hkv, Hkv, D, 16, nb, blocks, 1, P.LAMPS_BF16, 0.0, 0, a.staging_mib << 20, 0)
+    elems = P.lamps_pool_bytes(cfg) // 2
+    k_pool = torch.empty(elems, dtype=torch.bfloat16, device=dev).normal_()
+    v_pool = torch.empty(elems, dtype=torch.bfloat16, device=dev).normal_()
+    ws = torch.empty(P.lamps_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+    cs, so, si = (torch.cuda.Stream(dev) for _ in range(3))
+    torch.cuda.synchronize()
+    lam = P.Lamps(cfg, k_pool, v_pool, ws, cs.cuda_stream, so.cuda_stream, si.cuda_stream)
+    ids = lam.alloc_blocks(nb)[:blocks]
+    nbytes = blocks * P.lamps_block_bytes(cfg)
+    host = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+
+    def ready_times(layered, layers):
+        """ms from the swap-in call until the compute stream is released for each listed layer."""
+        ticket = None
+        lam.ticket_wait(lam.swap_out(ids, host, layered=layered))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ticket = lam.swap_in(host, ids, layered=layered)
+        evs = []
+        for layer in layers:
+            if layered:
+                lam.compute_wait_layer(ticket, layer)
+            else:
+                lam.compute_wait(ticket)
+            e = torch.cuda.Event()
+            e.record(cs)
+            evs.append(e)
+        done = [None] * len(evs)
+        while any(d is None for d in done):         # polled: a host wait on such an event returns only
+            for i, e in enumerate(evs):             # when the whole copy stream has drained
+                if done[i] is None and e.query():
+                    done[i] = (time.perf_counter() - t0) * 1e3
+        lam.ticket_wait(ticket)
+        return done, (time.perf_counter() - t0) * 1e3
+
+    layers = sorted(set([0, L // 2, L - 1]))
+    best = {}
+    for layered in (False, True):
+        runs = [ready_times(layered, layers) for _ in range(6)]
+        runs.sort(key=lambda r: r[1])               # the runtime now and then blocks a copy call for ms: take the median
+        done, total = runs[len(runs) // 2]
+        best[layered] = {"ready_ms": dict(zip(["layer_%d" % x for x in layers], done)), "all_ms": total,
+                         "GBs": nbytes / total / 1e6}
+    line = {"metric": "swap-in of one request: ms until a layer's attention may start", "unit": "ms",
+            "value": best[True]["ready_ms"]["layer_0"], "higher_is_better": False, "n_gpus": 1, "data": "synthetic",
+            "config": {"workload": "swap-in-%d-blocks-L%d-Hkv%d-D%d" % (blocks, L, Hkv, D), "bytes": nbytes},
+            "block_major": best[False], "layer_major": best[True]}
+    print(json.dumps(line))
+    lam.destroy()
+
+
 def prefill_bench(a):
     """lamps_kv_append_tokens + lamps_prefill_attn for `requests` requests of `tokens` new tokens
     each on top of `cached` old ones (0 = a discarded context recomputed from scratch), one layer,
@@ -395,6 +460,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if a.swap_layered:
+        swap_layered_bench(a)
+        return
     if a.prefill:
         prefill_bench(a)
         return

@@ -247,6 +247,27 @@ int lamps_swap_out(lamps_ctx *ctx, const int32_t *block_ids, int32_t n, void *ho
 int lamps_swap_in(lamps_ctx *ctx, const void *host_buf, const int32_t *block_ids, int32_t n,
                   uint64_t *ticket);
 
+/* Layer-major variants of the two calls above (Section 4.2: the swap's time, the
+ * term of equation (3), is what a returning request waits for; moved one layer
+ * after the other, the first layers' attention can start while the rest is still
+ * on its way).  The host image is laid out
+ *   [layer][i][keys of block_ids[i], layer | values of block_ids[i], layer]
+ * (same size as the block-major image of lamps_swap_out, NOT interchangeable
+ * with it: an image written by lamps_swap_out_layered is read back only by
+ * lamps_swap_in_layered, with the same n).  The copy proceeds in steps of one or
+ * more whole layers (several when a layer of the list is small, so that no step
+ * moves much less than 8 MiB); lamps_compute_wait_layer orders the compute stream
+ * behind the step that holds a given layer.  Everything else -- ordering, guards,
+ * errors, ticket calls -- is as for lamps_swap_out / lamps_swap_in. */
+int lamps_swap_out_layered(lamps_ctx *ctx, const int32_t *block_ids, int32_t n, void *host_buf,
+                           uint64_t *ticket);
+int lamps_swap_in_layered(lamps_ctx *ctx, const void *host_buf, const int32_t *block_ids, int32_t n,
+                          uint64_t *ticket);
+/* Makes the compute stream wait (on the device) until layer `layer` of the
+ * ticket's copy has landed.  For a ticket of the block-major calls this is
+ * lamps_compute_wait.  Errors: INVALID, RANGE (unknown ticket, layer), HIP. */
+int lamps_compute_wait_layer(lamps_ctx *ctx, uint64_t ticket, int32_t layer);
+
 /* LAMPS_OK if the ticket's copy has finished, LAMPS_ERR_BUSY if not. */
 int lamps_ticket_query(lamps_ctx *ctx, uint64_t ticket);
 /* Blocks the calling host thread until the ticket's copy has finished. */

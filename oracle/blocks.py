@@ -6,7 +6,9 @@ Discard : blocks go back to the free list; contents become undefined.
 Swap    : the request's KV cache is offloaded to CPU memory and reloaded when
           the API returns; a block id denotes the block in all layers, keys
           and values.  Host image of block i = key-pool bytes of that block
-          followed by value-pool bytes of that block.
+          followed by value-pool bytes of that block.  A second, layer-major
+          image holds the same bytes layer by layer (a reload in that order
+          lets the first layers run while the rest is on its way).
 
 The pools are opaque byte rows here: the model knows nothing of the layout
 inside a block.
@@ -49,6 +51,33 @@ class PoolModel:
         for i, b in enumerate(ids):
             self.k[b] = host[i, :self.half_bytes]
             self.v[b] = host[i, self.half_bytes:]
+
+
+    def swap_out_layered(self, block_ids, num_layers):
+        """The layer-major host image uint8[layers][n][2][half / layers]: the request's cache
+        layer by layer (a block's half is its layers one after the other), so that a reload
+        can hand over layer 0 first.  The pool is unchanged."""
+        ids = list(block_ids)
+        lb = self.half_bytes // num_layers
+        assert lb * num_layers == self.half_bytes
+        host = np.empty((num_layers, len(ids), 2, lb), dtype=np.uint8)
+        for layer in range(num_layers):
+            for i, b in enumerate(ids):
+                host[layer, i, 0] = self.k[b, layer * lb:(layer + 1) * lb]
+                host[layer, i, 1] = self.v[b, layer * lb:(layer + 1) * lb]
+        return host
+
+    def swap_in_layered(self, host, block_ids, num_layers, layers=None):
+        """Writes a layer-major image back (only the listed layers, if given: what has landed
+        when the reload is `layers` layers in); every other byte is untouched."""
+        ids = list(block_ids)
+        lb = self.half_bytes // num_layers
+        host = np.asarray(host, dtype=np.uint8).reshape(num_layers, len(ids), 2, lb)
+        assert len(set(ids)) == len(ids), "duplicate destination block"
+        for layer in (range(num_layers) if layers is None else layers):
+            for i, b in enumerate(ids):
+                self.k[b, layer * lb:(layer + 1) * lb] = host[layer, i, 0]
+                self.v[b, layer * lb:(layer + 1) * lb] = host[layer, i, 1]
 
 
 class AllocatorModel:

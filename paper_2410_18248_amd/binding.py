@@ -73,6 +73,9 @@ def load_library():
         "lamps_prefill_attn": [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp],
         "lamps_swap_out": [vp, vp, i32, vp, ctypes.POINTER(u64)],
         "lamps_swap_in": [vp, vp, vp, i32, ctypes.POINTER(u64)],
+        "lamps_swap_out_layered": [vp, vp, i32, vp, ctypes.POINTER(u64)],
+        "lamps_swap_in_layered": [vp, vp, vp, i32, ctypes.POINTER(u64)],
+        "lamps_compute_wait_layer": [vp, u64, i32],
         "lamps_ticket_query": [vp, u64],
         "lamps_ticket_wait": [vp, u64],
         "lamps_compute_wait": [vp, u64],
@@ -310,17 +313,22 @@ class Lamps:
                                                 _ptr(q_start), _ptr(block_table), _ptr(ctx_lens),
                                                 _ptr(out)))
 
-    def swap_out(self, block_ids, host_buf):
+    def swap_out(self, block_ids, host_buf, layered=False):
         arr, n = _ids(block_ids)
         t = ctypes.c_uint64()
-        self._check(self.lib.lamps_swap_out(self.h, arr, n, _ptr(host_buf), ctypes.byref(t)))
+        f = self.lib.lamps_swap_out_layered if layered else self.lib.lamps_swap_out
+        self._check(f(self.h, arr, n, _ptr(host_buf), ctypes.byref(t)))
         return t.value
 
-    def swap_in(self, host_buf, block_ids):
+    def swap_in(self, host_buf, block_ids, layered=False):
         arr, n = _ids(block_ids)
         t = ctypes.c_uint64()
-        self._check(self.lib.lamps_swap_in(self.h, _ptr(host_buf), arr, n, ctypes.byref(t)))
+        f = self.lib.lamps_swap_in_layered if layered else self.lib.lamps_swap_in
+        self._check(f(self.h, _ptr(host_buf), arr, n, ctypes.byref(t)))
         return t.value
+
+    def compute_wait_layer(self, ticket, layer):
+        self._check(self.lib.lamps_compute_wait_layer(self.h, ticket, layer))
 
     def ticket_query(self, ticket):
         rc = self.lib.lamps_ticket_query(self.h, ticket)

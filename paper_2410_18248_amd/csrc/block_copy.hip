@@ -5,8 +5,10 @@
 // other way when the API returns.
 //
 // Staging image i = key-pool bytes of block ids[i] (all layers) followed by its
-// value-pool bytes.  Pure 16-byte copies, bit-exact; grid.y walks (block, pool)
-// pairs, grid.x and a stride loop walk the bytes of one such half.
+// value-pool bytes; the layer-major variant packs [layer][i][keys | values] of a
+// range of layers instead, so that a swap can move one layer after the other.
+// Pure 16-byte copies, bit-exact; grid.y walks (block, pool) pairs, grid.x and a
+// stride loop walk the bytes of one such half.
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
@@ -52,7 +54,62 @@ hipError_t launch(void *k_pool, void *v_pool, const int32_t *ids, int32_t n, siz
     return hipGetLastError();
 }
 
+// One layer range of the listed blocks: grid.y walks (block, pool) pairs, grid.z the layers.
+template <bool GATHER>
+__global__ __launch_bounds__(kCopyThreads) void block_copy_layers(uint4 *k_pool, uint4 *v_pool,
+                                                                  const int32_t *ids, int n,
+                                                                  size_t half_vecs, size_t layer_vecs,
+                                                                  int layer0, uint4 *staging)
+{
+    const int i = blockIdx.y >> 1, which = blockIdx.y & 1, z = blockIdx.z;
+    const size_t b = (size_t)ids[i];
+    uint4 *pool = (which ? v_pool : k_pool) + b * half_vecs + (size_t)(layer0 + z) * layer_vecs;
+    uint4 *img = staging + (((size_t)z * n + i) * 2 + which) * layer_vecs;
+    for (size_t x = (size_t)blockIdx.x * kCopyThreads + threadIdx.x; x < layer_vecs;
+         x += (size_t)gridDim.x * kCopyThreads) {
+        if (GATHER)
+            img[x] = pool[x];
+        else
+            pool[x] = img[x];
+    }
+}
+
+template <bool GATHER>
+hipError_t launch_layers(void *k_pool, void *v_pool, const int32_t *ids, int32_t n, size_t half_bytes,
+                         size_t layer_bytes, int32_t layer0, int32_t nl, void *staging, hipStream_t stream)
+{
+    if (n == 0 || nl == 0) return hipSuccess;
+    if (n < 0 || 2 * (int64_t)n > 65535 || nl < 0 || nl > 65535 || layer0 < 0 || half_bytes % 16 != 0 ||
+        layer_bytes % 16 != 0 || (size_t)(layer0 + nl) * layer_bytes > half_bytes)
+        return hipErrorInvalidValue;
+    const size_t layer_vecs = layer_bytes / 16;
+    size_t gx = (layer_vecs + kCopyThreads * 4 - 1) / (kCopyThreads * 4);
+    if (gx < 1) gx = 1;
+    if (gx > 256) gx = 256;
+    dim3 grid((unsigned)gx, (unsigned)(2 * n), (unsigned)nl);
+    hipLaunchKernelGGL(block_copy_layers<GATHER>, grid, dim3(kCopyThreads), 0, stream,
+                       static_cast<uint4 *>(k_pool), static_cast<uint4 *>(v_pool), ids, (int)n, half_bytes / 16,
+                       layer_vecs, (int)layer0, static_cast<uint4 *>(staging));
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_gather_layers(const void *k_pool, const void *v_pool, const int32_t *ids, int32_t n,
+                                size_t half_bytes, size_t layer_bytes, int32_t layer0, int32_t nl,
+                                void *staging, hipStream_t stream)
+{
+    return launch_layers<true>(const_cast<void *>(k_pool), const_cast<void *>(v_pool), ids, n, half_bytes,
+                               layer_bytes, layer0, nl, staging, stream);
+}
+
+hipError_t launch_scatter_layers(void *k_pool, void *v_pool, const int32_t *ids, int32_t n,
+                                 size_t half_bytes, size_t layer_bytes, int32_t layer0, int32_t nl,
+                                 const void *staging, hipStream_t stream)
+{
+    return launch_layers<false>(k_pool, v_pool, ids, n, half_bytes, layer_bytes, layer0, nl,
+                                const_cast<void *>(staging), stream);
+}
 
 hipError_t launch_gather(const void *k_pool, const void *v_pool, const int32_t *ids, int32_t n,
                          size_t half_bytes, void *staging, hipStream_t stream)

@@ -74,5 +74,13 @@ hipError_t launch_gather(const void *k_pool, const void *v_pool, const int32_t *
                          size_t half_bytes, void *staging, hipStream_t stream);
 hipError_t launch_scatter(void *k_pool, void *v_pool, const int32_t *ids, int32_t n,
                           size_t half_bytes, const void *staging, hipStream_t stream);
+// The same for `nl` layers starting at `layer0` only; staging (and the host image of the
+// layer-major swap calls) is [layer - layer0][i][keys | values] with layer_bytes each.
+hipError_t launch_gather_layers(const void *k_pool, const void *v_pool, const int32_t *ids, int32_t n,
+                                size_t half_bytes, size_t layer_bytes, int32_t layer0, int32_t nl,
+                                void *staging, hipStream_t stream);
+hipError_t launch_scatter_layers(void *k_pool, void *v_pool, const int32_t *ids, int32_t n,
+                                 size_t half_bytes, size_t layer_bytes, int32_t layer0, int32_t nl,
+                                 const void *staging, hipStream_t stream);
 
 }  // namespace lamps

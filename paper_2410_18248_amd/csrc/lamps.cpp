@@ -10,6 +10,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -94,6 +95,8 @@ struct Ticket {
     size_t ring_slots;
     const char *host_lo, *host_hi;   // host bytes the copy writes (swap-out) or reads (swap-in)
     bool is_out;
+    std::vector<hipEvent_t> step_ev; // layer-major copies: one event per step of layers_per_step layers
+    int32_t layers_per_step = 0;
 };
 
 }  // namespace
@@ -178,6 +181,7 @@ void retire_finished(lamps_ctx *c)
 {
     while (!c->tickets.empty() && hipEventQuery(c->tickets.front().ev) == hipSuccess) {
         c->spare_events.push_back(c->tickets.front().ev);
+        for (hipEvent_t e : c->tickets.front().step_ev) c->spare_events.push_back(e);
         c->ring_tail += c->tickets.front().ring_slots;
         c->tickets.pop_front();
         ++c->base_ticket;
@@ -302,6 +306,89 @@ int wait_host_overlap(lamps_ctx *c, hipStream_t stream, const char *lo, const ch
         if (t.is_out == other_is_out && t.host_lo < hi && lo < t.host_hi &&
             hipEventQuery(t.ev) != hipSuccess)
             LAMPS_HIP(hipStreamWaitEvent(stream, t.ev, 0));
+    return LAMPS_OK;
+}
+
+// The layer-major swap, both directions.
+int swap_layered(lamps_ctx *c, bool out, char *host, const int32_t *block_ids, int32_t n, uint64_t *ticket,
+                 const char *who)
+{
+    if (!ticket || (n > 0 && !host)) return fail(c, LAMPS_ERR_INVALID, std::string(who) + ": null argument");
+    int rc = check_ids(c, block_ids, n, who);
+    if (rc != LAMPS_OK) return rc;
+    if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
+    retire_finished(c);
+    int32_t *ids = nullptr;
+    size_t slots = 0;
+    if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
+    if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
+    hipEvent_t ev;
+    if ((rc = new_event(c, &ev)) != LAMPS_OK) return rc;
+
+    hipStream_t st = out ? c->os : c->is;
+    LAMPS_HIP(hipEventRecord(c->fence, c->cs));
+    LAMPS_HIP(hipStreamWaitEvent(st, c->fence, 0));
+    if ((rc = wait_guards(c, st, out ? c->in_guard : c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
+    const size_t total = (size_t)n * c->d.block_bytes;
+    if ((rc = wait_host_overlap(c, st, host, host + total, !out)) != LAMPS_OK) return rc;
+
+    const int32_t L = c->cfg.num_layers;
+    const size_t layer_bytes = c->d.half_bytes / L;          // one block, one pool, one layer
+    const size_t slice = (size_t)n * 2 * layer_bytes;         // one layer of the whole list
+    char *stage = out ? c->stage_out : c->stage_in;
+    Ticket t{ev, slots, host, host + total, out, {}, 0};
+    if (n > 0) {
+        // whole layers per step while a layer of the list fits the staging area, else one layer
+        // in chunks of blocks
+        int32_t nl = 1;
+        if (slice <= c->d.staging_bytes) {
+            const size_t want = (size_t)8 << 20;
+            nl = (int32_t)std::min<size_t>({(size_t)L, c->d.staging_bytes / slice, (want + slice - 1) / slice});
+            if (nl < 1) nl = 1;
+        }
+        int32_t bpc = (int32_t)std::min<size_t>({(size_t)n, c->d.staging_bytes / (2 * layer_bytes), (size_t)16384});
+        t.layers_per_step = nl;
+        for (int32_t l0 = 0; l0 < L; l0 += nl) {
+            const int32_t cnt_l = std::min<int32_t>(nl, L - l0);
+            char *himg = host + (size_t)l0 * slice;
+            if (slice <= c->d.staging_bytes) {
+                if (out) {
+                    LAMPS_HIP(lamps::launch_gather_layers(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, layer_bytes,
+                                                          l0, cnt_l, stage, st));
+                    LAMPS_HIP(hipMemcpyAsync(himg, stage, (size_t)cnt_l * slice, hipMemcpyDeviceToHost, st));
+                } else {
+                    LAMPS_HIP(hipMemcpyAsync(stage, himg, (size_t)cnt_l * slice, hipMemcpyHostToDevice, st));
+                    LAMPS_HIP(lamps::launch_scatter_layers(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, layer_bytes,
+                                                           l0, cnt_l, stage, st));
+                }
+            } else {
+                for (int32_t done = 0; done < n; done += bpc) {
+                    const int32_t cnt = std::min<int32_t>(bpc, n - done);
+                    char *hc = himg + (size_t)done * 2 * layer_bytes;
+                    const size_t bytes = (size_t)cnt * 2 * layer_bytes;
+                    if (out) {
+                        LAMPS_HIP(lamps::launch_gather_layers(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                                              layer_bytes, l0, 1, stage, st));
+                        LAMPS_HIP(hipMemcpyAsync(hc, stage, bytes, hipMemcpyDeviceToHost, st));
+                    } else {
+                        LAMPS_HIP(hipMemcpyAsync(stage, hc, bytes, hipMemcpyHostToDevice, st));
+                        LAMPS_HIP(lamps::launch_scatter_layers(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                                               layer_bytes, l0, 1, stage, st));
+                    }
+                }
+            }
+            hipEvent_t se;
+            if ((rc = new_event(c, &se)) != LAMPS_OK) return rc;
+            LAMPS_HIP(hipEventRecord(se, st));
+            t.step_ev.push_back(se);
+        }
+    }
+    LAMPS_HIP(hipEventRecord(ev, st));
+    c->tickets.push_back(t);
+    const uint64_t id = c->base_ticket + c->tickets.size() - 1;
+    std::vector<uint64_t> &guard = out ? c->out_guard : c->in_guard;
+    for (int32_t i = 0; i < n; ++i) guard[block_ids[i]] = id;
+    *ticket = id;
     return LAMPS_OK;
 }
 
@@ -630,6 +717,35 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
     const uint64_t id = c->base_ticket + c->tickets.size() - 1;
     for (int32_t i = 0; i < n; ++i) c->in_guard[block_ids[i]] = id;
     *ticket = id;
+    return LAMPS_OK;
+}
+
+int lamps_swap_out_layered(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host_buf, uint64_t *ticket)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    return swap_layered(c, true, static_cast<char *>(host_buf), block_ids, n, ticket, "lamps_swap_out_layered");
+}
+
+int lamps_swap_in_layered(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, int32_t n,
+                          uint64_t *ticket)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    return swap_layered(c, false, const_cast<char *>(static_cast<const char *>(host_buf)), block_ids, n, ticket,
+                        "lamps_swap_in_layered");
+}
+
+int lamps_compute_wait_layer(lamps_ctx *c, uint64_t ticket, int32_t layer)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_compute_wait_layer: unknown ticket");
+    if (layer < 0 || layer >= c->cfg.num_layers)
+        return fail(c, LAMPS_ERR_RANGE, "lamps_compute_wait_layer: layer out of range");
+    if (ticket_done(c, ticket)) return LAMPS_OK;
+    const Ticket &t = c->tickets[ticket - c->base_ticket];
+    hipEvent_t e = t.ev;
+    if (t.layers_per_step > 0 && (size_t)(layer / t.layers_per_step) < t.step_ev.size())
+        e = t.step_ev[layer / t.layers_per_step];
+    if (hipEventQuery(e) != hipSuccess) LAMPS_HIP(hipStreamWaitEvent(c->cs, e, 0));
     return LAMPS_OK;
 }
 

@@ -3,7 +3,8 @@ GPU calls of lamps.h execute.
 
 Every iteration of Algorithm 1 (arXiv 2410.18248) becomes:
   lamps_sched_next_batch  -> which requests run, and what each brings back first
-      swap_in   > 0 : lamps_alloc_blocks + lamps_swap_in + lamps_compute_wait   (Swap)
+      swap_in   > 0 : lamps_alloc_blocks + lamps_swap_in + lamps_compute_wait   (Swap; or the
+                      layer-major calls, each layer's work behind lamps_compute_wait_layer)
       recompute > 0 : lamps_alloc_blocks + lamps_kv_append_tokens + lamps_prefill_attn
                       per layer (Discard's recompute, a prompt, an API response)
       otherwise     : lamps_kv_append + lamps_decode_attn per layer (one new token)
@@ -44,11 +45,14 @@ class RandomSource:
 
 
 class LiveEngine:
-    def __init__(self, cfg, sched_cfg, source, device="cuda:0", observer=None):
+    def __init__(self, cfg, sched_cfg, source, device="cuda:0", observer=None, layered_swap=False):
         """cfg: LampsConfig (pools are allocated here); sched_cfg: LampsSchedConfig whose
         memory_tokens must not exceed num_blocks * block_size; observer(kind, rid, layer, first_pos,
-        out_rows): called with the attention output of every processed token (tests)."""
+        out_rows): called with the attention output of every processed token (tests);
+        layered_swap: swap layer-major, so that a returning request's first layers run while the
+        later ones are still on their way."""
         self.cfg, self.dev, self.source, self.observer = cfg, torch.device(device), source, observer
+        self.layered = layered_swap
         self.tdtype = torch.bfloat16 if cfg.dtype == P.LAMPS_BF16 else torch.float32
         elems = P.lamps_pool_bytes(cfg) // (2 if cfg.dtype == P.LAMPS_BF16 else 4)
         self.k_pool = torch.zeros(elems, dtype=self.tdtype, device=self.dev)
@@ -113,14 +117,18 @@ class LiveEngine:
         self._inflight = [(t, b) for t, b in self._inflight if not lam.ticket_query(t)]
         t0 = time.perf_counter()
         dec, pre = [], []                           # (rid,) / (rid, count)
+        landing = []                                # layer-major swap-ins of this iteration
         with torch.cuda.stream(self.cs):
             for rid, swap_in, recompute, _ in batch:
                 if swap_in:                         # Swap: back from pinned host memory into fresh blocks
                     buf, nblk, tokens = self.host.pop(rid)
                     assert tokens == swap_in
                     ids = lam.alloc_blocks(nblk)
-                    ticket = lam.swap_in(buf, ids)
-                    lam.compute_wait(ticket)
+                    ticket = lam.swap_in(buf, ids, layered=self.layered)
+                    if self.layered:
+                        landing.append(ticket)      # each layer's work waits for its own slice only
+                    else:
+                        lam.compute_wait(ticket)
                     self._inflight.append((ticket, buf))    # the buffer lives until the copy is done
                     self.blocks[rid], self.ctx[rid] = ids, tokens
                     self.stats["swapped_in_blocks"] += nblk
@@ -141,6 +149,8 @@ class LiveEngine:
                 cd = torch.tensor([self.ctx[r] for r in rids], dtype=torch.int32, device=self.dev)
                 total = int(sum(counts))
                 for layer in range(L):
+                    for ticket in landing:
+                        lam.compute_wait_layer(ticket, layer)
                     parts = [self.source.rows(r, f, n, layer) for r, f, n in zip(rids, first, counts)]
                     q = torch.cat([p[0] for p in parts]).contiguous().to(self.dev)
                     k = torch.cat([p[1] for p in parts]).contiguous().to(self.dev)
@@ -162,6 +172,8 @@ class LiveEngine:
                 cd = torch.tensor([self.ctx[r] for r in dec], dtype=torch.int32, device=self.dev)
                 md = torch.ones(len(dec), dtype=torch.uint8, device=self.dev)
                 for layer in range(L):
+                    for ticket in landing:
+                        lam.compute_wait_layer(ticket, layer)
                     parts = [self.source.rows(r, self.ctx[r], 1, layer) for r in dec]
                     q = torch.cat([p[0] for p in parts]).contiguous().to(self.dev)
                     k = torch.cat([p[1] for p in parts]).contiguous().to(self.dev)
@@ -192,7 +204,7 @@ class LiveEngine:
             elif handling == P.LAMPS_SWAP:
                 ids = self.blocks[rid]
                 buf = torch.empty(max(1, len(ids) * self.block_bytes), dtype=torch.uint8).pin_memory()
-                ticket = lam.swap_out(ids, buf)     # the library orders the blocks' reuse behind the copy
+                ticket = lam.swap_out(ids, buf, layered=self.layered)   # the library orders the blocks' reuse behind the copy
                 self._inflight.append((ticket, buf))
                 self.host[rid] = (buf, len(ids), self.ctx[rid])
                 self.stats["swapped_out_blocks"] += len(ids)

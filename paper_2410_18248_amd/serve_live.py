@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--memory-tokens", type=int, default=6000)
     ap.add_argument("--max-batch", type=int, default=16)
     ap.add_argument("--seed", type=int, default=2410)
+    ap.add_argument("--layered-swap", action="store_true", help="swap layer-major (a returning request runs layer by layer)")
     a = ap.parse_args()
     import torch
     pol = {"fcfs": P.LAMPS_POLICY_FCFS, "sjf": P.LAMPS_POLICY_SJF, "sjf_total": P.LAMPS_POLICY_SJF_TOTAL,
@@ -51,7 +52,8 @@ def main():
     # cost model used for the handling decision and the rank only (time itself is measured)
     cost = P.LampsCostModel(2e-3, 2e-8 * a.layers, 1e-3, 3e-6 * a.layers, 3e-4, 3.7e-7 * a.layers, 0, 0)
     scfg = P.LampsSchedConfig(pol, a.max_batch, a.memory_tokens, 100, 1, 2048, 0.5 * a.memory_tokens, M, cost)
-    eng = LiveEngine(cfg, scfg, RandomSource(a.seed, a.heads, a.kv_heads, D, torch.bfloat16))
+    eng = LiveEngine(cfg, scfg, RandomSource(a.seed, a.heads, a.kv_heads, D, torch.bfloat16),
+                     layered_swap=a.layered_swap)
     trace = synthetic_trace(a.seed, a.requests, a.rate)
     for rid, arr, prompt, segs, _ in trace:
         eng.add(rid, arr, prompt, [(n, None if d is None else d * a.time_scale, rho, None) for n, d, rho in segs])

@@ -38,7 +38,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "lamps.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = sorted(set(re.findall(r"\b(lamps_[a-z_]+)\s*\(", header)))
-    assert len(names) >= 19 and "lamps_kv_append" in names
+    assert len(names) >= 22 and "lamps_kv_append" in names and "lamps_swap_in_layered" in names
     lib = P.load_library()
     for n in names:
         assert hasattr(lib, n), n

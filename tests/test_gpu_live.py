@@ -19,9 +19,10 @@ def _bits(t):
     return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
 
 
-@pytest.mark.parametrize("dtype,H,Hkv,policy", [("bf16", 4, 4, P.LAMPS_POLICY_LAMPS), ("bf16", 8, 2, P.LAMPS_POLICY_FCFS),
-                                                ("f32", 4, 2, P.LAMPS_POLICY_SJF)])
-def test_trace_served_on_the_gpu_matches_the_oracle_token_by_token(dtype, H, Hkv, policy):
+@pytest.mark.parametrize("dtype,H,Hkv,policy,layered", [
+    ("bf16", 4, 4, P.LAMPS_POLICY_LAMPS, False), ("bf16", 8, 2, P.LAMPS_POLICY_FCFS, False),
+    ("f32", 4, 2, P.LAMPS_POLICY_SJF, False), ("bf16", 8, 2, P.LAMPS_POLICY_LAMPS, True)])
+def test_trace_served_on_the_gpu_matches_the_oracle_token_by_token(dtype, H, Hkv, policy, layered):
     L, D, bs = 2, 64, 16
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     memory_tokens, n_req = 400, 10
@@ -42,7 +43,7 @@ def test_trace_served_on_the_gpu_matches_the_oracle_token_by_token(dtype, H, Hkv
         worst[0] = max(worst[0], float(np.abs(rows.double().numpy() - ref).max()))
         seen[(rid, layer)] = seen.get((rid, layer), 0) + n
 
-    eng = LiveEngine(cfg, scfg, src, observer=observer)
+    eng = LiveEngine(cfg, scfg, src, observer=observer, layered_swap=layered)
     u = W.uniform01(5, 10 * n_req)
     want_tokens = {}
     strategies = [P.LAMPS_PRESERVE, P.LAMPS_DISCARD, P.LAMPS_SWAP]

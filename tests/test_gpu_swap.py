@@ -68,6 +68,85 @@ def test_swap_out_image_and_round_trip(dtype, L, Hkv, D, bs, staging_blocks, dir
     rig.close()
 
 
+@pytest.mark.parametrize("dtype,L,Hkv,D,bs,staging_blocks", [
+    ("f32", 1, 8, 64, 16, 0), ("bf16", 3, 2, 128, 16, 4), ("bf16", 5, 4, 128, 32, 1), ("bf16", 40, 2, 64, 16, 0)])
+def test_layer_major_swap_image_and_round_trip(dtype, L, Hkv, D, bs, staging_blocks):
+    """The layer-major variant: image layout against the oracle's, round trip into other
+    blocks, every other block untouched; small staging areas force steps of one layer in
+    chunks of blocks, large ones several layers per step."""
+    geom = W.Geometry(L, Hkv, Hkv, D, bs, 48, 8, dtype)
+    bb = 2 * geom.block_half_bytes
+    rig = Rig(geom, max_batch=2, staging_bytes=staging_blocks * bb)
+    lam = rig.lamps
+    _fill_random(rig, 12)
+    model = _model(rig)
+    lam.alloc_blocks(geom.num_blocks)
+    src = [int(x) for x in W.permutation(6, geom.num_blocks)[:11]]
+    host = _pinned(len(src) * bb)
+    t = lam.swap_out(src, host, layered=True)
+    lam.ticket_wait(t)
+    want = model.swap_out_layered(src, L)
+    np.testing.assert_array_equal(host.numpy().reshape(want.shape), want)
+    np.testing.assert_array_equal(_bytes(rig.k_pool).reshape(geom.num_blocks, -1), model.k)
+    dst = [int(x) for x in W.permutation(6, geom.num_blocks)[20:31]]
+    t2 = lam.swap_in(host, dst, layered=True)
+    for layer in range(L):
+        lam.compute_wait_layer(t2, layer)           # enqueues waits on the compute stream; any order is legal
+    with pytest.raises(P.LampsError) as e:
+        lam.compute_wait_layer(t2, L)
+    assert e.value.status == -2
+    lam.ticket_wait(t2)
+    lam.compute_wait_layer(t2, 0)                   # a finished ticket: nothing to wait for
+    model.swap_in_layered(want, dst, L)
+    np.testing.assert_array_equal(_bytes(rig.k_pool).reshape(geom.num_blocks, -1), model.k)
+    np.testing.assert_array_equal(_bytes(rig.v_pool).reshape(geom.num_blocks, -1), model.v)
+    rig.close()
+
+
+def test_layer_major_swap_in_feeds_decode_layer_by_layer():
+    """A swapped-out request comes back layer-major into new blocks; each layer is decoded
+    behind lamps_compute_wait_layer only, and matches the oracle."""
+    geom = W.Geometry(6, 8, 2, 128, 16, 300, 40, "bf16")
+    ctx = [600, 200]
+    B = len(ctx)
+    rig = Rig(geom, max_batch=B)
+    lam = rig.lamps
+    lam.alloc_blocks(geom.num_blocks)
+    perm = W.permutation(9, geom.num_blocks)
+    table, used = W.deal_block_table(perm, ctx, geom)
+    lam.free_blocks([int(x) for x in perm[used:]])
+    K, V, q = [], [], W.queries(9, geom, B)
+    for r, c in enumerate(ctx):
+        k, v = W.logical_kv(200 + r, geom, c)
+        K.append(k)
+        V.append(v)
+    for layer in range(geom.num_layers):
+        rig.page_requests(layer, table, K, V)       # the same K, V in every layer
+    ref = oracle.decode_attn(q, K, V, ctx, [1] * B)
+    bb = 2 * geom.block_half_bytes
+    old = [int(x) for x in table[0, :geom.blocks_for(ctx[0])]]
+    host = _pinned(len(old) * bb)
+    lam.swap_out(old, host, layered=True)
+    lam.free_blocks(old)
+    new = lam.alloc_blocks(len(old))[::-1]          # the same physical blocks in another order
+    tab = table.copy()
+    tab[0, :len(new)] = new
+    with torch.cuda.stream(rig.compute):
+        idx = torch.as_tensor(old, device=rig.dev)
+        lam.compute_wait_blocks(old)
+        rig.k_pool[idx] = 0.0                       # whatever the swap-in has not brought back is wrong
+        rig.v_pool[idx] = 0.0
+    ticket = lam.swap_in(host, new, layered=True)
+    outs = []
+    for layer in range(geom.num_layers):
+        lam.compute_wait_layer(ticket, layer)
+        outs.append(rig.decode(layer, q, tab, ctx, [1] * B))
+    for layer, got in enumerate(outs):
+        np.testing.assert_allclose(to_f64(got), ref, rtol=0, atol=2e-2, err_msg="layer %d" % layer)
+    lam.ticket_wait(ticket)
+    rig.close()
+
+
 def test_empty_list_and_ticket_errors():
     geom = W.Geometry(1, 2, 2, 64, 16, 8, 2, "bf16")
     rig = Rig(geom, max_batch=1)

@@ -62,6 +62,33 @@ def test_swap_round_trip_is_identity_and_touches_nothing_else():
             assert _crc(p.k[b]) == before_k[b] and _crc(p.v[b]) == before_v[b]
 
 
+def test_layer_major_image_is_a_permutation_of_the_block_major_one():
+    """Pins the layer-major image by the block-major one (itself pinned above): byte x of
+    layer l of block i's key half sits at [l][i][0][x]; a reload of all layers is the same
+    identity, a reload of the first layers only restores exactly those bytes."""
+    L, lb = 3, 8
+    p = _pool(4, 10, L * lb)
+    src, dst = [5, 1, 8], [0, 9, 2]
+    flat = p.swap_out(src)
+    img = p.swap_out_layered(src, L)
+    assert img.shape == (L, 3, 2, lb) and img.size == flat.size
+    for i in range(3):
+        for layer in range(L):
+            assert img[layer, i, 0].tobytes() == flat[i, layer * lb:(layer + 1) * lb].tobytes()
+            assert img[layer, i, 1].tobytes() == flat[i, L * lb + layer * lb:L * lb + (layer + 1) * lb].tobytes()
+    q = PoolModel(p.k, p.v)
+    q.swap_in(flat, dst)
+    r = PoolModel(p.k, p.v)
+    r.swap_in_layered(img, dst, L)
+    np.testing.assert_array_equal(q.k, r.k)
+    np.testing.assert_array_equal(q.v, r.v)
+    part = PoolModel(p.k, p.v)
+    part.swap_in_layered(img, dst, L, layers=[0])
+    np.testing.assert_array_equal(part.k[dst][:, :lb], q.k[dst][:, :lb])
+    np.testing.assert_array_equal(part.k[dst][:, lb:], p.k[dst][:, lb:])      # later layers not there yet
+    np.testing.assert_array_equal(part.v[dst][:, lb:], p.v[dst][:, lb:])
+
+
 def test_swap_in_rejects_duplicate_destination():
     p = _pool(3, 4, 8)
     with pytest.raises(AssertionError):
