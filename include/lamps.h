@@ -208,7 +208,7 @@ int lamps_kv_append_tokens(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t
  * rounded to nearest even, results independent of block placement.
  * max_new_tokens: an upper bound, known on the host, of the new tokens of any one
  * request (it sizes the launch; 0 = unknown, total_tokens is used).  bf16 with at
- * most 64 query heads per kv head runs on the matrix cores (weights rounded to
+ * most 32 query heads per kv head runs on the matrix cores (weights rounded to
  * bf16 before the second product); other geometries, and any geometry when
  * max_new_tokens < 0, run one wavefront per new token with fp32 weights. */
 int lamps_prefill_attn(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t total_tokens,

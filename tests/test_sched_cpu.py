@@ -110,6 +110,40 @@ def test_step_interface_reports_what_the_driver_must_do():
     sched.destroy()
 
 
+def test_out_of_memory_discards_are_reported_once_and_recomputed():
+    """Two requests come back from Preserve calls holding 5 tokens each with room for neither's
+    next segment: the worse-ranked one is discarded; the step interface names it once, and it
+    recomputes its context when it runs again.  Totals equal the oracle's."""
+    cost = S.CostModel(unit=True)
+
+    def reqs():
+        return [S.Request(i, 0.0, 3, [(2, 1.0, 0), (4, None, 0)], [S.PRESERVE, None]) for i in (1, 2)]
+    sim = S.Simulator(reqs(), S.FCFS, 2, 12, cost).run()
+    assert sim.preemptions >= 1
+    sched = P.LampsSched(_cfg(S.FCFS, 2, 12, cost))
+    for r in reqs():
+        sched.add(r.id, r.arrival, r.prompt, [(s[0], s[1], s[2], r.handling[k]) for k, s in enumerate(r.segments)])
+    dropped, recomputed = [], {}
+    for _ in range(200):
+        batch = sched.next_batch()
+        got = sched.take_discards()
+        assert sched.take_discards() == []            # each is reported once
+        dropped += got
+        if not batch:
+            break
+        for rid, swap_in, recompute, context in batch:
+            if rid in dropped and recompute > 0:
+                recomputed[rid] = recomputed.get(rid, 0) + recompute
+        sched.commit()
+    assert len(dropped) == sim.preemptions == sched.stats()[2]
+    for rid in set(dropped):
+        assert recomputed[rid] >= 5                   # prompt + the two generated tokens come back by recompute
+    for r in sim.reqs:
+        c, f, h = sched.result(r.id, len(r.segments))
+        assert c == r.completion and f == r.first_token
+    sched.destroy()
+
+
 def test_closed_forms_equal_the_oracle():
     u = W.uniform01(99, 900)
     for k in range(100):
