@@ -27,6 +27,11 @@ CASES = [
     ("bf16", 8, 2, 128, 16, [(333, 333), (500, 100)]),
     ("bf16", 6, 2, 128, 16, [(100, 100), (77, 10)]),                                 # group of 3
     ("bf16", 4, 4, 256, 16, [(90, 90), (50, 6)]),
+    # few new tokens per request: the waves of a workgroup split the cached positions (4 and 2 ways)
+    ("bf16", 4, 4, 128, 16, [(300, 20), (150, 32), (64, 1), (33, 0)]),
+    ("bf16", 4, 4, 128, 16, [(300, 50), (100, 64), (70, 3)]),
+    ("bf16", 8, 2, 128, 16, [(500, 8), (100, 3), (8, 8)]),
+    ("bf16", 8, 2, 64, 32, [(200, 16), (90, 9)]),
 ]
 
 
