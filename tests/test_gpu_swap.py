@@ -155,6 +155,10 @@ def test_empty_list_and_ticket_errors():
     t = lam.swap_out([], host)
     lam.ticket_wait(t)
     assert lam.ticket_query(t)
+    t = lam.swap_in(host, [], layered=True)         # an empty layer-major copy is a ticket like any other
+    lam.compute_wait_layer(t, 0)
+    lam.ticket_wait(t)
+    assert lam.ticket_query(t)
     with pytest.raises(P.LampsError) as e:
         lam.ticket_wait(t + 5)
     assert e.value.status == -2
