@@ -61,10 +61,11 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
 //
 // One workgroup = one (request, kv head, tile of new tokens); its four waves each
 // own kCols = 32 columns (kCols / G tokens x G heads) as blocks of 16.  K and V
-// are streamed 32 positions at a time through LDS: all 256 threads load stage
-// s + 2 from the paged pools into registers and write stage s + 1 to LDS while
-// stage s is consumed (two LDS buffers, one barrier per stage; one buffer and two
-// barriers where two do not fit).  Every wave reads each K / V operand from LDS
+// are streamed 32 positions at a time through LDS: while stage s is consumed,
+// stage s + 1 arrives in the other of two LDS buffers (tiled layout: straight from
+// the pools; plain layout: all 256 threads load stage s + 2 into registers and
+// write stage s + 1 to LDS), one barrier per stage; one buffer and two barriers
+// where two do not fit.  Every wave reads each K / V operand from LDS
 // once per stage and uses it for both column blocks.  Scores come out transposed
 // (lane: four consecutive positions of one column), which is the operand layout
 // the second product wants for the weights, so nothing is shuffled between the
@@ -84,15 +85,16 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
 // (they accumulate, like the outputs, in registers and need no cross-lane sum at
 // the end), and V reaches the second product without any shuffling in registers.
 //
-// LDS layouts of a stage.  Tiled pool layout: K tiles as they are (16-byte runs
-// are operands already); V in two planes (dims 32 i + j and 32 i + 16 + j), where
-// unit ((i * 4 + qd) * 16 + j) of a plane holds, for its dim, positions
-// 4 qd .. 4 qd + 3 of the first and of the second 16-position half -- the 8-deep
-// operand -- written as the two 8-byte halves of the pool's 16-byte units.  Plain
-// layout: K and V row-major, K rows padded by 16 bytes (the 16 rows of an operand
-// fall in different banks), V rows by 32; V^T operands come out of the transposing
-// LDS read of gfx950 (ds_read_b64_tr_b16: the 16 lanes of a group read four rows
-// of 16 dims, lane j receives dim j of the four rows).
+// LDS layouts of a stage.  Tiled pool layout: K and V tiles as they are, brought
+// in by loads that write LDS directly (no registers, no LDS-write instructions;
+// a K unit is an operand already, a V operand is the first or the second 8 bytes
+// of the same unit of the stage's two sub-tiles).  Where two stage buffers do not
+// fit (head_dim 256) the tiles go through registers, and V is regrouped on the
+// way into two planes (dims 32 i + j and 32 i + 16 + j) whose 16-byte units are
+// operands.  Plain layout: K and V row-major, K rows padded by 16 bytes (the 16
+// rows of an operand fall in different banks), V rows by 32; V^T operands come out
+// of the transposing LDS read of gfx950 (ds_read_b64_tr_b16: the 16 lanes of a
+// group read four rows of 16 dims, lane j receives dim j of the four rows).
 constexpr int kMaxCols = 32;             // columns per wave: two blocks of 16 keep a wave under 256 registers,
                                          // so two workgroups share a CU and cover each other's stalls
 constexpr int kStage = 32;               // cached positions per LDS stage
@@ -109,13 +111,18 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
     constexpr int NS = D / 16;                       // 16-dim slabs of the output
     constexpr int U = D * 2;                         // 16-byte units of one 16-position sub-tile
     constexpr int LPT = (2 * U) / kThreads;          // units per thread, pool and stage
-    constexpr int ROWB = D * 2 + 16;                 // plain layout: padded K row, bytes
-    constexpr int ROWV = D * 2 + 32;                 // plain layout: padded V row
-    constexpr int SUBB = TILED ? 16 * D * 2 : 16 * ROWB;   // K sub-tile in LDS
-    constexpr int PLANE = U * 16;                    // tiled layout: one V plane of a stage
+    // Up to head_dim 128 two stage buffers fit and the pool's tiles go to LDS as they are, by loads
+    // that write LDS directly (global_load_lds_dwordx4: lane l of a wave writes 16 bytes at
+    // base + 16 l, read from any address); above, one buffer, filled through registers.
+    constexpr bool DMA = D <= 128;
+    constexpr int NB = DMA ? 2 : 1;                  // stage buffers
+    constexpr int NU = D / 8;                        // 16-byte units of one row (plain layout)
+    constexpr int ROWB = D * 2 + 16;                 // plain layout through registers: padded K row, bytes
+    constexpr int ROWV = D * 2 + 32;                 // ... padded V row
+    constexpr int SUBB = TILED || DMA ? 16 * D * 2 : 16 * ROWB;   // K sub-tile in LDS
+    constexpr int PLANE = U * 16;                    // tiled layout through registers: one V plane of a stage
     constexpr int VOFF = 2 * SUBB;                   // V follows the two K sub-tiles
-    constexpr int STAGE = VOFF + (TILED ? 2 * PLANE : 32 * ROWV);
-    constexpr int NB = 2 * STAGE <= 40 * 1024 ? 2 : 1;     // stage buffers
+    constexpr int STAGE = VOFF + (TILED || DMA ? 2 * PLANE : 32 * ROWV);
     static_assert(LPT >= 1 && (2 * U) % kThreads == 0, "head_dim");
     __shared__ __align__(16) char lds[NB * STAGE];
 
@@ -135,7 +142,8 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
     if (tile * WT >= n_new) return;
     const int C = a.ctx_lens[r];
     const int base_pos = C - n_new;                  // position of the request's first new token
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 15, qd = lane >> 4;
 
     // this lane's column in each block: (token, head), its position, its q slices
@@ -256,10 +264,71 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
         }
     };
 
+    // Direct form: the stage's tiles from the pools straight into LDS buffer `buf`, each wave
+    // instruction one run of 64 units (1 KiB).  Nothing waits here: the caller waits for vmcnt
+    // before the barrier that publishes the stage.
+    auto dma = [&](int st, char *buf) {
+        const long long at0 = where(st * kStage, e0), at1 = where(st * kStage + 16, e1);
+#pragma unroll
+        for (int k = 0; k < LPT; ++k) {
+            const int x0 = kThreads * k + 64 * wv;    // the wave's first unit: sub-tile x0 / U, unit x0 % U
+            const long long off = x0 / U ? at1 : at0;
+            if (off >= 0) {
+                // (written as assembly: the compiler would make every later LDS read wait for these loads;
+                // m0, the LDS base of such a load, is a register the compiler reserves and sets itself
+                // before any instruction of its own that reads it)
+                typedef __attribute__((address_space(3))) char *lptr;
+                const int x = x0 % U + lane;          // the lane's LDS slot within the sub-tile
+                // Tiled layout: slot x holds unit x.  Plain layout (rows of NU units, which cannot be
+                // padded here): slot s of row r holds unit s ^ (r mod NU) of a K row and s ^ (2 r mod NU)
+                // of a V row, so that the rows an operand read touches fall in different banks.
+                const int row = x / NU, sl = x % NU;
+                const int xk = TILED ? x : row * NU + (sl ^ (row & (NU - 1)));
+                const int xv = TILED ? x : row * NU + (sl ^ ((2 * row) & (NU - 1)));
+                const uint32_t lk = (uint32_t)(uintptr_t)(lptr)(buf + x0 * 16), lv = lk + VOFF;
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lk),
+                             "v"(kp + (size_t)off + (size_t)xk * 16) : "memory");
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lv),
+                             "v"(vp + (size_t)off + (size_t)xv * 16) : "memory");
+            }
+        }
+    };
+    // The same zeroing of value slots at or past the context's end, for a stage already in LDS.
+    auto zero_tail = [&](int st, char *buf) {
+#pragma unroll
+        for (int k = 0; k < LPT; ++k) {
+            const int x = tid + kThreads * k, u = x / U, unit = x % U;
+            if (!TILED) {                             // a slot is part of one row: position 16 u + unit / NU
+                if (st * kStage + 16 * u + unit / NU >= C)
+                    *reinterpret_cast<uint4 *>(buf + VOFF + x * 16) = make_uint4(0, 0, 0, 0);
+                continue;
+            }
+            const int valid = C - (st * kStage + 16 * u + 4 * ((unit >> 4) & 3));
+            if (valid < 4) {
+                uint4 *slot = reinterpret_cast<uint4 *>(buf + VOFF + x * 16);
+                uint4 v = *slot;
+                const uint32_t m01 = valid >= 2 ? 0xFFFFFFFFu : (valid == 1 ? 0x0000FFFFu : 0u);
+                const uint32_t m23 = valid == 3 ? 0x0000FFFFu : 0u;
+                v.x &= m01; v.z &= m01;
+                v.y &= m23; v.w &= m23;
+                *slot = v;
+            }
+        }
+    };
+
     // per-lane operand offsets in a stage buffer
     const int koff = TILED ? qd * 256 + j * 16 : j * ROWB + qd * 16;   // + i * (TILED ? 1024 : 64), + SUBB for the second half
     const int voff = VOFF + (TILED ? (qd * 16 + j) * 16                // + i * 1024, + PLANE for dims 16 + j
                                    : (4 * qd + (j >> 2)) * ROWV + (j & 3) * 8);   // + s * 32, + 16 * ROWV for the second half
+    // plain layout, tiles as they are: the swizzled slots of this lane's operands
+    int kslot[NK], vslot[NS];
+#pragma unroll
+    for (int i = 0; i < NK; ++i) kslot[i] = (j * NU + ((4 * i + qd) ^ (j & (NU - 1)))) * 16;   // row j, dims 32 i + 8 qd ..
+#pragma unroll
+    for (int s2 = 0; s2 < NS; ++s2) {                 // row 4 qd + j / 4, dims 16 s + 4 (j % 4) ..
+        const int rv = 4 * qd + (j >> 2);
+        vslot[s2] = VOFF + (rv * NU + ((2 * s2 + ((j & 3) >> 1)) ^ ((2 * rv) & (NU - 1)))) * 16 + (j & 1) * 8;
+    }
 
     bf16x8 kop[NK][2];                                // K rows: position (16 h +) j, dims 32 i + 8 qd ..
     bf16x8 vop[NS];                                   // V^T rows: dim 16 s + j, positions 4 qd .. of both halves
@@ -268,12 +337,23 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
         for (int i = 0; i < NK; ++i)
 #pragma unroll
             for (int h = 0; h < 2; ++h)
-                kop[i][h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + koff + i * (TILED ? 1024 : 64) + h * SUBB));
+                kop[i][h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(
+                    buf + (DMA && !TILED ? kslot[i] : koff + i * (TILED ? 1024 : 64)) + h * SUBB));
     };
     auto read_v = [&](const char *buf) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            if (TILED) {
+            if (DMA && !TILED) {
+                typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
+                const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + vslot[s]));
+                const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + vslot[s] + SUBB));
+                vop[s] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
+            } else if (DMA) {
+                // the two sub-tiles' units as they lie in the pool: dims 32 i + j in bytes 0..7, 32 i + 16 + j in 8..15
+                const char *at = buf + voff + (s >> 1) * 1024 + (s & 1) * 8;
+                const uint2 h0 = *reinterpret_cast<const uint2 *>(at), h1 = *reinterpret_cast<const uint2 *>(at + SUBB);
+                vop[s] = __builtin_bit_cast(bf16x8, make_uint4(h0.x, h0.y, h1.x, h1.y));
+            } else if (TILED) {
                 vop[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + voff + (s >> 1) * 1024 + (s & 1) * PLANE));
             } else {
                 typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
@@ -348,8 +428,38 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
     };
 
     lookup(0);
-    fetch(0);
-    if constexpr (NB == 2) {
+    if constexpr (!DMA) fetch(0);
+    if constexpr (DMA) {
+        // what is never loaded (sub-tiles past the workgroup's last position) reads as zero
+        for (int i = tid; i < NB * STAGE / 16; i += kThreads) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(0, 0, 0, 0);
+        __syncthreads();
+        dma(0, lds);
+        lookup(1);
+        dma(1, lds + STAGE);
+        lookup(2);
+        __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): both stages have landed
+        __syncthreads();
+        read_k(lds);
+        for (int st = 0; st < n_stages; ++st) {
+            char *cur = lds + (st & 1) * STAGE, *nxt = lds + ((st + 1) & 1) * STAGE;
+            if (st * kStage + kStage > C) {           // the context's last stage: uniform
+                zero_tail(st, cur);
+                __syncthreads();
+            }
+            const bool live = st * kStage <= wave_maxpos;   // wave-uniform: this wave's columns see the stage
+            if (live) {
+                read_v(cur);                          // needed after the barrier
+                scores();
+                softmax(st * kStage);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): stage st + 1, on its way since the last barrier
+            __syncthreads();                          // ... is in LDS for everyone; stage st's operands are in registers
+            dma(st + 2, cur);                         // in flight for a whole iteration (a third buffer and
+            lookup(st + 3);                           // two iterations were measured: slower)
+            if (st + 1 < n_stages) read_k(nxt);       // needed at the top of the next iteration
+            if (live) accumulate();
+        }
+    } else if constexpr (NB == 2) {
         stash(0, lds);
         lookup(1);
         fetch(1);
