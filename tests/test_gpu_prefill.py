@@ -133,3 +133,50 @@ def test_prefill_rejects_bad_host_arguments():
         rig.lamps.kv_append_tokens(0, 1, -1, x, x, x, x, x)
     assert e.value.status == -2
     rig.close()
+
+
+@pytest.mark.parametrize("H,Hkv,n_req,n_new,cached", [(40, 40, 2, 4096, 0), (32, 8, 2, 4096, 0), (32, 8, 4, 512, 4096),
+                                                      (32, 32, 8, 32, 1024)])
+def test_full_size_sampled_prefill(H, Hkv, n_req, n_new, cached):
+    """The sizes `bench.py --prefill` times (many tiles per request, hundreds of stages, the
+    launch order over the XCDs): append + attention on device-generated data, sampled rows of
+    the first and the last request against the oracle on the un-paged cache."""
+    D, bs = 128, 16
+    C = cached + n_new
+    per = (C + bs - 1) // bs
+    nb = n_req * per + 8
+    geom = W.Geometry(1, H, Hkv, D, bs, nb, per, "bf16")
+    rig = Rig(geom, n_req, poison=False)
+    dev = rig.dev
+    gen = torch.Generator(device=dev).manual_seed(W.config_seed(6) + H + n_new)
+    rig.k_pool.normal_(generator=gen)
+    rig.v_pool.normal_(generator=gen)
+    perm = W.permutation(W.config_seed(6) + 1, nb)
+    table, _ = W.deal_block_table(perm, [C] * n_req, geom)
+    td = torch.as_tensor(table, device=dev)
+    cd = torch.full((n_req,), C, dtype=torch.int32, device=dev)
+    sd = torch.arange(0, (n_req + 1) * n_new, n_new, dtype=torch.int32, device=dev)
+    total = n_req * n_new
+    q = torch.empty((total, H, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+    kn = torch.empty((total, Hkv, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+    vn = torch.empty((total, Hkv, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+    out = torch.full_like(q, 7.0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(rig.compute):
+        rig.lamps.kv_append_tokens(0, n_req, total, kn, vn, sd, td, cd)
+        rig.lamps.prefill_attn(0, n_req, total, q, sd, td, cd, out, max_new_tokens=n_new)
+    rig.compute.synchronize()
+    k_index, v_index = geom.tile_index_maps()
+    rows = sorted(set([0, 1, 31, 32, n_new // 3, n_new // 2 + 17, n_new - 2, n_new - 1]) & set(range(n_new)))
+    for r in (0, n_req - 1):
+        ids = torch.as_tensor(table[r, :per].astype(np.int64), device=dev)
+        K = W.tiles_to_logical(rig.k_pool[ids, 0].cpu().view(torch.int16).numpy().view(np.uint16), k_index, C)
+        V = W.tiles_to_logical(rig.v_pool[ids, 0].cpu().view(torch.int16).numpy().view(np.uint16), v_index, C)
+        # the appended rows are where the new keys and values were asked to go
+        np.testing.assert_array_equal(K[cached:], kn[r * n_new:(r + 1) * n_new].cpu().view(torch.int16).numpy().view(np.uint16))
+        np.testing.assert_array_equal(V[cached:], vn[r * n_new:(r + 1) * n_new].cpu().view(torch.int16).numpy().view(np.uint16))
+        qh = q[r * n_new:(r + 1) * n_new].cpu().view(torch.int16).numpy().view(np.uint16)
+        ref = oracle.decode_attn(qh[rows], [K] * len(rows), [V] * len(rows), [cached + i + 1 for i in rows], [1] * len(rows))
+        got = to_f64(out[r * n_new:(r + 1) * n_new])[rows]
+        np.testing.assert_allclose(got, ref, rtol=0, atol=tol(geom))
+    rig.close()
