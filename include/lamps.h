@@ -16,7 +16,10 @@
  * Conventions
  *   - Plain C ABI.  Every call returns a lamps_status (0 = ok, negative =
  *     error) unless stated otherwise.  On error nothing has been enqueued and
- *     no library state has changed; lamps_last_error() describes it.
+ *     no library state has changed; lamps_last_error() describes it.  The one
+ *     exception is LAMPS_ERR_HIP (the HIP runtime refused a call): work
+ *     enqueued before the refusal stays enqueued, and the call hands out no
+ *     ticket.
  *   - The CALLER owns all data memory: both KV pools, the workspace, q / out /
  *     block tables / context lengths / masks (device memory) and the swap
  *     buffers (pinned host memory), and both HIP streams.  The library owns

@@ -254,7 +254,7 @@ int ring_reserve(lamps_ctx *c, int32_t n, int32_t **where, size_t *slots)
     }
 }
 
-// Checks an id list: range, duplicates, and (if want_allocated) that every block is allocated.
+// Checks an id list: range, duplicates, and that every block is allocated.
 int check_ids(lamps_ctx *c, const int32_t *ids, int32_t n, const char *who)
 {
     if (n < 0) return fail(c, LAMPS_ERR_INVALID, std::string(who) + ": n is negative");
@@ -309,6 +309,67 @@ int wait_host_overlap(lamps_ctx *c, hipStream_t stream, const char *lo, const ch
     return LAMPS_OK;
 }
 
+// Last step of every swap call.  The ticket is filed whether or not the enqueue went through,
+// so that its events and ring slots come back when the stream has passed it; a failed call
+// hands no ticket to the caller and leaves the guards alone.
+int file_ticket(lamps_ctx *c, int enqueue_rc, hipStream_t st, Ticket &t, std::vector<uint64_t> &guard,
+                const int32_t *block_ids, int32_t n, uint64_t *ticket)
+{
+    const hipError_t e = hipEventRecord(t.ev, st);
+    c->tickets.push_back(t);
+    if (enqueue_rc != LAMPS_OK) return enqueue_rc;
+    if (e != hipSuccess) return hip_fail(c, "hipEventRecord", e);
+    const uint64_t id = c->base_ticket + c->tickets.size() - 1;
+    for (int32_t i = 0; i < n; ++i) guard[block_ids[i]] = id;
+    *ticket = id;
+    return LAMPS_OK;
+}
+
+// Enqueues the steps of a layer-major swap on `st`, one event per step into t->step_ev:
+// whole layers per step while a layer of the list fits the staging area (several when they
+// are small, so that a copy is at least about 8 MiB), else one layer in chunks of blocks.
+int enqueue_layer_steps(lamps_ctx *c, bool out, char *host, const int32_t *ids, int32_t n, hipStream_t st,
+                        Ticket *t)
+{
+    const int32_t L = c->cfg.num_layers;
+    const size_t layer_bytes = c->d.half_bytes / L;           // one block, one pool, one layer
+    const size_t unit = 2 * layer_bytes;                       // keys + values of one block, one layer
+    const size_t slice = (size_t)n * unit;                     // one layer of the whole list
+    const bool whole = slice <= c->d.staging_bytes && n <= 16384;   // 16384: the copy grid's y limit
+    char *stage = out ? c->stage_out : c->stage_in;
+    int32_t nl = 1;
+    if (whole) {
+        const size_t want = (size_t)8 << 20;
+        nl = (int32_t)std::min<size_t>({(size_t)L, c->d.staging_bytes / slice, (want + slice - 1) / slice});
+        if (nl < 1) nl = 1;
+    }
+    const int32_t bpc = whole ? n : (int32_t)std::min<size_t>({(size_t)n, c->d.staging_bytes / unit, (size_t)16384});
+    t->layers_per_step = nl;
+    for (int32_t l0 = 0; l0 < L; l0 += nl) {
+        const int32_t cnt_l = std::min<int32_t>(nl, L - l0);
+        for (int32_t done = 0; done < n; done += bpc) {
+            const int32_t cnt = std::min<int32_t>(bpc, n - done);
+            char *himg = host + (size_t)l0 * slice + (size_t)done * unit;
+            const size_t bytes = (size_t)cnt_l * cnt * unit;
+            if (out) {
+                LAMPS_HIP(lamps::launch_gather_layers(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                                      layer_bytes, l0, cnt_l, stage, st));
+                LAMPS_HIP(hipMemcpyAsync(himg, stage, bytes, hipMemcpyDeviceToHost, st));
+            } else {
+                LAMPS_HIP(hipMemcpyAsync(stage, himg, bytes, hipMemcpyHostToDevice, st));
+                LAMPS_HIP(lamps::launch_scatter_layers(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                                       layer_bytes, l0, cnt_l, stage, st));
+            }
+        }
+        hipEvent_t se;
+        const int rc = new_event(c, &se);
+        if (rc != LAMPS_OK) return rc;
+        t->step_ev.push_back(se);
+        LAMPS_HIP(hipEventRecord(se, st));
+    }
+    return LAMPS_OK;
+}
+
 // The layer-major swap, both directions.
 int swap_layered(lamps_ctx *c, bool out, char *host, const int32_t *block_ids, int32_t n, uint64_t *ticket,
                  const char *who)
@@ -323,73 +384,23 @@ int swap_layered(lamps_ctx *c, bool out, char *host, const int32_t *block_ids, i
     if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
     if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
     hipEvent_t ev;
-    if ((rc = new_event(c, &ev)) != LAMPS_OK) return rc;
+    if ((rc = new_event(c, &ev)) != LAMPS_OK) {
+        c->ring_head -= slots;                      // nothing reads the reserved slots yet
+        return rc;
+    }
 
     hipStream_t st = out ? c->os : c->is;
-    LAMPS_HIP(hipEventRecord(c->fence, c->cs));
-    LAMPS_HIP(hipStreamWaitEvent(st, c->fence, 0));
-    if ((rc = wait_guards(c, st, out ? c->in_guard : c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
     const size_t total = (size_t)n * c->d.block_bytes;
-    if ((rc = wait_host_overlap(c, st, host, host + total, !out)) != LAMPS_OK) return rc;
-
-    const int32_t L = c->cfg.num_layers;
-    const size_t layer_bytes = c->d.half_bytes / L;          // one block, one pool, one layer
-    const size_t slice = (size_t)n * 2 * layer_bytes;         // one layer of the whole list
-    char *stage = out ? c->stage_out : c->stage_in;
     Ticket t{ev, slots, host, host + total, out, {}, 0};
-    if (n > 0) {
-        // whole layers per step while a layer of the list fits the staging area, else one layer
-        // in chunks of blocks
-        int32_t nl = 1;
-        if (slice <= c->d.staging_bytes) {
-            const size_t want = (size_t)8 << 20;
-            nl = (int32_t)std::min<size_t>({(size_t)L, c->d.staging_bytes / slice, (want + slice - 1) / slice});
-            if (nl < 1) nl = 1;
-        }
-        int32_t bpc = (int32_t)std::min<size_t>({(size_t)n, c->d.staging_bytes / (2 * layer_bytes), (size_t)16384});
-        t.layers_per_step = nl;
-        for (int32_t l0 = 0; l0 < L; l0 += nl) {
-            const int32_t cnt_l = std::min<int32_t>(nl, L - l0);
-            char *himg = host + (size_t)l0 * slice;
-            if (slice <= c->d.staging_bytes) {
-                if (out) {
-                    LAMPS_HIP(lamps::launch_gather_layers(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, layer_bytes,
-                                                          l0, cnt_l, stage, st));
-                    LAMPS_HIP(hipMemcpyAsync(himg, stage, (size_t)cnt_l * slice, hipMemcpyDeviceToHost, st));
-                } else {
-                    LAMPS_HIP(hipMemcpyAsync(stage, himg, (size_t)cnt_l * slice, hipMemcpyHostToDevice, st));
-                    LAMPS_HIP(lamps::launch_scatter_layers(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, layer_bytes,
-                                                           l0, cnt_l, stage, st));
-                }
-            } else {
-                for (int32_t done = 0; done < n; done += bpc) {
-                    const int32_t cnt = std::min<int32_t>(bpc, n - done);
-                    char *hc = himg + (size_t)done * 2 * layer_bytes;
-                    const size_t bytes = (size_t)cnt * 2 * layer_bytes;
-                    if (out) {
-                        LAMPS_HIP(lamps::launch_gather_layers(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
-                                                              layer_bytes, l0, 1, stage, st));
-                        LAMPS_HIP(hipMemcpyAsync(hc, stage, bytes, hipMemcpyDeviceToHost, st));
-                    } else {
-                        LAMPS_HIP(hipMemcpyAsync(stage, hc, bytes, hipMemcpyHostToDevice, st));
-                        LAMPS_HIP(lamps::launch_scatter_layers(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
-                                                               layer_bytes, l0, 1, stage, st));
-                    }
-                }
-            }
-            hipEvent_t se;
-            if ((rc = new_event(c, &se)) != LAMPS_OK) return rc;
-            LAMPS_HIP(hipEventRecord(se, st));
-            t.step_ev.push_back(se);
-        }
-    }
-    LAMPS_HIP(hipEventRecord(ev, st));
-    c->tickets.push_back(t);
-    const uint64_t id = c->base_ticket + c->tickets.size() - 1;
-    std::vector<uint64_t> &guard = out ? c->out_guard : c->in_guard;
-    for (int32_t i = 0; i < n; ++i) guard[block_ids[i]] = id;
-    *ticket = id;
-    return LAMPS_OK;
+    auto enqueue = [&]() -> int {
+        LAMPS_HIP(hipEventRecord(c->fence, c->cs));
+        LAMPS_HIP(hipStreamWaitEvent(st, c->fence, 0));
+        int rc = wait_guards(c, st, out ? c->in_guard : c->out_guard, block_ids, n);
+        if (rc != LAMPS_OK) return rc;
+        if ((rc = wait_host_overlap(c, st, host, host + total, !out)) != LAMPS_OK) return rc;
+        return n > 0 ? enqueue_layer_steps(c, out, host, ids, n, st, &t) : LAMPS_OK;
+    };
+    return file_ticket(c, enqueue(), st, t, out ? c->out_guard : c->in_guard, block_ids, n, ticket);
 }
 
 }  // namespace
@@ -487,6 +498,7 @@ int lamps_destroy(lamps_ctx *c)
     while (!c->tickets.empty()) {
         if (hipEventSynchronize(c->tickets.front().ev) != hipSuccess) rc = LAMPS_ERR_HIP;
         (void)hipEventDestroy(c->tickets.front().ev);
+        for (hipEvent_t e : c->tickets.front().step_ev) (void)hipEventDestroy(e);
         c->tickets.pop_front();
     }
     for (hipEvent_t e : c->spare_events) (void)hipEventDestroy(e);
@@ -633,39 +645,43 @@ int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host
         if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
     }
     hipEvent_t ev;
-    if ((rc = new_event(c, &ev)) != LAMPS_OK) return rc;
+    if ((rc = new_event(c, &ev)) != LAMPS_OK) {
+        c->ring_head -= slots;                      // nothing reads the reserved slots yet
+        return rc;
+    }
 
-    // the copy reads what the compute stream (and any earlier swap-in) wrote
-    LAMPS_HIP(hipEventRecord(c->fence, c->cs));
-    LAMPS_HIP(hipStreamWaitEvent(c->os, c->fence, 0));
-    if ((rc = wait_guards(c, c->os, c->in_guard, block_ids, n)) != LAMPS_OK) return rc;
     char *host = static_cast<char *>(host_buf);
     const size_t total = (size_t)n * c->d.block_bytes;
-    if ((rc = wait_host_overlap(c, c->os, host, host + total, false)) != LAMPS_OK) return rc;
+    Ticket t{ev, slots, host, host + total, true, {}, 0};
+    auto enqueue = [&]() -> int {
+        // the copy reads what the compute stream (and any earlier swap-in) wrote
+        LAMPS_HIP(hipEventRecord(c->fence, c->cs));
+        LAMPS_HIP(hipStreamWaitEvent(c->os, c->fence, 0));
+        int rc = wait_guards(c, c->os, c->in_guard, block_ids, n);
+        if (rc != LAMPS_OK) return rc;
+        if ((rc = wait_host_overlap(c, c->os, host, host + total, false)) != LAMPS_OK) return rc;
 
-    if (c->d.direct_copy) {
-        // each block is two long contiguous runs: the copy engines take them as they are
-        for (int32_t i = 0; i < n; ++i) {
-            const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
-            LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes, c->k_pool + at, c->d.half_bytes,
-                                     hipMemcpyDeviceToHost, c->os));
-            LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes + c->d.half_bytes, c->v_pool + at,
-                                     c->d.half_bytes, hipMemcpyDeviceToHost, c->os));
+        if (c->d.direct_copy) {
+            // each block is two long contiguous runs: the copy engines take them as they are
+            for (int32_t i = 0; i < n; ++i) {
+                const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
+                LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes, c->k_pool + at, c->d.half_bytes,
+                                         hipMemcpyDeviceToHost, c->os));
+                LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes + c->d.half_bytes, c->v_pool + at,
+                                         c->d.half_bytes, hipMemcpyDeviceToHost, c->os));
+            }
+        } else {
+            for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
+                const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
+                LAMPS_HIP(lamps::launch_gather(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                               c->stage_out, c->os));
+                LAMPS_HIP(hipMemcpyAsync(host + (size_t)done * c->d.block_bytes, c->stage_out,
+                                         (size_t)cnt * c->d.block_bytes, hipMemcpyDeviceToHost, c->os));
+            }
         }
-    } else
-    for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
-        const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
-        LAMPS_HIP(lamps::launch_gather(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
-                                       c->stage_out, c->os));
-        LAMPS_HIP(hipMemcpyAsync(host + (size_t)done * c->d.block_bytes, c->stage_out,
-                                 (size_t)cnt * c->d.block_bytes, hipMemcpyDeviceToHost, c->os));
-    }
-    LAMPS_HIP(hipEventRecord(ev, c->os));
-    c->tickets.push_back(Ticket{ev, slots, host, host + total, true});
-    const uint64_t id = c->base_ticket + c->tickets.size() - 1;
-    for (int32_t i = 0; i < n; ++i) c->out_guard[block_ids[i]] = id;
-    *ticket = id;
-    return LAMPS_OK;
+        return LAMPS_OK;
+    };
+    return file_ticket(c, enqueue(), c->os, t, c->out_guard, block_ids, n, ticket);
 }
 
 int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, int32_t n,
@@ -685,39 +701,43 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
         if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
     }
     hipEvent_t ev;
-    if ((rc = new_event(c, &ev)) != LAMPS_OK) return rc;
+    if ((rc = new_event(c, &ev)) != LAMPS_OK) {
+        c->ring_head -= slots;                      // nothing reads the reserved slots yet
+        return rc;
+    }
 
-    // the scatter overwrites blocks: earlier compute-stream readers and an
-    // unfinished swap-out of the same blocks go first
-    LAMPS_HIP(hipEventRecord(c->fence, c->cs));
-    LAMPS_HIP(hipStreamWaitEvent(c->is, c->fence, 0));
-    if ((rc = wait_guards(c, c->is, c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
     const char *host = static_cast<const char *>(host_buf);
     const size_t total = (size_t)n * c->d.block_bytes;
-    if ((rc = wait_host_overlap(c, c->is, host, host + total, true)) != LAMPS_OK) return rc;
+    Ticket t{ev, slots, host, host + total, false, {}, 0};
+    auto enqueue = [&]() -> int {
+        // the scatter overwrites blocks: earlier compute-stream readers and an
+        // unfinished swap-out of the same blocks go first
+        LAMPS_HIP(hipEventRecord(c->fence, c->cs));
+        LAMPS_HIP(hipStreamWaitEvent(c->is, c->fence, 0));
+        int rc = wait_guards(c, c->is, c->out_guard, block_ids, n);
+        if (rc != LAMPS_OK) return rc;
+        if ((rc = wait_host_overlap(c, c->is, host, host + total, true)) != LAMPS_OK) return rc;
 
-    if (c->d.direct_copy) {
-        for (int32_t i = 0; i < n; ++i) {
-            const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
-            LAMPS_HIP(hipMemcpyAsync(c->k_pool + at, host + (size_t)i * c->d.block_bytes, c->d.half_bytes,
-                                     hipMemcpyHostToDevice, c->is));
-            LAMPS_HIP(hipMemcpyAsync(c->v_pool + at, host + (size_t)i * c->d.block_bytes + c->d.half_bytes,
-                                     c->d.half_bytes, hipMemcpyHostToDevice, c->is));
+        if (c->d.direct_copy) {
+            for (int32_t i = 0; i < n; ++i) {
+                const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
+                LAMPS_HIP(hipMemcpyAsync(c->k_pool + at, host + (size_t)i * c->d.block_bytes, c->d.half_bytes,
+                                         hipMemcpyHostToDevice, c->is));
+                LAMPS_HIP(hipMemcpyAsync(c->v_pool + at, host + (size_t)i * c->d.block_bytes + c->d.half_bytes,
+                                         c->d.half_bytes, hipMemcpyHostToDevice, c->is));
+            }
+        } else {
+            for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
+                const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
+                LAMPS_HIP(hipMemcpyAsync(c->stage_in, host + (size_t)done * c->d.block_bytes,
+                                         (size_t)cnt * c->d.block_bytes, hipMemcpyHostToDevice, c->is));
+                LAMPS_HIP(lamps::launch_scatter(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                                c->stage_in, c->is));
+            }
         }
-    } else
-    for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
-        const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
-        LAMPS_HIP(hipMemcpyAsync(c->stage_in, host + (size_t)done * c->d.block_bytes,
-                                 (size_t)cnt * c->d.block_bytes, hipMemcpyHostToDevice, c->is));
-        LAMPS_HIP(lamps::launch_scatter(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
-                                        c->stage_in, c->is));
-    }
-    LAMPS_HIP(hipEventRecord(ev, c->is));
-    c->tickets.push_back(Ticket{ev, slots, host, host + total, false});
-    const uint64_t id = c->base_ticket + c->tickets.size() - 1;
-    for (int32_t i = 0; i < n; ++i) c->in_guard[block_ids[i]] = id;
-    *ticket = id;
-    return LAMPS_OK;
+        return LAMPS_OK;
+    };
+    return file_ticket(c, enqueue(), c->is, t, c->in_guard, block_ids, n, ticket);
 }
 
 int lamps_swap_out_layered(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host_buf, uint64_t *ticket)
