@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--staging-mib", type=int, default=0, help="lamps_config.staging_bytes in MiB (0 = default)")
     ap.add_argument("--direct-copy-bytes", type=int, default=0,
                     help="lamps_config.direct_copy_bytes (0 = staged through the gather kernels, the default)")
+    ap.add_argument("--zero-copy", type=int, default=0, metavar="WORKGROUPS",
+                    help="lamps_config.zero_copy_workgroups (0 = off, the default)")
     ap.add_argument("--ctx-override", type=int, default=0,
                     help="diagnostic: give every request this context length")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -69,7 +71,7 @@ class Job:
     """Device-resident state of one benchmark workload."""
 
     def __init__(self, cfg_id, rotations, part_tokens, table_kind="random", ctx_override=0,
-                 geom_override="", direct_copy_bytes=0, staging_mib=0):
+                 geom_override="", direct_copy_bytes=0, staging_mib=0, zero_copy=0):
         import torch
 
         import lamps_workloads as W
@@ -106,7 +108,7 @@ class Job:
         self.cfg = P.LampsConfig(g.num_layers, g.num_q_heads, g.num_kv_heads, g.head_dim,
                                  g.block_size, g.num_blocks, g.max_blocks_per_req, wl.batch,
                                  P.LAMPS_BF16 if g.dtype == "bf16" else P.LAMPS_F32, 0.0,
-                                 part_tokens, staging_mib << 20, direct_copy_bytes)
+                                 part_tokens, staging_mib << 20, direct_copy_bytes, zero_copy)
         tdt = torch.bfloat16 if g.dtype == "bf16" else torch.float32
         seed = W.config_seed(cfg_id)
         gen = torch.Generator(device=dev).manual_seed(seed)
@@ -481,7 +483,8 @@ def main():
     if a.prefill:
         prefill_bench(a)
         return
-    job = Job(a.config, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom, a.direct_copy_bytes, a.staging_mib)
+    job = Job(a.config, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom, a.direct_copy_bytes, a.staging_mib,
+              a.zero_copy)
     with_swap = not a.no_swap
 
     # calibrate: one short train to size the run

@@ -101,6 +101,16 @@ typedef struct {
                                    kernel, no staging, nothing runs on the compute
                                    units.  0 or < 0 => never (the default: on this
                                    hardware the staged path is the faster one)       */
+    int32_t zero_copy_workgroups; /* > 0: lamps_swap_out / lamps_swap_in move the blocks
+                                   with ONE kernel of this many workgroups (at most
+                                   1024) that reads or writes the pinned host buffer
+                                   over the host link itself: no staging, no
+                                   hipMemcpyAsync.  The host buffer must then be
+                                   mapped into the device's address space
+                                   (hipHostMalloc memory is) and 16-byte aligned.
+                                   0 => off (the default); not together with
+                                   direct_copy_bytes.  The layer-major calls always
+                                   stage.                                            */
 } lamps_config;
 
 /* ---- sizes (pure functions of the config; return 0 on an invalid config) ---- */

@@ -93,7 +93,67 @@ hipError_t launch_layers(void *k_pool, void *v_pool, const int32_t *ids, int32_t
     return hipGetLastError();
 }
 
+// The same block-major image, but the image lives in pinned host memory that the device
+// reaches over the host link: `workgroups` workgroups walk all 16-byte units of the list,
+// four units in flight per thread (a read over the link takes microseconds).
+template <bool GATHER>
+__global__ __launch_bounds__(kCopyThreads) void block_copy_host(uint4 *k_pool, uint4 *v_pool,
+                                                                const int32_t *ids, size_t half_vecs,
+                                                                size_t total_vecs, uint4 *host)
+{
+    constexpr int kInFlight = 4;
+    const size_t stride = (size_t)gridDim.x * kCopyThreads;
+    for (size_t v0 = (size_t)blockIdx.x * kCopyThreads + threadIdx.x; v0 < total_vecs;
+         v0 += kInFlight * stride) {
+        uint4 r[kInFlight];
+        uint4 *dev[kInFlight];
+#pragma unroll
+        for (int k = 0; k < kInFlight; ++k) {
+            const size_t v = v0 + k * stride;
+            if (v >= total_vecs) continue;
+            const size_t pair = v / half_vecs, x = v - pair * half_vecs;
+            dev[k] = ((pair & 1) ? v_pool : k_pool) + (size_t)ids[pair >> 1] * half_vecs + x;
+            r[k] = GATHER ? *dev[k] : host[v];
+        }
+#pragma unroll
+        for (int k = 0; k < kInFlight; ++k) {
+            const size_t v = v0 + k * stride;
+            if (v >= total_vecs) continue;
+            if (GATHER)
+                host[v] = r[k];
+            else
+                *dev[k] = r[k];
+        }
+    }
+}
+
+template <bool GATHER>
+hipError_t launch_host(void *k_pool, void *v_pool, const int32_t *ids, int32_t n, size_t half_bytes,
+                       void *host, int32_t workgroups, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    if (n < 0 || workgroups < 1 || workgroups > 1024 || half_bytes % 16 != 0) return hipErrorInvalidValue;
+    const size_t half_vecs = half_bytes / 16;
+    hipLaunchKernelGGL(block_copy_host<GATHER>, dim3((unsigned)workgroups), dim3(kCopyThreads), 0, stream,
+                       static_cast<uint4 *>(k_pool), static_cast<uint4 *>(v_pool), ids, half_vecs,
+                       (size_t)n * 2 * half_vecs, static_cast<uint4 *>(host));
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_gather_host(const void *k_pool, const void *v_pool, const int32_t *ids, int32_t n,
+                              size_t half_bytes, void *host, int32_t workgroups, hipStream_t stream)
+{
+    return launch_host<true>(const_cast<void *>(k_pool), const_cast<void *>(v_pool), ids, n, half_bytes, host,
+                             workgroups, stream);
+}
+
+hipError_t launch_scatter_host(void *k_pool, void *v_pool, const int32_t *ids, int32_t n, size_t half_bytes,
+                               const void *host, int32_t workgroups, hipStream_t stream)
+{
+    return launch_host<false>(k_pool, v_pool, ids, n, half_bytes, const_cast<void *>(host), workgroups, stream);
+}
 
 hipError_t launch_gather_layers(const void *k_pool, const void *v_pool, const int32_t *ids, int32_t n,
                                 size_t half_bytes, size_t layer_bytes, int32_t layer0, int32_t nl,

@@ -74,6 +74,12 @@ hipError_t launch_gather(const void *k_pool, const void *v_pool, const int32_t *
                          size_t half_bytes, void *staging, hipStream_t stream);
 hipError_t launch_scatter(void *k_pool, void *v_pool, const int32_t *ids, int32_t n,
                           size_t half_bytes, const void *staging, hipStream_t stream);
+// The same image written to / read from `host` directly: pinned host memory at its device
+// address, 16-byte aligned.  `workgroups` (1..1024) bounds what the copy occupies of the chip.
+hipError_t launch_gather_host(const void *k_pool, const void *v_pool, const int32_t *ids, int32_t n,
+                              size_t half_bytes, void *host, int32_t workgroups, hipStream_t stream);
+hipError_t launch_scatter_host(void *k_pool, void *v_pool, const int32_t *ids, int32_t n, size_t half_bytes,
+                               const void *host, int32_t workgroups, hipStream_t stream);
 // The same for `nl` layers starting at `layer0` only; staging (and the host image of the
 // layer-major swap calls) is [layer - layer0][i][keys | values] with layer_bytes each.
 hipError_t launch_gather_layers(const void *k_pool, const void *v_pool, const int32_t *ids, int32_t n,

@@ -32,6 +32,7 @@ struct Derived {
     size_t partial_bytes = 0, prefix_bytes = 0, staging_bytes = 0, workspace_bytes = 0;
     int part_tokens = 0, max_parts = 0, log2_bs = 0, blocks_per_chunk = 0;
     bool direct_copy = false;           // blocks are large enough to be copied one by one, unstaged
+    int zero_copy = 0;                  // > 0: workgroups of the kernel that copies to / from host memory
     float scale_log2e = 0.f;
 };
 
@@ -85,6 +86,11 @@ const char *derive(const lamps_config *c, Derived *d)
     d->workspace_bytes = align256(d->partial_bytes) + align256(d->prefix_bytes) +
                          2 * align256(d->staging_bytes);
     d->direct_copy = c->direct_copy_bytes > 0 && (int64_t)d->half_bytes >= c->direct_copy_bytes;
+    if (c->zero_copy_workgroups < 0 || c->zero_copy_workgroups > 1024)
+        return "zero_copy_workgroups must be in [0, 1024]";
+    if (c->zero_copy_workgroups > 0 && c->direct_copy_bytes > 0)
+        return "zero_copy_workgroups and direct_copy_bytes exclude each other";
+    d->zero_copy = c->zero_copy_workgroups;
     const float scale = c->softmax_scale != 0.f ? c->softmax_scale : 1.0f / std::sqrt((float)c->head_dim);
     d->scale_log2e = scale * 1.4426950408889634f;
     return nullptr;
@@ -306,6 +312,29 @@ int wait_host_overlap(lamps_ctx *c, hipStream_t stream, const char *lo, const ch
         if (t.is_out == other_is_out && t.host_lo < hi && lo < t.host_hi &&
             hipEventQuery(t.ev) != hipSuccess)
             LAMPS_HIP(hipStreamWaitEvent(stream, t.ev, 0));
+    return LAMPS_OK;
+}
+
+// The device address of the pinned, mapped host range [host, host + bytes), for the copy
+// kernel that reaches it over the host link; anything else must not get near a kernel.
+int mapped_host(lamps_ctx *c, const void *host, size_t bytes, const char *who, void **dev)
+{
+    *dev = nullptr;
+    if (bytes == 0) return LAMPS_OK;
+    if ((uintptr_t)host & 15)
+        return fail(c, LAMPS_ERR_INVALID, std::string(who) + ": host_buf must be 16-byte aligned for the zero-copy path");
+    const char *ends[2] = {static_cast<const char *>(host), static_cast<const char *>(host) + bytes - 1};
+    for (int k = 0; k < 2; ++k) {
+        hipPointerAttribute_t at;
+        std::memset(&at, 0, sizeof at);
+        if (hipPointerGetAttributes(&at, ends[k]) != hipSuccess || at.type != hipMemoryTypeHost ||
+            at.devicePointer == nullptr) {
+            (void)hipGetLastError();
+            return fail(c, LAMPS_ERR_INVALID,
+                        std::string(who) + ": host_buf is not pinned host memory mapped into the device");
+        }
+        if (k == 0) *dev = at.devicePointer;
+    }
     return LAMPS_OK;
 }
 
@@ -636,6 +665,10 @@ int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host
         return fail(c, LAMPS_ERR_INVALID, "lamps_swap_out: null argument");
     int rc = check_ids(c, block_ids, n, "lamps_swap_out");
     if (rc != LAMPS_OK) return rc;
+    void *host_dev = nullptr;
+    if (c->d.zero_copy &&
+        (rc = mapped_host(c, host_buf, (size_t)n * c->d.block_bytes, "lamps_swap_out", &host_dev)) != LAMPS_OK)
+        return rc;
     if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
     retire_finished(c);
     int32_t *ids = nullptr;
@@ -670,6 +703,9 @@ int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host
                 LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes + c->d.half_bytes, c->v_pool + at,
                                          c->d.half_bytes, hipMemcpyDeviceToHost, c->os));
             }
+        } else if (c->d.zero_copy) {
+            LAMPS_HIP(lamps::launch_gather_host(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, host_dev,
+                                                c->d.zero_copy, c->os));
         } else {
             for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
                 const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
@@ -692,6 +728,10 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
         return fail(c, LAMPS_ERR_INVALID, "lamps_swap_in: null argument");
     int rc = check_ids(c, block_ids, n, "lamps_swap_in");
     if (rc != LAMPS_OK) return rc;
+    void *host_dev = nullptr;
+    if (c->d.zero_copy &&
+        (rc = mapped_host(c, host_buf, (size_t)n * c->d.block_bytes, "lamps_swap_in", &host_dev)) != LAMPS_OK)
+        return rc;
     if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
     retire_finished(c);
     int32_t *ids = nullptr;
@@ -726,6 +766,9 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
                 LAMPS_HIP(hipMemcpyAsync(c->v_pool + at, host + (size_t)i * c->d.block_bytes + c->d.half_bytes,
                                          c->d.half_bytes, hipMemcpyHostToDevice, c->is));
             }
+        } else if (c->d.zero_copy) {
+            LAMPS_HIP(lamps::launch_scatter_host(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, host_dev,
+                                                 c->d.zero_copy, c->is));
         } else {
             for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
                 const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);

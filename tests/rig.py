@@ -7,11 +7,12 @@ import lamps_workloads as W
 import paper_2410_18248_amd as P
 
 
-def make_config(geom, max_batch, part_tokens=0, staging_bytes=0, scale=0.0, direct_copy_bytes=0):
+def make_config(geom, max_batch, part_tokens=0, staging_bytes=0, scale=0.0, direct_copy_bytes=0,
+                zero_copy_workgroups=0):
     return P.LampsConfig(geom.num_layers, geom.num_q_heads, geom.num_kv_heads, geom.head_dim,
                          geom.block_size, geom.num_blocks, geom.max_blocks_per_req, max_batch,
                          P.LAMPS_BF16 if geom.dtype == "bf16" else P.LAMPS_F32, scale,
-                         part_tokens, staging_bytes, direct_copy_bytes)
+                         part_tokens, staging_bytes, direct_copy_bytes, zero_copy_workgroups)
 
 
 def t2n(t):
@@ -34,11 +35,12 @@ class Rig:
     """Pools, workspace, streams and a Lamps context for one geometry."""
 
     def __init__(self, geom, max_batch, part_tokens=0, staging_bytes=0, poison=True,
-                 side_streams=True, scale=0.0, direct_copy_bytes=0):
+                 side_streams=True, scale=0.0, direct_copy_bytes=0, zero_copy_workgroups=0):
         self.geom = geom
         self.dev = torch.device("cuda:0")
         self.tdtype = torch.bfloat16 if geom.dtype == "bf16" else torch.float32
-        self.cfg = make_config(geom, max_batch, part_tokens, staging_bytes, scale, direct_copy_bytes)
+        self.cfg = make_config(geom, max_batch, part_tokens, staging_bytes, scale, direct_copy_bytes,
+                               zero_copy_workgroups)
         assert P.lamps_pool_bytes(self.cfg) == int(np.prod(geom.pool_shape)) * geom.elem_bytes
         assert P.lamps_kv_layout(self.cfg) == (P.LAMPS_LAYOUT_TILED if geom.kv_layout == "tiled"
                                                else P.LAMPS_LAYOUT_PLAIN)

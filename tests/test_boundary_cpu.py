@@ -74,7 +74,8 @@ def test_kv_bytes_matches_paper_example():
 @pytest.mark.parametrize("bad", [
     dict(num_q_heads=7), dict(head_dim=96), dict(block_size=8), dict(block_size=24),
     dict(dtype=5), dict(num_blocks=0), dict(part_tokens=24), dict(staging_bytes=100),
-    dict(dtype=P.LAMPS_F32, head_dim=256)])
+    dict(dtype=P.LAMPS_F32, head_dim=256), dict(zero_copy_workgroups=-1), dict(zero_copy_workgroups=2000),
+    dict(zero_copy_workgroups=4, direct_copy_bytes=1)])
 def test_invalid_configs_are_rejected(bad):
     c = _cfg(**bad)
     assert P.lamps_block_bytes(c) == 0 and P.lamps_workspace_bytes(c) == 0

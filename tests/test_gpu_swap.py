@@ -34,14 +34,19 @@ def _pinned(n):
     return torch.empty(max(n, 1), dtype=torch.uint8).pin_memory()
 
 
-@pytest.mark.parametrize("direct", [-1, 1])      # staged through the gather kernels / plain copies per block
+# the three ways a block-major image moves: staged through the gather kernels, plain copies
+# per block, one kernel that reaches the pinned buffer itself
+PATHS = {"staged": {}, "direct": {"direct_copy_bytes": 1}, "zero-copy": {"zero_copy_workgroups": 3}}
+
+
+@pytest.mark.parametrize("path", list(PATHS))
 @pytest.mark.parametrize("dtype,L,Hkv,D,bs,staging_blocks", [
     ("f32", 1, 8, 64, 16, 0), ("bf16", 3, 2, 128, 16, 4), ("bf16", 2, 4, 128, 32, 1)])
-def test_swap_out_image_and_round_trip(dtype, L, Hkv, D, bs, staging_blocks, direct):
+def test_swap_out_image_and_round_trip(dtype, L, Hkv, D, bs, staging_blocks, path):
     geom = W.Geometry(L, Hkv, Hkv, D, bs, 48, 8, dtype)
     bb = 2 * geom.block_half_bytes
     rig = Rig(geom, max_batch=2, staging_bytes=staging_blocks * bb,     # small staging: several chunks
-              direct_copy_bytes=direct)
+              **PATHS[path])
     lam = rig.lamps
     assert P.lamps_block_bytes(rig.cfg) == bb
     _fill_random(rig, 11)
@@ -223,11 +228,11 @@ def test_compute_stream_writer_is_ordered_by_compute_wait_blocks():
     rig.close()
 
 
-@pytest.mark.parametrize("direct", [-1, 1])
-def test_swap_in_right_behind_swap_out_through_one_buffer(direct):
+@pytest.mark.parametrize("path", list(PATHS))
+def test_swap_in_right_behind_swap_out_through_one_buffer(path):
     geom = W.Geometry(4, 8, 8, 128, 16, 128, 8, "bf16")
     bb = 2 * geom.block_half_bytes
-    rig = Rig(geom, max_batch=1, direct_copy_bytes=direct)
+    rig = Rig(geom, max_batch=1, **PATHS[path])
     lam = rig.lamps
     _fill_random(rig, 31)
     model = _model(rig)
@@ -241,6 +246,28 @@ def test_swap_in_right_behind_swap_out_through_one_buffer(direct):
     model.swap_in(model.swap_out(src), dst)
     np.testing.assert_array_equal(_bytes(rig.k_pool).reshape(geom.num_blocks, -1), model.k)
     np.testing.assert_array_equal(_bytes(rig.v_pool).reshape(geom.num_blocks, -1), model.v)
+    rig.close()
+
+
+def test_zero_copy_refuses_memory_the_device_cannot_reach():
+    """The copy kernel of the zero-copy path dereferences the host buffer: pageable or
+    misaligned memory is turned down on the host, before anything is enqueued."""
+    geom = W.Geometry(1, 2, 2, 64, 16, 8, 4, "bf16")
+    bb = 2 * geom.block_half_bytes
+    rig = Rig(geom, max_batch=1, zero_copy_workgroups=2)
+    lam = rig.lamps
+    ids = lam.alloc_blocks(2)
+    pageable = np.zeros(2 * bb + 64, dtype=np.uint8)
+    for call in (lambda: lam.swap_out(ids, pageable), lambda: lam.swap_in(pageable, ids)):
+        with pytest.raises(P.LampsError) as e:
+            call()
+        assert e.value.status == -1
+    pinned = _pinned(2 * bb + 16)
+    with pytest.raises(P.LampsError) as e:
+        lam.swap_out(ids, pinned.data_ptr() + 4)
+    assert e.value.status == -1
+    t = lam.swap_out(ids, pinned)                   # and the context still works
+    lam.ticket_wait(t)
     rig.close()
 
 
