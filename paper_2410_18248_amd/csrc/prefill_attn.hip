@@ -62,10 +62,9 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
 // One workgroup = one (request, kv head, tile of new tokens); its four waves each
 // own kCols = 32 columns (kCols / G tokens x G heads) as blocks of 16.  K and V
 // are streamed 32 positions at a time through LDS: while stage s is consumed,
-// stage s + 1 arrives in the other of two LDS buffers (tiled layout: straight from
-// the pools; plain layout: all 256 threads load stage s + 2 into registers and
-// write stage s + 1 to LDS), one barrier per stage; one buffer and two barriers
-// where two do not fit.  Every wave reads each K / V operand from LDS
+// stage s + 1 arrives in the other of two LDS buffers, straight from the pools (loads
+// that write LDS directly: no registers, no LDS-write instructions), one barrier
+// per stage.  Every wave reads each K / V operand from LDS
 // once per stage and uses it for both column blocks.  Scores come out transposed
 // (lane: four consecutive positions of one column), which is the operand layout
 // the second product wants for the weights, so nothing is shuffled between the
@@ -85,16 +84,14 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
 // (they accumulate, like the outputs, in registers and need no cross-lane sum at
 // the end), and V reaches the second product without any shuffling in registers.
 //
-// LDS layouts of a stage.  Tiled pool layout: K and V tiles as they are, brought
-// in by loads that write LDS directly (no registers, no LDS-write instructions;
-// a K unit is an operand already, a V operand is the first or the second 8 bytes
-// of the same unit of the stage's two sub-tiles).  Where two stage buffers do not
-// fit (head_dim 256) the tiles go through registers, and V is regrouped on the
-// way into two planes (dims 32 i + j and 32 i + 16 + j) whose 16-byte units are
-// operands.  Plain layout: K and V row-major, K rows padded by 16 bytes (the 16
-// rows of an operand fall in different banks), V rows by 32; V^T operands come out
-// of the transposing LDS read of gfx950 (ds_read_b64_tr_b16: the 16 lanes of a
-// group read four rows of 16 dims, lane j receives dim j of the four rows).
+// LDS layouts of a stage: the pools' tiles as they are.  Tiled pool layout: a K unit
+// is an operand already, a V operand is the first or the second 8 bytes of the same
+// unit of the stage's two sub-tiles.  Plain layout: K and V row-major; rows cannot
+// be padded on the way in, so the 16-byte units of a row are permuted instead (unit
+// s of row r sits in slot s ^ r, or s ^ 2 r for V) and the rows an operand read
+// touches fall in different banks; V^T operands come out of the transposing LDS
+// read of gfx950 (ds_read_b64_tr_b16: the 16 lanes of a group read four rows of 16
+// dims, lane j receives dim j of the four rows).
 constexpr int kMaxCols = 32;             // columns per wave: two blocks of 16 keep a wave under 256 registers,
                                          // so two workgroups share a CU and cover each other's stalls
 constexpr int kStage = 32;               // cached positions per LDS stage
@@ -111,18 +108,14 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
     constexpr int NS = D / 16;                       // 16-dim slabs of the output
     constexpr int U = D * 2;                         // 16-byte units of one 16-position sub-tile
     constexpr int LPT = (2 * U) / kThreads;          // units per thread, pool and stage
-    // Up to head_dim 128 two stage buffers fit and the pool's tiles go to LDS as they are, by loads
-    // that write LDS directly (global_load_lds_dwordx4: lane l of a wave writes 16 bytes at
-    // base + 16 l, read from any address); above, one buffer, filled through registers.
-    constexpr bool DMA = D <= 128;
-    constexpr int NB = DMA ? 2 : 1;                  // stage buffers
+    // The pool's tiles go to LDS as they are, by loads that write LDS directly
+    // (global_load_lds_dwordx4: lane l of a wave writes 16 bytes at base + 16 l, read from any
+    // address); two stage buffers (64 KiB at head_dim 256).
+    constexpr int NB = 2;                            // stage buffers
     constexpr int NU = D / 8;                        // 16-byte units of one row (plain layout)
-    constexpr int ROWB = D * 2 + 16;                 // plain layout through registers: padded K row, bytes
-    constexpr int ROWV = D * 2 + 32;                 // ... padded V row
-    constexpr int SUBB = TILED || DMA ? 16 * D * 2 : 16 * ROWB;   // K sub-tile in LDS
-    constexpr int PLANE = U * 16;                    // tiled layout through registers: one V plane of a stage
+    constexpr int SUBB = 16 * D * 2;                 // one 16-position sub-tile of K or V
     constexpr int VOFF = 2 * SUBB;                   // V follows the two K sub-tiles
-    constexpr int STAGE = VOFF + (TILED || DMA ? 2 * PLANE : 32 * ROWV);
+    constexpr int STAGE = 4 * SUBB;
     static_assert(LPT >= 1 && (2 * U) % kThreads == 0, "head_dim");
     __shared__ __align__(16) char lds[NB * STAGE];
 
@@ -197,13 +190,6 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
     const char *kp = static_cast<const char *>(a.k_pool) + head_off;
     const char *vp = static_cast<const char *>(a.v_pool) + head_off;
 
-    // Unit k of this thread: 16-byte unit unit_of(k) of the stage's sub-tile sub_of(k).  Sixteen
-    // consecutive lanes take sixteen consecutive units of one sub-tile, the next sixteen the same
-    // units of the other sub-tile: global loads stay coalesced (256-byte runs) and the two halves
-    // of a V operand are written to LDS by neighbouring half-groups, into one contiguous run.
-    auto sub_of = [&](int k) { return ((tid + kThreads * k) >> 4) & 1; };
-    auto unit_of = [&](int k) { const int x = tid + kThreads * k; return (x & 15) | ((x >> 5) << 4); };
-
     // Block-table entries of a stage's two sub-tiles: wave-uniform, through the scalar unit, and
     // looked up one iteration before the loads that use them so that nobody waits for them.
     int e0, e1;
@@ -217,56 +203,10 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
         return t <= wg_maxpos ? (long long)((size_t)entry * block_stride + (size_t)((t & (a.block_size - 1)) >> 4) * (16 * D * 2))
                               : -1LL;
     };
-    // A stage -> registers.  Sub-tiles past the workgroup's last position are not loaded: the
-    // registers keep what they held (finite: zero at first, cache contents later), and every
-    // column's weight for those positions is zero.
-    uint4 kreg[LPT], vreg[LPT];
-#pragma unroll
-    for (int k = 0; k < LPT; ++k) kreg[k] = vreg[k] = make_uint4(0, 0, 0, 0);
-    auto fetch = [&](int st) {
-        const long long at0 = where(st * kStage, e0), at1 = where(st * kStage + 16, e1);
-#pragma unroll
-        for (int k = 0; k < LPT; ++k) {
-            const long long off = sub_of(k) ? at1 : at0;
-            if (off >= 0) {
-                kreg[k] = *reinterpret_cast<const uint4 *>(kp + off + unit_of(k) * 16);
-                vreg[k] = *reinterpret_cast<const uint4 *>(vp + off + unit_of(k) * 16);
-            }
-        }
-    };
-    // registers -> LDS buffer `buf`; value slots at or past the context's end are zeroed (they
-    // may hold anything, and a zero weight does not silence a NaN)
-    auto stash = [&](int st, char *buf) {
-        const bool tail = st * kStage + kStage > C;   // only the context's last stage has such slots
-#pragma unroll
-        for (int k = 0; k < LPT; ++k) {
-            const int u = sub_of(k), unit = unit_of(k);
-            const int t = st * kStage + 16 * u;
-            uint4 v = vreg[k];
-            if (TILED) {
-                if (tail) {
-                    const int valid = C - (t + 4 * ((unit >> 4) & 3));     // of the unit's four positions
-                    const uint32_t m01 = valid >= 2 ? 0xFFFFFFFFu : (valid == 1 ? 0x0000FFFFu : 0u);
-                    const uint32_t m23 = valid >= 4 ? 0xFFFFFFFFu : (valid == 3 ? 0x0000FFFFu : 0u);
-                    v.x &= m01; v.z &= m01;
-                    v.y &= m23; v.w &= m23;
-                }
-                *reinterpret_cast<uint4 *>(buf + u * SUBB + unit * 16) = kreg[k];
-                char *dst = buf + VOFF + unit * 16 + u * 8;
-                *reinterpret_cast<uint2 *>(dst) = make_uint2(v.x, v.y);
-                *reinterpret_cast<uint2 *>(dst + PLANE) = make_uint2(v.z, v.w);
-            } else {
-                const int row = unit / (D / 8), c16 = unit % (D / 8);     // position t + row, dims 8 c16 ..
-                if (tail && t + row >= C) v = make_uint4(0, 0, 0, 0);
-                *reinterpret_cast<uint4 *>(buf + u * SUBB + row * ROWB + c16 * 16) = kreg[k];
-                *reinterpret_cast<uint4 *>(buf + VOFF + (16 * u + row) * ROWV + c16 * 16) = v;
-            }
-        }
-    };
-
-    // Direct form: the stage's tiles from the pools straight into LDS buffer `buf`, each wave
-    // instruction one run of 64 units (1 KiB).  Nothing waits here: the caller waits for vmcnt
-    // before the barrier that publishes the stage.
+    // The stage's tiles from the pools straight into LDS buffer `buf`, each wave instruction one
+    // run of 64 units (1 KiB).  Sub-tiles past the workgroup's last position are not loaded (LDS is
+    // cleared once at the start, and every column's weight for those positions is zero).  Nothing
+    // waits here: the caller waits for vmcnt before the barrier that publishes the stage.
     auto dma = [&](int st, char *buf) {
         const long long at0 = where(st * kStage, e0), at1 = where(st * kStage + 16, e1);
 #pragma unroll
@@ -293,7 +233,8 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
             }
         }
     };
-    // The same zeroing of value slots at or past the context's end, for a stage already in LDS.
+    // Value slots at or past the context's end are zeroed once the stage is in LDS (they may hold
+    // anything, and a zero weight does not silence a NaN).
     auto zero_tail = [&](int st, char *buf) {
 #pragma unroll
         for (int k = 0; k < LPT; ++k) {
@@ -316,10 +257,9 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
         }
     };
 
-    // per-lane operand offsets in a stage buffer
-    const int koff = TILED ? qd * 256 + j * 16 : j * ROWB + qd * 16;   // + i * (TILED ? 1024 : 64), + SUBB for the second half
-    const int voff = VOFF + (TILED ? (qd * 16 + j) * 16                // + i * 1024, + PLANE for dims 16 + j
-                                   : (4 * qd + (j >> 2)) * ROWV + (j & 3) * 8);   // + s * 32, + 16 * ROWV for the second half
+    // per-lane operand offsets in a stage buffer, tiled layout
+    const int koff = qd * 256 + j * 16;               // + i * 1024, + SUBB for the second half
+    const int voff = VOFF + (qd * 16 + j) * 16;       // + (s / 2) * 1024 + (s % 2) * 8, + SUBB for the second half
     // plain layout, tiles as they are: the swizzled slots of this lane's operands
     int kslot[NK], vslot[NS];
 #pragma unroll
@@ -338,28 +278,21 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
 #pragma unroll
             for (int h = 0; h < 2; ++h)
                 kop[i][h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(
-                    buf + (DMA && !TILED ? kslot[i] : koff + i * (TILED ? 1024 : 64)) + h * SUBB));
+                    buf + (TILED ? koff + i * 1024 : kslot[i]) + h * SUBB));
     };
     auto read_v = [&](const char *buf) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            if (DMA && !TILED) {
+            if (!TILED) {                             // four rows of 16 dims, transposed on the way
                 typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
                 const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + vslot[s]));
                 const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + vslot[s] + SUBB));
                 vop[s] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
-            } else if (DMA) {
+            } else {
                 // the two sub-tiles' units as they lie in the pool: dims 32 i + j in bytes 0..7, 32 i + 16 + j in 8..15
                 const char *at = buf + voff + (s >> 1) * 1024 + (s & 1) * 8;
                 const uint2 h0 = *reinterpret_cast<const uint2 *>(at), h1 = *reinterpret_cast<const uint2 *>(at + SUBB);
                 vop[s] = __builtin_bit_cast(bf16x8, make_uint4(h0.x, h0.y, h1.x, h1.y));
-            } else if (TILED) {
-                vop[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(buf + voff + (s >> 1) * 1024 + (s & 1) * PLANE));
-            } else {
-                typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
-                const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + voff + s * 32));
-                const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + voff + s * 32 + 16 * ROWV));
-                vop[s] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
             }
         }
     };
@@ -428,74 +361,34 @@ __global__ __launch_bounds__(kThreads) void prefill_mfma(const PrefillArgs p, co
     };
 
     lookup(0);
-    if constexpr (!DMA) fetch(0);
-    if constexpr (DMA) {
-        // what is never loaded (sub-tiles past the workgroup's last position) reads as zero
-        for (int i = tid; i < NB * STAGE / 16; i += kThreads) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(0, 0, 0, 0);
-        __syncthreads();
-        dma(0, lds);
-        lookup(1);
-        dma(1, lds + STAGE);
-        lookup(2);
-        __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): both stages have landed
-        __syncthreads();
-        read_k(lds);
-        for (int st = 0; st < n_stages; ++st) {
-            char *cur = lds + (st & 1) * STAGE, *nxt = lds + ((st + 1) & 1) * STAGE;
-            if (st * kStage + kStage > C) {           // the context's last stage: uniform
-                zero_tail(st, cur);
-                __syncthreads();
-            }
-            const bool live = st * kStage <= wave_maxpos;   // wave-uniform: this wave's columns see the stage
-            if (live) {
-                read_v(cur);                          // needed after the barrier
-                scores();
-                softmax(st * kStage);
-            }
-            __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): stage st + 1, on its way since the last barrier
-            __syncthreads();                          // ... is in LDS for everyone; stage st's operands are in registers
-            dma(st + 2, cur);                         // in flight for a whole iteration (a third buffer and
-            lookup(st + 3);                           // two iterations were measured: slower)
-            if (st + 1 < n_stages) read_k(nxt);       // needed at the top of the next iteration
-            if (live) accumulate();
-        }
-    } else if constexpr (NB == 2) {
-        stash(0, lds);
-        lookup(1);
-        fetch(1);
-        lookup(2);
-        __syncthreads();
-        read_k(lds);
-        for (int st = 0; st < n_stages; ++st) {
-            char *cur = lds + (st & 1) * STAGE, *nxt = lds + ((st + 1) & 1) * STAGE;
-            const bool live = st * kStage <= wave_maxpos;   // wave-uniform: this wave's columns see the stage
-            if (live) {
-                read_v(cur);                          // needed after the barrier
-                scores();
-            }
-            if (st + 1 < n_stages) stash(st + 1, nxt);    // nobody reads that buffer now
-            fetch(st + 2);                            // in flight for a whole iteration
-            lookup(st + 3);
-            if (live) softmax(st * kStage);
-            __syncthreads();                          // stage st + 1 is in LDS, stage st's operands are in registers
-            if (st + 1 < n_stages) read_k(nxt);       // needed at the top of the next iteration
-            if (live) accumulate();
-        }
-    } else {
-        for (int st = 0; st < n_stages; ++st) {
-            __syncthreads();                          // everyone is done with the previous stage
-            stash(st, lds);
+    // what is never loaded (sub-tiles past the workgroup's last position) reads as zero
+    for (int i = tid; i < NB * STAGE / 16; i += kThreads) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+    dma(0, lds);
+    lookup(1);
+    dma(1, lds + STAGE);
+    lookup(2);
+    __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): both stages have landed
+    __syncthreads();
+    read_k(lds);
+    for (int st = 0; st < n_stages; ++st) {
+        char *cur = lds + (st & 1) * STAGE, *nxt = lds + ((st + 1) & 1) * STAGE;
+        if (st * kStage + kStage > C) {               // the context's last stage: uniform
+            zero_tail(st, cur);
             __syncthreads();
-            lookup(st + 1);
-            fetch(st + 1);
-            if (st * kStage <= wave_maxpos) {
-                read_k(lds);
-                read_v(lds);
-                scores();
-                softmax(st * kStage);
-                accumulate();
-            }
         }
+        const bool live = st * kStage <= wave_maxpos;   // wave-uniform: this wave's columns see the stage
+        if (live) {
+            read_v(cur);                              // needed after the barrier
+            scores();
+            softmax(st * kStage);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): stage st + 1, on its way since the last barrier
+        __syncthreads();                              // ... is in LDS for everyone; stage st's operands are in registers
+        dma(st + 2, cur);                             // in flight for a whole iteration (a third buffer and
+        lookup(st + 3);                               // two iterations were measured: slower)
+        if (st + 1 < n_stages) read_k(nxt);           // needed at the top of the next iteration
+        if (live) accumulate();
     }
 
 #pragma unroll
