@@ -30,6 +30,12 @@
  *   - Arguments that live in device memory (block_table, ctx_lens,
  *     running_mask) are NOT validated: no call synchronises with the device.
  *   - A context is not thread-safe; calls on it must be serialised.
+ *   - lamps_decode_attn, lamps_kv_append, lamps_kv_append_tokens and
+ *     lamps_prefill_attn enqueue kernels on the compute stream and nothing else
+ *     (no memset, no copy, no allocation, no host wait): once each has run
+ *     eagerly on the device, a caller may record them into a HIP graph by stream
+ *     capture and replay a whole decode iteration.  The swap calls use events
+ *     and copies on the side streams and are not meant for capture.
  *
  * KV pool layout (part of the ABI, so swap images can be checked byte by byte)
  *   Keys and values live in two pools of identical size
