@@ -401,7 +401,6 @@ def prefill_bench(a):
     vn = torch.empty((total, Hkv, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
     out = torch.empty_like(q)
     steps = a.steps if a.steps > 0 else 20
-    warmup = a.warmup if a.warmup >= 0 else 3
 
     def run(k, append):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -415,6 +414,10 @@ def prefill_bench(a):
         e1.record(cs)
         torch.cuda.synchronize()
         return time.perf_counter() - t0, e0.elapsed_time(e1) * 1e-3
+    # the kernel gets faster over its first 20-30 ms after an idle period (clocks ramp up):
+    # warm up for about 40 ms unless told otherwise
+    _, probe = run(3, True)
+    warmup = a.warmup if a.warmup >= 0 else max(3, int(0.04 / (probe / 3)))
     run(warmup, True)
     wall, dev_s = run(steps, True)
     _, attn_s = run(steps, False)
