@@ -64,7 +64,8 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
 // are streamed 32 positions at a time through LDS: while stage s is consumed,
 // stage s + 1 arrives in the other of two LDS buffers, straight from the pools (loads
 // that write LDS directly: no registers, no LDS-write instructions), one barrier
-// per stage.  Every wave reads each K / V operand from LDS
+// per stage -- or per two stages, loaded and published together, when a request has
+// several tiles of new tokens and two such groups fit the 64 KiB of a workgroup.  Every wave reads each K / V operand from LDS
 // once per stage and uses it for both column blocks.  Scores come out transposed
 // (lane: four consecutive positions of one column), which is the operand layout
 // the second product wants for the weights, so nothing is shuffled between the
@@ -100,7 +101,7 @@ constexpr float kSlack = 8.0f;           // log2 of the largest weight before th
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((address_space(4))) const int32_t *table_ptr;   // read-only: scalar loads
 
-template <int D, bool TILED, int kCols>
+template <int D, bool TILED, int kCols, int GRP>
 __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void prefill_mfma(const PrefillArgs p, const int tiles)
 {
     constexpr int kColBlocks = kCols / 16;
@@ -116,8 +117,12 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
     constexpr int SUBB = 16 * D * 2;                 // one 16-position sub-tile of K or V
     constexpr int VOFF = 2 * SUBB;                   // V follows the two K sub-tiles
     constexpr int STAGE = 4 * SUBB;
+    // Stages are loaded, and published by a barrier, GRP at a time: with two, half as many
+    // barriers and waits for loads, and a group's loads have twice as long to arrive.
+    constexpr int GSTAGE = GRP * STAGE;
+    static_assert(NB * GSTAGE <= 65536, "LDS of one workgroup");
     static_assert(LPT >= 1 && (2 * U) % kThreads == 0, "head_dim");
-    __shared__ __align__(16) char lds[NB * STAGE];
+    __shared__ __align__(16) char lds[NB * GSTAGE];
 
     const DecodeArgs &a = p.d;
     // All tiles of one (request, kv head) run on one XCD (workgroups are dealt to the 8 XCDs
@@ -192,10 +197,10 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
 
     // Block-table entries of a stage's two sub-tiles: wave-uniform, through the scalar unit, and
     // looked up one iteration before the loads that use them so that nobody waits for them.
-    int e0, e1;
-    auto lookup = [&](int st) {
-        e0 = table[min(st * kStage, wg_maxpos) >> a.log2_block_size];
-        e1 = table[min(st * kStage + 16, wg_maxpos) >> a.log2_block_size];
+    int ent[2 * GRP];
+    auto lookup = [&](int grp) {
+#pragma unroll
+        for (int i = 0; i < 2 * GRP; ++i) ent[i] = table[min(grp * GRP * kStage + 16 * i, wg_maxpos) >> a.log2_block_size];
     };
     // Byte offset (from kp / vp) of the sub-tile that starts at position t in block `entry`;
     // -1 past the workgroup's last position.
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
     // run of 64 units (1 KiB).  Sub-tiles past the workgroup's last position are not loaded (LDS is
     // cleared once at the start, and every column's weight for those positions is zero).  Nothing
     // waits here: the caller waits for vmcnt before the barrier that publishes the stage.
-    auto dma = [&](int st, char *buf) {
+    auto dma = [&](int st, char *buf, int e0, int e1) {
         const long long at0 = where(st * kStage, e0), at1 = where(st * kStage + 16, e1);
 #pragma unroll
         for (int k = 0; k < LPT; ++k) {
@@ -281,18 +286,21 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
                     buf + (TILED ? koff + i * 1024 : kslot[i]) + h * SUBB));
     };
     auto read_v = [&](const char *buf) {
+        if constexpr (TILED) {
+            // the two sub-tiles' units as they lie in the pool: dims 32 i + j in bytes 0..7, 32 i + 16 + j in 8..15
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            if (!TILED) {                             // four rows of 16 dims, transposed on the way
+            for (int s = 0; s < NS; ++s) {
+                const char *at = buf + voff + (s >> 1) * 1024 + (s & 1) * 8;
+                const uint2 h0 = *reinterpret_cast<const uint2 *>(at), h1 = *reinterpret_cast<const uint2 *>(at + SUBB);
+                vop[s] = __builtin_bit_cast(bf16x8, make_uint4(h0.x, h0.y, h1.x, h1.y));
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {            // four rows of 16 dims, transposed on the way
                 typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
                 const s16x4 h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + vslot[s]));
                 const s16x4 h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(buf + vslot[s] + SUBB));
                 vop[s] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
-            } else {
-                // the two sub-tiles' units as they lie in the pool: dims 32 i + j in bytes 0..7, 32 i + 16 + j in 8..15
-                const char *at = buf + voff + (s >> 1) * 1024 + (s & 1) * 8;
-                const uint2 h0 = *reinterpret_cast<const uint2 *>(at), h1 = *reinterpret_cast<const uint2 *>(at + SUBB);
-                vop[s] = __builtin_bit_cast(bf16x8, make_uint4(h0.x, h0.y, h1.x, h1.y));
             }
         }
     };
@@ -360,41 +368,55 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
             for (int b = 0; b < kColBlocks; ++b) o[b][s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[s], pw[b], o[b][s], 0, 0, 0);
     };
 
+    auto dma_group = [&](int grp, char *buf) {
+#pragma unroll
+        for (int h = 0; h < GRP; ++h) dma(grp * GRP + h, buf + h * STAGE, ent[2 * h], ent[2 * h + 1]);
+    };
     lookup(0);
     // what is never loaded (sub-tiles past the workgroup's last position) reads as zero
-    for (int i = tid; i < NB * STAGE / 16; i += kThreads) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(0, 0, 0, 0);
+    for (int i = tid; i < NB * GSTAGE / 16; i += kThreads) reinterpret_cast<uint4 *>(lds)[i] = make_uint4(0, 0, 0, 0);
     __syncthreads();
-    dma(0, lds);
+    dma_group(0, lds);
     lookup(1);
-    dma(1, lds + STAGE);
+    dma_group(1, lds + GSTAGE);
     lookup(2);
-    __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): both stages have landed
+    __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): both groups have landed
     __syncthreads();
     // At head_dim 256 the K and V operands of a stage are 64 registers each.  With 16 columns per
     // wave they are read one after the other, K right before the scores and V behind them: the
     // wave then stays under 256 registers and two workgroups share a CU here as well.
     constexpr bool kLean = D >= 256 && kCols <= 16;
     if (!kLean) read_k(lds);
-    for (int st = 0; st < n_stages; ++st) {
-        char *cur = lds + (st & 1) * STAGE, *nxt = lds + ((st + 1) & 1) * STAGE;
-        if (st * kStage + kStage > C) {               // the context's last stage: uniform
-            zero_tail(st, cur);
+    const int n_groups = (n_stages + GRP - 1) / GRP;
+    for (int grp = 0; grp < n_groups; ++grp) {
+        char *cur = lds + (grp & 1) * GSTAGE, *nxt = lds + ((grp + 1) & 1) * GSTAGE;
+        if ((grp + 1) * GRP * kStage > C) {           // the group holds the context's last stage: uniform
+#pragma unroll
+            for (int h = 0; h < GRP; ++h)
+                if ((grp * GRP + h) * kStage + kStage > C) zero_tail(grp * GRP + h, cur + h * STAGE);
             __syncthreads();
         }
-        const bool live = st * kStage <= wave_maxpos;   // wave-uniform: this wave's columns see the stage
-        if (live) {
-            if (kLean) read_k(cur);
-            else read_v(cur);                         // needed after the barrier
-            scores();
-            if (kLean) read_v(cur);
-            softmax(st * kStage);
+#pragma unroll
+        for (int h = 0; h < GRP; ++h) {
+            const int st = grp * GRP + h;
+            char *at = cur + h * STAGE;
+            const bool live = st * kStage <= wave_maxpos;   // wave-uniform: this wave's columns see the stage
+            if (live) {
+                if (kLean) read_k(at);
+                else read_v(at);                      // needed after the next K operands are asked for
+                scores();
+                if (kLean) read_v(at);
+                softmax(st * kStage);
+            }
+            if (h == GRP - 1) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): group grp + 1, on its way since the last barrier
+                __syncthreads();                      // ... is in LDS for everyone; this group's operands are in registers
+                dma_group(grp + 2, cur);              // in flight until the next barrier (a third buffer and
+                lookup(grp + 3);                      // loads two barriers ahead were measured: slower)
+            }
+            if (!kLean && st + 1 < n_stages) read_k(h == GRP - 1 ? nxt : at + STAGE);   // needed at the top of the next stage
+            if (live) accumulate();
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): stage st + 1, on its way since the last barrier
-        __syncthreads();                              // ... is in LDS for everyone; stage st's operands are in registers
-        dma(st + 2, cur);                             // in flight for a whole iteration (a third buffer and
-        lookup(st + 3);                               // two iterations were measured: slower)
-        if (!kLean && st + 1 < n_stages) read_k(nxt); // needed at the top of the next iteration
-        if (live) accumulate();
     }
 
 #pragma unroll
@@ -421,7 +443,14 @@ hipError_t launch_mfma_prefill(const PrefillArgs &p, hipStream_t s)
     const long long tiles = (p.max_new_tokens + WT - 1) / WT;
     const long long pairs8 = ((long long)p.d.num_kv_heads * p.d.batch + 7) / 8 * 8;
     if (tiles < 1 || tiles * pairs8 > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((prefill_mfma<D, TILED, kCols>), dim3((unsigned)(tiles * pairs8)), dim3(kThreads), 0, s, p, (int)tiles);
+    // Two stages per barrier where they fit and a request has many new tokens (the matrix cores
+    // bind: +2-5 %); with one tile per request the kernel is a stream over the cache, and the
+    // finer grain is the faster one (+3 %).
+    constexpr bool kFits = 2 * 2 * (4 * 16 * D * 2) <= 65536;
+    if (kFits && tiles > 1)
+        hipLaunchKernelGGL((prefill_mfma<D, TILED, kCols, kFits ? 2 : 1>), dim3((unsigned)(tiles * pairs8)), dim3(kThreads), 0, s, p, (int)tiles);
+    else
+        hipLaunchKernelGGL((prefill_mfma<D, TILED, kCols, 1>), dim3((unsigned)(tiles * pairs8)), dim3(kThreads), 0, s, p, (int)tiles);
     return hipGetLastError();
 }
 
