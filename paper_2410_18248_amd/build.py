@@ -19,7 +19,9 @@ SOURCES = ["decode_attn.hip", "block_copy.hip", "kv_append.hip", "prefill_attn.h
 # no fused multiply-adds in its host code
 PER_SOURCE = {"sched.cpp": ["-ffp-contract=off"],
               # the prefill kernel rescales its MFMA accumulators on the vector ALUs now and then;
-              # with the accumulators in ordinary vector registers that needs no register moves
+              # with the accumulators in ordinary vector registers that needs no register moves, and
+              # mfma_f32_16x16x32_bf16 issues every 16 cycles instead of every 30-47 (measured); the
+              # HBM-bound decode kernels are 2-4 % slower that way (registers) and keep the default
               "prefill_attn.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
