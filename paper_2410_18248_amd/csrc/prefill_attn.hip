@@ -189,52 +189,56 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
     const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
 
     const table_ptr table = (table_ptr)(uintptr_t)(a.block_table + (size_t)r * a.max_blocks);
-    const size_t tile_bytes = (size_t)a.block_size * D * 2;
-    const size_t block_stride = (size_t)a.num_layers * a.num_kv_heads * tile_bytes;
+    const uint32_t tile_bytes = (uint32_t)a.block_size * D * 2;
+    // bytes from one block to the next; the launcher has checked that they fit 32 bits
+    const uint32_t block_stride = (uint32_t)a.num_layers * a.num_kv_heads * tile_bytes;
     const size_t head_off = ((size_t)a.layer * a.num_kv_heads + g) * tile_bytes;
     const char *kp = static_cast<const char *>(a.k_pool) + head_off;
     const char *vp = static_cast<const char *>(a.v_pool) + head_off;
 
-    // Block-table entries of a stage's two sub-tiles: wave-uniform, through the scalar unit, and
+    // Block-table entries of a group's sub-tiles: wave-uniform, through the scalar unit, and
     // looked up one iteration before the loads that use them so that nobody waits for them.
-    int ent[2 * GRP];
+    uint32_t ent[2 * GRP];
     auto lookup = [&](int grp) {
 #pragma unroll
-        for (int i = 0; i < 2 * GRP; ++i) ent[i] = table[min(grp * GRP * kStage + 16 * i, wg_maxpos) >> a.log2_block_size];
+        for (int i = 0; i < 2 * GRP; ++i)
+            ent[i] = (uint32_t)table[min(grp * GRP * kStage + 16 * i, wg_maxpos) >> a.log2_block_size];
     };
-    // Byte offset (from kp / vp) of the sub-tile that starts at position t in block `entry`;
-    // -1 past the workgroup's last position.
-    auto where = [&](int t, int entry) {
-        return t <= wg_maxpos ? (long long)((size_t)entry * block_stride + (size_t)((t & (a.block_size - 1)) >> 4) * (16 * D * 2))
-                              : -1LL;
-    };
+    // This lane's part of a load's address: unit x of a sub-tile as it lies in the pool goes to
+    // LDS slot x (tiled layout), or, plain layout (rows of NU units, which cannot be padded on the
+    // way in), slot s of row r takes unit s ^ (r mod NU) of a K row and s ^ (2 r mod NU) of a V
+    // row, so that the rows an operand read touches fall in different banks.
+    uint32_t lane_k[LPT], lane_v[LPT];
+#pragma unroll
+    for (int k = 0; k < LPT; ++k) {
+        const int x = (kThreads * k + 64 * wv) % U + lane;   // the lane's LDS slot within the sub-tile
+        const int row = x / NU, sl = x % NU;
+        lane_k[k] = (uint32_t)(TILED ? x : row * NU + (sl ^ (row & (NU - 1)))) * 16;
+        lane_v[k] = (uint32_t)(TILED ? x : row * NU + (sl ^ ((2 * row) & (NU - 1)))) * 16;
+    }
     // The stage's tiles from the pools straight into LDS buffer `buf`, each wave instruction one
     // run of 64 units (1 KiB).  Sub-tiles past the workgroup's last position are not loaded (LDS is
     // cleared once at the start, and every column's weight for those positions is zero).  Nothing
     // waits here: the caller waits for vmcnt before the barrier that publishes the stage.
-    auto dma = [&](int st, char *buf, int e0, int e1) {
-        const long long at0 = where(st * kStage, e0), at1 = where(st * kStage + 16, e1);
+    // The address is a scalar base (pool + block + sub-tile, all on the scalar unit, 32 x 32 -> 64
+    // bit) plus the lane's constant 32-bit offset: no vector arithmetic per load.
+    auto dma = [&](int st, char *buf, uint32_t e0, uint32_t e1) {
 #pragma unroll
         for (int k = 0; k < LPT; ++k) {
             const int x0 = kThreads * k + 64 * wv;    // the wave's first unit: sub-tile x0 / U, unit x0 % U
-            const long long off = x0 / U ? at1 : at0;
-            if (off >= 0) {
+            const int t = st * kStage + 16 * (x0 / U);
+            if (t <= wg_maxpos) {
+                const uint64_t off = (uint64_t)(x0 / U ? e1 : e0) * block_stride +
+                                     (uint32_t)(((t & (a.block_size - 1)) >> 4) * (16 * D * 2));
                 // (written as assembly: the compiler would make every later LDS read wait for these loads;
                 // m0, the LDS base of such a load, is a register the compiler reserves and sets itself
                 // before any instruction of its own that reads it)
                 typedef __attribute__((address_space(3))) char *lptr;
-                const int x = x0 % U + lane;          // the lane's LDS slot within the sub-tile
-                // Tiled layout: slot x holds unit x.  Plain layout (rows of NU units, which cannot be
-                // padded here): slot s of row r holds unit s ^ (r mod NU) of a K row and s ^ (2 r mod NU)
-                // of a V row, so that the rows an operand read touches fall in different banks.
-                const int row = x / NU, sl = x % NU;
-                const int xk = TILED ? x : row * NU + (sl ^ (row & (NU - 1)));
-                const int xv = TILED ? x : row * NU + (sl ^ ((2 * row) & (NU - 1)));
                 const uint32_t lk = (uint32_t)(uintptr_t)(lptr)(buf + x0 * 16), lv = lk + VOFF;
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lk),
-                             "v"(kp + (size_t)off + (size_t)xk * 16) : "memory");
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lv),
-                             "v"(vp + (size_t)off + (size_t)xv * 16) : "memory");
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lk), "v"(lane_k[k]),
+                             "s"(kp + off) : "memory");
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lv), "v"(lane_v[k]),
+                             "s"(vp + off) : "memory");
             }
         }
     };
@@ -489,7 +493,9 @@ hipError_t launch_prefill(const PrefillArgs &p, hipStream_t stream)
     if (a.heads_per_pass != decode_heads_per_pass(a.bf16, a.head_dim, G) || a.heads_per_pass == 0)
         return hipErrorInvalidValue;
     const int lpt = a.head_dim * (a.bf16 ? 2 : 4) / 16;
-    if (a.bf16 && G <= kMaxCols && !p.force_rows) {     // matrix cores
+    // (the matrix-core kernel keeps the distance between two blocks of a pool in 32 bits)
+    const unsigned long long stride = 2ull * a.num_layers * a.num_kv_heads * a.block_size * a.head_dim;
+    if (a.bf16 && G <= kMaxCols && !p.force_rows && stride <= 0xffffffffull) {     // matrix cores
         const bool tiled = decode_uses_tiled_layout(a.bf16, G);
         if (a.head_dim == 64) return tiled ? launch_mfma_prefill<64, true>(p, stream) : launch_mfma_prefill<64, false>(p, stream);
         if (a.head_dim == 128) return tiled ? launch_mfma_prefill<128, true>(p, stream) : launch_mfma_prefill<128, false>(p, stream);
