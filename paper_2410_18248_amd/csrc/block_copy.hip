@@ -18,6 +18,16 @@ namespace {
 
 constexpr int kCopyThreads = 256;
 
+// Every byte is touched once: non-temporal loads and stores keep the copy from displacing what
+// the decode kernels stream through the caches next to it (decode under swap 1.046x -> 1.041x
+// of decode alone).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void copy16(uint4 *dst, const uint4 *src)
+{
+    __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src)),
+                                reinterpret_cast<u32x4 *>(dst));
+}
+
 template <bool GATHER>
 __global__ __launch_bounds__(kCopyThreads) void block_copy(uint4 *k_pool, uint4 *v_pool,
                                                            const int32_t *ids, size_t half_vecs,
@@ -30,9 +40,9 @@ __global__ __launch_bounds__(kCopyThreads) void block_copy(uint4 *k_pool, uint4 
     for (size_t x = (size_t)blockIdx.x * kCopyThreads + threadIdx.x; x < half_vecs;
          x += (size_t)gridDim.x * kCopyThreads) {
         if (GATHER)
-            img[x] = pool[x];
+            copy16(&img[x], &pool[x]);
         else
-            pool[x] = img[x];
+            copy16(&pool[x], &img[x]);
     }
 }
 
@@ -68,9 +78,9 @@ __global__ __launch_bounds__(kCopyThreads) void block_copy_layers(uint4 *k_pool,
     for (size_t x = (size_t)blockIdx.x * kCopyThreads + threadIdx.x; x < layer_vecs;
          x += (size_t)gridDim.x * kCopyThreads) {
         if (GATHER)
-            img[x] = pool[x];
+            copy16(&img[x], &pool[x]);
         else
-            pool[x] = img[x];
+            copy16(&pool[x], &img[x]);
     }
 }
 
