@@ -44,6 +44,28 @@ class RandomSource:
         return x[:, :self.H], x[:, self.H:self.H + self.Hkv], x[:, self.H + self.Hkv:]
 
 
+class DeviceSource:
+    """The same contract as RandomSource -- a pure function of (seed, rid, pos, layer) -- but made
+    on the device by integer hashing (uniform, zero mean, unit variance), so that a serving run is
+    not dominated by the host making its inputs."""
+
+    def __init__(self, seed, num_q_heads, num_kv_heads, head_dim, dtype, device="cuda:0"):
+        self.seed, self.H, self.Hkv, self.D, self.dtype = seed, num_q_heads, num_kv_heads, head_dim, dtype
+        self.dev = torch.device(device)
+        self.idx = torch.arange((num_q_heads + 2 * num_kv_heads) * head_dim, dtype=torch.int64, device=self.dev)
+
+    def rows(self, rid, first_pos, count, layer):
+        key = ((((self.seed * 1000003 + rid) * 8191 + layer) * 1048573) & 0x3FFFFFFFFFFF)
+        pos = torch.arange(first_pos, first_pos + count, dtype=torch.int64, device=self.dev)[:, None]
+        z = self.idx[None, :] * 0x9E3779B1 + pos * 0x85EBCA77 + key      # int64 arithmetic wraps
+        z = (z ^ ((z >> 29) & 0x7FFFFFFFF)) * 0xBF58476D
+        z = (z ^ ((z >> 32) & 0xFFFFFFFF)) * 0x94D049BB
+        z = z ^ ((z >> 31) & 0x1FFFFFFFF)
+        u = (z & 0xFFFFFF).to(torch.float32) * (1.0 / (1 << 24)) - 0.5
+        x = (u * 12.0 ** 0.5).view(count, self.H + 2 * self.Hkv, self.D).to(self.dtype)
+        return x[:, :self.H], x[:, self.H:self.H + self.Hkv], x[:, self.H + self.Hkv:]
+
+
 class LiveEngine:
     def __init__(self, cfg, sched_cfg, source, device="cuda:0", observer=None, layered_swap=False):
         """cfg: LampsConfig (pools are allocated here); sched_cfg: LampsSchedConfig whose

@@ -24,7 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 import paper_2410_18248_amd as P  # noqa: E402
-from paper_2410_18248_amd.engine import LiveEngine, RandomSource  # noqa: E402
+from paper_2410_18248_amd.engine import DeviceSource, LiveEngine, RandomSource  # noqa: E402
 from paper_2410_18248_amd.serve_sim import synthetic_trace  # noqa: E402
 
 
@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--memory-tokens", type=int, default=6000)
     ap.add_argument("--max-batch", type=int, default=16)
     ap.add_argument("--seed", type=int, default=2410)
+    ap.add_argument("--source", default="device", choices=["device", "host"],
+                    help="where the random q / k / v rows are made (host: slow, the tests' source)")
     ap.add_argument("--layered-swap", action="store_true", help="swap layer-major (a returning request runs layer by layer)")
     a = ap.parse_args()
     import torch
@@ -52,8 +54,8 @@ def main():
     # cost model used for the handling decision and the rank only (time itself is measured)
     cost = P.LampsCostModel(2e-3, 2e-8 * a.layers, 1e-3, 3e-6 * a.layers, 3e-4, 3.7e-7 * a.layers, 0, 0)
     scfg = P.LampsSchedConfig(pol, a.max_batch, a.memory_tokens, 100, 1, 2048, 0.5 * a.memory_tokens, M, cost)
-    eng = LiveEngine(cfg, scfg, RandomSource(a.seed, a.heads, a.kv_heads, D, torch.bfloat16),
-                     layered_swap=a.layered_swap)
+    make = DeviceSource if a.source == "device" else RandomSource
+    eng = LiveEngine(cfg, scfg, make(a.seed, a.heads, a.kv_heads, D, torch.bfloat16), layered_swap=a.layered_swap)
     trace = synthetic_trace(a.seed, a.requests, a.rate)
     for rid, arr, prompt, segs, _ in trace:
         eng.add(rid, arr, prompt, [(n, None if d is None else d * a.time_scale, rho, None) for n, d, rho in segs])
@@ -74,8 +76,9 @@ def main():
            "mean_latency_s": float(np.mean(lat)), "p99_latency_s": float(np.percentile(lat, 99)),
            "mean_ttft_s": float(np.mean(ttft)), "handling_preserve_discard_swap": mix,
            "all_blocks_free_at_end": bool(free_ok),
-           "note": "no model: q/k/v are seeded random tensors made on the host each iteration, which "
-                   "dominates wall time; the library's share is gpu_s"}
+           "note": "no model: q/k/v are seeded random tensors (made on the %s); gpu_s is the time from the first "
+                   "enqueue of an iteration to the compute stream running dry, the iteration time the scheduler "
+                   "is given" % a.source}
     eng.close()
     print(json.dumps(out))
 

@@ -72,3 +72,31 @@ def test_trace_served_on_the_gpu_matches_the_oracle_token_by_token(dtype, H, Hkv
     assert stats["swapped_out_blocks"] > 0 and stats["swapped_in_blocks"] > 0 and stats["discarded_blocks"] > 0
     assert worst[0] <= (1e-5 if dtype == "f32" else 2e-2), worst[0]
     eng.close()
+
+
+def test_device_source_is_a_pure_function_and_serves_a_trace():
+    """The device-side input source of serve_live: rows depend on (seed, rid, position, layer)
+    only, whatever range they are asked for in; a short trace served with it ends with every
+    block free."""
+    from paper_2410_18248_amd.engine import DeviceSource
+    H, Hkv, D, L, bs = 4, 2, 64, 2, 16
+    src = DeviceSource(5, H, Hkv, D, torch.bfloat16)
+    q, k, v = src.rows(3, 0, 9, 1)
+    q2, k2, v2 = src.rows(3, 4, 5, 1)
+    assert torch.equal(q[4:], q2) and torch.equal(k[4:], k2) and torch.equal(v[4:], v2)
+    assert not torch.equal(src.rows(3, 0, 9, 0)[0], q) and not torch.equal(src.rows(4, 0, 9, 1)[0], q)
+    big = torch.cat([x.float().flatten() for x in src.rows(1, 0, 64, 0)])
+    assert abs(float(big.mean())) < 0.05 and abs(float(big.var()) - 1.0) < 0.05
+    memory_tokens, n_req = 300, 6
+    nb = memory_tokens // bs + n_req + 2
+    cfg = P.LampsConfig(L, H, Hkv, D, bs, nb, 16, 4, P.LAMPS_BF16, 0.0, 0, 0)
+    cost = P.LampsCostModel(1e-3, 1e-7, 1e-4, 1e-5, 1e-4, 1e-6, 0, 0)
+    scfg = P.LampsSchedConfig(P.LAMPS_POLICY_LAMPS, 4, memory_tokens, 20, 1, 1 << 20, 50.0, 1.0, cost)
+    eng = LiveEngine(cfg, scfg, src)
+    for i in range(n_req):
+        eng.add(i, 0.001 * i, 10 + 3 * i, [(5 + i, 0.003, 4, [P.LAMPS_PRESERVE, P.LAMPS_DISCARD, P.LAMPS_SWAP][i % 3]),
+                                            (6, None, 0, None)])
+    stats = eng.run(max_iterations=2000)
+    assert eng.lam.num_free() == nb
+    assert stats["decode_tokens"] == sum(5 + i + 6 for i in range(n_req))
+    eng.close()
