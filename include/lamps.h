@@ -226,10 +226,12 @@ int lamps_kv_append_tokens(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t
  * q, out: device, [total_tokens][H][d_h] dtype, 16-byte aligned.  fp32 accumulation, bf16 output
  * rounded to nearest even, results independent of block placement.
  * max_new_tokens: an upper bound, known on the host, of the new tokens of any one
- * request (it sizes the launch; 0 = unknown, total_tokens is used).  bf16 with at
+ * request (it sizes the launch; 0 = unknown, total_tokens is used; rows of a
+ * request beyond a bound that is too small are left unwritten).  bf16 with at
  * most 32 query heads per kv head runs on the matrix cores (weights rounded to
- * bf16 before the second product); other geometries, and any geometry when
- * max_new_tokens < 0, run one wavefront per new token with fp32 weights. */
+ * bf16 before the second product); other geometries -- also pools whose blocks
+ * lie 4 GiB or more apart -- and any geometry when max_new_tokens < 0, run one
+ * wavefront per new token with fp32 weights. */
 int lamps_prefill_attn(lamps_ctx *ctx, int32_t layer, int32_t n_req, int32_t total_tokens,
                        int32_t max_new_tokens, const void *q, const int32_t *q_start,
                        const int32_t *block_table, const int32_t *ctx_lens, void *out);
