@@ -204,10 +204,11 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
     // Block-table entries of a group's sub-tiles: wave-uniform, through the scalar unit, and
     // looked up one iteration before the loads that use them so that nobody waits for them.
     uint32_t ent[2 * GRP];
+    const uint32_t last_entry = (uint32_t)wg_maxpos >> a.log2_block_size;   // nothing past it is looked up
     auto lookup = [&](int grp) {
+        const uint32_t t0 = (uint32_t)(grp * GRP * kStage);
 #pragma unroll
-        for (int i = 0; i < 2 * GRP; ++i)
-            ent[i] = (uint32_t)table[min(grp * GRP * kStage + 16 * i, wg_maxpos) >> a.log2_block_size];
+        for (int i = 0; i < 2 * GRP; ++i) ent[i] = (uint32_t)table[min((t0 + 16 * i) >> a.log2_block_size, last_entry)];
     };
     // This lane's part of a load's address: unit x of a sub-tile as it lies in the pool goes to
     // LDS slot x (tiled layout), or, plain layout (rows of NU units, which cannot be padded on the
@@ -231,9 +232,11 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
 #pragma unroll
         for (int k = 0; k < LPT; ++k) {
             const int x0 = kThreads * k + 64 * wv;    // the wave's first unit: sub-tile x0 / U, unit x0 % U
-            const int t = st * kStage + 16 * (x0 / U);
+            // (known at compile time where a sub-tile is at least as large as a pass of the workgroup)
+            const int sub = U >= kThreads ? (kThreads * k) / U : x0 / U;
+            const int t = st * kStage + 16 * sub;
             if (t <= wg_maxpos) {
-                const uint64_t off = (uint64_t)(x0 / U ? e1 : e0) * block_stride +
+                const uint64_t off = (uint64_t)(sub ? e1 : e0) * block_stride +
                                      (uint32_t)(((t & (a.block_size - 1)) >> 4) * (16 * D * 2));
                 // (written as assembly: the compiler would make every later LDS read wait for these loads;
                 // m0, the LDS base of such a load, is a register the compiler reserves and sets itself
