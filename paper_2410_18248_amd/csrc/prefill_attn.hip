@@ -102,7 +102,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((address_space(4))) const int32_t *table_ptr;   // read-only: scalar loads
 
 template <int D, bool TILED, int kCols, int GRP>
-__global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void prefill_mfma(const PrefillArgs p, const int tiles, const int pair_span)
+__global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void prefill_mfma(const PrefillArgs p, const int tiles, const int full_groups)
 {
     constexpr int kColBlocks = kCols / 16;
     constexpr int NK = D / 32;                       // score MFMAs per 16 positions
@@ -127,15 +127,22 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
     const DecodeArgs &a = p.d;
     // All tiles of one (request, kv head) run on one XCD (workgroups are dealt to the 8 XCDs
     // round-robin in launch order), so its K/V stream is fetched into one L2 and shared there;
-    // consecutive kv heads go to different XCDs; the longest tiles of a pair start first.  With
-    // fewer than 8 pairs (pair_span = 1, 2 or 4: the pairs rounded up to a power of two) the
-    // tiles of a pair are dealt over 8 / pair_span XCDs instead of leaving XCDs empty.
+    // consecutive kv heads go to different XCDs; the longest tiles of a pair start first.  That
+    // holds for the pairs that fill whole groups of 8; the (pair, tile) items of the remaining
+    // 1..7 pairs are dealt round-robin over all XCDs instead of leaving some of them empty.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int ways = 8 / pair_span;                  // XCDs per pair
-    const int slots = (tiles + ways - 1) / ways;     // workgroups per pair and XCD
-    const int pair = xcd % pair_span + pair_span * (slot / slots);
-    const int t = (slot % slots) * ways + xcd / pair_span;
-    if (pair >= a.num_kv_heads * a.batch || t >= tiles) return;
+    const int pairs = a.num_kv_heads * a.batch;
+    int pair, t;
+    if (slot < full_groups * tiles) {
+        pair = xcd + 8 * (slot / tiles);
+        t = slot % tiles;
+    } else {
+        const int rest = pairs - 8 * full_groups;    // 1..7 here: the grid has no such slots otherwise
+        const int item = (slot - full_groups * tiles) * 8 + xcd;
+        pair = 8 * full_groups + item % rest;
+        t = item / rest;
+        if (t >= tiles) return;
+    }
     const int tile = tiles - 1 - t;
     const int r = pair / a.num_kv_heads, g = pair - r * a.num_kv_heads;
     const int G = a.num_q_heads / a.num_kv_heads;
@@ -454,10 +461,8 @@ hipError_t launch_mfma_prefill(const PrefillArgs &p, hipStream_t s)
     const int WT = kWaves * (kCols / G);
     const long long tiles = (p.max_new_tokens + WT - 1) / WT;
     const long long pairs = (long long)p.d.num_kv_heads * p.d.batch;
-    int span = 8;                                     // pairs side by side on the XCDs: 8, or fewer if there are fewer
-    while (span > 1 && span / 2 >= pairs) span /= 2;
-    const long long ways = 8 / span, slots = (tiles + ways - 1) / ways;
-    const long long grid = (pairs + span - 1) / span * slots * 8;
+    const long long full = pairs / 8, rest = pairs % 8;   // whole groups of 8 pairs, and the pairs left over
+    const long long grid = full * tiles * 8 + (rest * tiles + 7) / 8 * 8;
     if (tiles < 1 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
     // Two stages per barrier where they fit and a request has many new tokens (the matrix cores
     // bind: +2-5 %); with one tile per request the kernel is a stream over the cache, and the
@@ -465,10 +470,10 @@ hipError_t launch_mfma_prefill(const PrefillArgs &p, hipStream_t s)
     constexpr bool kFits = 2 * 2 * (4 * 16 * D * 2) <= 65536;
     if (kFits && tiles > 1)
         hipLaunchKernelGGL((prefill_mfma<D, TILED, kCols, kFits ? 2 : 1>), dim3((unsigned)grid), dim3(kThreads), 0, s, p,
-                           (int)tiles, span);
+                           (int)tiles, (int)full);
     else
         hipLaunchKernelGGL((prefill_mfma<D, TILED, kCols, 1>), dim3((unsigned)grid), dim3(kThreads), 0, s, p, (int)tiles,
-                           span);
+                           (int)full);
     return hipGetLastError();
 }
 

@@ -27,9 +27,11 @@ CASES = [
     ("bf16", 8, 2, 128, 16, [(333, 333), (500, 100)]),
     ("bf16", 6, 2, 128, 16, [(100, 100), (77, 10)]),                                 # group of 3
     ("bf16", 4, 4, 256, 16, [(90, 90), (50, 6)]),
-    # fewer than 8 (request, kv head) pairs: a pair's tiles are dealt over several XCDs (8 and 2 ways)
+    # (request, kv head) pairs that do not fill groups of 8: their tiles are dealt over all XCDs
     ("bf16", 8, 1, 128, 16, [(300, 300)]),
     ("bf16", 4, 1, 64, 16, [(100, 100), (50, 50), (70, 70)]),
+    ("bf16", 8, 4, 128, 16, [(100, 100), (60, 60), (40, 17)]),       # 12 pairs: a whole group of 8 and 4 left over
+    ("bf16", 5, 5, 64, 16, [(150, 150)]),                            # 5 pairs
     # few new tokens per request: the waves of a workgroup split the cached positions (4 and 2 ways)
     ("bf16", 4, 4, 128, 16, [(300, 20), (150, 32), (64, 1), (33, 0)]),
     ("bf16", 4, 4, 128, 16, [(300, 50), (100, 64), (70, 3)]),
