@@ -163,3 +163,14 @@ def test_argument_validation_makes_no_gpu_call(ctx):
     with pytest.raises(P.LampsError) as e:
         ctx.ticket_query(1)                                          # no ticket issued yet
     assert e.value.status == -2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits (before touching a device)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one MI355X" in r.stderr and r.stdout.strip() == ""
