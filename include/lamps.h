@@ -29,6 +29,10 @@
  *     pointers are ordinary process memory unless marked pinned.
  *   - Arguments that live in device memory (block_table, ctx_lens,
  *     running_mask) are NOT validated: no call synchronises with the device.
+ *     The kernels keep two mistakes harmless: a context length beyond
+ *     max_blocks_per_req * block_size is clamped to the row by the decode
+ *     kernels, and ignored (nothing read, nothing written) by the append and
+ *     many-token calls, as is a context shorter than its new tokens.
  *   - A context is not thread-safe; calls on it must be serialised.
  *   - lamps_decode_attn, lamps_kv_append, lamps_kv_append_tokens and
  *     lamps_prefill_attn enqueue kernels on the compute stream and nothing else

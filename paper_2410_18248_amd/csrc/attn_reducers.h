@@ -20,6 +20,13 @@ constexpr int kHalves = 2;              // half-chunks per chunk on the 1-2 head
 constexpr float kLowest = -3.0e38f;     // finite stand-in for "no score seen yet"
 constexpr int kMaxShares = 16384;       // most wave shares the balanced scheme ever uses
 constexpr size_t kPartialBudget = (size_t)64 << 20;   // bytes of partial slots it may need
+// The context length of request r as the kernels use it: never beyond the block-table row (a
+// longer value is the caller's mistake; clamped, it cannot send a lookup past the row).
+__device__ __forceinline__ int ctx_len(const DecodeArgs &a, int r)
+{
+    return min(a.ctx_lens[r], a.max_blocks * a.block_size);
+}
+
 constexpr int kShareOwner = 1, kShareSlot1 = 2, kShareEmpty = 4;   // flags in share_info[].w
 constexpr int kMergeList = 64;          // pieces whose slots are resolved per pass of the balanced merge
 

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial(const DecodeArgs a)
     const int r = (int)((item / hc_count) % a.batch);
     const int part = (int)(item / ((long long)hc_count * a.batch));
     const int running = a.running[r];          // both loads are in flight together
-    const int C = a.ctx_lens[r];
+    const int C = ctx_len(a, r);
     if (!running) return;                      // Preserve / Swap / Discard: not in the batch
     const int t_begin = part * a.part_tokens;
     if (t_begin >= C && part != 0) return;     // partition 0 of an empty context writes zeros
@@ -97,7 +97,7 @@ __global__ void decode_merge(const DecodeArgs a)
 {
     const int r = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
     if (!a.running[r]) return;
-    const int C = a.ctx_lens[r];
+    const int C = ctx_len(a, r);
     const int n_parts = (C + a.part_tokens - 1) / a.part_tokens;
     if (n_parts <= 1) return;                  // written by the partial kernel already
     const int D = a.head_dim;
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     int mine = 0;
     for (int i = 0; i < per; ++i) {
         const int r = tid * per + i;
-        if (r < B) mine += chunks_of(a.running[r], a.ctx_lens[r], CT);
+        if (r < B) mine += chunks_of(a.running[r], ctx_len(a, r), CT);
     }
     int incl = mine;                                  // inclusive scan inside the wave
 #pragma unroll
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     for (int i = 0; i < per; ++i) {
         const int r = tid * per + i;
         if (r < B) {
-            run += chunks_of(a.running[r], a.ctx_lens[r], CT);
+            run += chunks_of(a.running[r], ctx_len(a, r), CT);
             prefix[r + 1] = run;
         }
     }
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
         const long long rem = x - (long long)HC * base;
         const int hc = (int)(rem / nr), c0 = (int)(rem % nr);
         const int len = (int)min((long long)(nr - c0), x_end - x);
-        const int C = a.ctx_lens[r];
+        const int C = ctx_len(a, r);
         const int g = hc / passes;
         const int h0 = g * G + (hc % passes) * GH;
         const bool whole = (c0 == 0 && len == nr);

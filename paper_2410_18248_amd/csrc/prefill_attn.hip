@@ -43,7 +43,11 @@ __global__ __launch_bounds__(kThreads) void prefill_rows(const PrefillArgs p)
     const int r = __builtin_amdgcn_readfirstlane(request_of(p.q_start, a.batch, n));
     const int first = p.q_start[r], count = p.q_start[r + 1] - first;
     if (n >= first + count) return;
-    const int t_end = a.ctx_lens[r] - count + (n - first) + 1;     // its own position included
+    const int C = a.ctx_lens[r];
+    // a context shorter than its new tokens, or longer than the block-table row, is the caller's
+    // mistake: nothing is read or written for it
+    if (C - count < 0 || C > a.max_blocks * a.block_size) return;
+    const int t_end = C - count + (n - first) + 1;    // its own position included
     const int g = hc / passes;
     const int h0 = g * G + (hc % passes) * GH;
     const size_t row0 = (size_t)n * a.num_q_heads + h0;
@@ -152,6 +156,9 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
     if (tile * WT >= n_new) return;
     const int C = a.ctx_lens[r];
     const int base_pos = C - n_new;                  // position of the request's first new token
+    // a context shorter than its new tokens, or longer than the block-table row, is the caller's
+    // mistake: nothing is read or written for it
+    if (base_pos < 0 || C > a.max_blocks * a.block_size) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 15, qd = lane >> 4;

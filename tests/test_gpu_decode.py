@@ -170,6 +170,20 @@ def test_unused_table_entries_and_blocks_are_never_read():
     rig.close()
 
 
+@pytest.mark.parametrize("dtype,H,Hkv,part", [("f32", 4, 4, 0), ("bf16", 4, 4, 32), ("bf16", 8, 2, 0)])
+def test_context_length_beyond_the_table_row_is_clamped(dtype, H, Hkv, part):
+    """A context length larger than max_blocks_per_req * block_size is the caller's mistake; the
+    kernels clamp it to the row, so no lookup leaves the block table: the result is attention
+    over the row's positions."""
+    geom = W.Geometry(1, H, Hkv, 64, 16, 12, 4, dtype)   # rows of 4 blocks = 64 positions
+    ctx = [64, 30]
+    rig, table, q, K, V = _setup(21, geom, ctx, part)
+    ref = oracle.decode_attn(q, K, V, ctx, [1, 1])
+    out = rig.decode(0, q, table, [64 + 5000, 30], [1, 1])
+    assert np.abs(to_f64(out) - ref).max() <= tol(geom)
+    rig.close()
+
+
 def test_scale_override():
     geom = W.Geometry(1, 4, 4, 64, 16, 10, 4, "f32")
     ctx = [40]

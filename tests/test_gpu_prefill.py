@@ -120,6 +120,30 @@ def test_prefill_is_independent_of_block_placement():
     assert torch.equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("rows_kernel", [False, True])
+def test_prefill_leaves_impossible_contexts_alone(rows_kernel):
+    """A context shorter than its new tokens, or longer than the block-table row, cannot be
+    addressed: both kernels write nothing for such a request and serve the others."""
+    reqs = [(40, 10), (64, 64), (33, 33)]
+    geom, rig, table, K, V, ctx, new, q_start = _setup("bf16", 4, 4, 64, 16, reqs, 321)
+    rig.page_requests(0, table, K, V)
+    total = int(q_start[-1])
+    q = W.queries(9, geom, total)
+    dev = rig.dev
+    bad = np.asarray([5, 64 + 7000, 33], dtype=np.int32)       # shorter than its 10 new tokens; past its 4-block row
+    out = torch.full((total, 4, 64), 3.0, dtype=rig.tdtype, device=dev)
+    with torch.cuda.stream(rig.compute):
+        rig.lamps.prefill_attn(0, 3, total, n2t(q, dev), torch.as_tensor(q_start, device=dev),
+                               torch.as_tensor(table, device=dev), torch.as_tensor(bad, device=dev), out,
+                               max_new_tokens=-1 if rows_kernel else 64)
+    rig.compute.synchronize()
+    got = to_f64(out)
+    assert (got[:74] == 3.0).all()                      # requests 0 and 1: untouched
+    ref = oracle.prefill_attn(q, K, V, q_start, ctx)
+    assert np.abs(got[74:] - ref[74:]).max() <= 2e-2
+    rig.close()
+
+
 def test_prefill_rejects_bad_host_arguments():
     geom = W.Geometry(2, 4, 4, 64, 16, 8, 2, "f32")
     rig = Rig(geom, 2)
