@@ -294,8 +294,11 @@ def cpu_baseline(job):
     got = job.out[0].cpu().to(torch.float64).numpy()
     run = job.running == 1
     err = float(np.abs(got[run] - ref[run]).max())
+    t1 = time.perf_counter()                        # and once on a single thread
+    oracle.decode_attn(q, K, V, job.wl.ctx_lens, job.running, threads=1)
+    dt1 = time.perf_counter() - t1
     return {"value": job.n_running / (dt * job.g.num_layers), "unit": "tokens/s", "cores": cores,
-            "kind": "oracle",
+            "kind": "oracle", "value_one_thread": job.n_running / (dt1 * job.g.num_layers),
             "sample": "all %d running requests of one batch, 1 of %d layer(s), %d passes of %.3f s; "
                       "scaled by the layer count" % (job.n_running, job.g.num_layers, reps, dt),
             "max_abs_err_gpu_vs_oracle": err}
