@@ -9,7 +9,8 @@
 // (request, kv head, pass over GH query heads of the group).  Two schemes share
 // the same inner loops:
 //   balanced (default): all chunks of all running requests form one flat
-//     sequence; as many wavefronts as the chip holds at once each take an equal
+//     sequence (head outermost, then request, then position); as many
+//     wavefronts as the chip holds at once each take an equal
 //     contiguous share of it, so every wavefront ends within a chunk of the
 //     others however skewed the context lengths are.  A share is at most: the
 //     tail of one (request, head), some whole ones, and the head of another;
@@ -148,10 +149,18 @@ __device__ __forceinline__ int chunks_of(int running, int C, int CT)
 }
 
 // gridDim.x * 4 wavefronts, each an equal contiguous share of the flat chunk
-// sequence ordered (request, kv head / pass, chunk).  prefix[] (dynamic LDS,
+// sequence ordered (kv head / pass, request, chunk).  prefix[] (dynamic LDS,
 // batch + 1 ints) holds the running chunk count per request; every workgroup
 // computes it for itself from ctx_lens / running (a few hundred loads that hit
 // in L2), which costs less than a dependent launch.
+//
+// Which share a wavefront takes: with the heads outermost, the shares that read
+// the same blocks for different heads lie shares / heads apart.  Workgroups go to
+// the eight XCDs in turn, each XCD translates addresses for itself, and a block's
+// heads share its pages; so the shares are handed out in the order of their
+// position inside a head's stretch, XCD 0 first: the waves that walk the same
+// blocks at the same time then sit on one XCD, next to each other.  With pools of
+// 100 GB and more this is worth several per cent; with small pools it is neutral.
 template <typename R>
 __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
 {
@@ -191,10 +200,20 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     const int GH = a.heads_per_pass;
     const int passes = G / GH;
     const int HC = a.num_kv_heads * passes;
-    const long long total = (long long)HC * prefix[B];
+    const int T = prefix[B];                          // chunks per head / pass
+    const long long total = (long long)HC * T;
     // from here on every wave is on its own: no barrier below
-    const int share = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(wv);
     const int P = gridDim.x * kWaves;
+    int share = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(wv);
+    if (a.share_gcd > 0) {
+        // rank = (share * HC mod P) + share / (P / gcd) orders the shares by where they
+        // start inside a head's stretch; this wave takes the share of rank
+        // (XCD, index inside the XCD), found by inverting that
+        const int rank = (blockIdx.x & 7) * (P >> 3) + (blockIdx.x >> 3) * kWaves +
+                         __builtin_amdgcn_readfirstlane(wv);
+        const int tie = rank % a.share_gcd, period = P / a.share_gcd;
+        share = (int)((long long)(rank / a.share_gcd) * a.share_inv % period) + tie * period;
+    }
     // What the merge kernel needs to know about this share: whether it is empty,
     // and the (request, head) range it starts but does not finish, if any (only
     // its last range can be one): request, head/pass, last share of the range,
@@ -207,19 +226,19 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
         return;
     }
 
-    // request that holds position x_begin: the last r with HC * prefix[r] <= x_begin
+    // request that holds position x_begin of its head: the last r with prefix[r] <= it
+    const int first_pos = (int)(x_begin % T);
     int lo = 0, hi = B;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if ((long long)HC * prefix[mid] <= x_begin) lo = mid; else hi = mid;
+        if (prefix[mid] <= first_pos) lo = mid; else hi = mid;
     }
     int r = __builtin_amdgcn_readfirstlane(lo);
     long long x = x_begin;
     while (x < x_end) {
         const int base = __builtin_amdgcn_readfirstlane(prefix[r]);
         const int nr = __builtin_amdgcn_readfirstlane(prefix[r + 1]) - base;   // > 0 here
-        const long long rem = x - (long long)HC * base;
-        const int hc = (int)(rem / nr), c0 = (int)(rem % nr);
+        const int hc = (int)(x / T), c0 = (int)(x % T) - base;
         const int len = (int)min((long long)(nr - c0), x_end - x);
         const int C = ctx_len(a, r);
         const int g = hc / passes;
@@ -239,9 +258,10 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
             owned = make_int4(r, hc, (int)share_of(x + nr - 1, total, P),
                               kShareOwner | (x == x_begin ? 0 : kShareSlot1));
         x += len;
-        if (c0 + len == nr && hc == HC - 1) {         // request finished: next one with work
-            ++r;
-            while (r < B && prefix[r + 1] == prefix[r]) ++r;
+        if (c0 + len == nr) {                         // request finished: next one with work,
+            do {                                      // after the last one the next head's first
+                if (++r == B) r = 0;
+            } while (prefix[r + 1] == prefix[r]);
         }
     }
     if (lane == 0) a.share_info[share] = owned;
@@ -341,7 +361,26 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
     }
     const int wgs = min(resident, decode_max_shares(a.heads_per_pass, a.head_dim) / kWaves);
     const size_t lds = (size_t)(a.batch + 1) * sizeof(int);
-    hipLaunchKernelGGL(decode_balanced<R>, dim3(wgs), dim3(kThreads), lds, s, a);
+    static int perm_for[2] = {0, 0}, perm[2] = {0, 0};   // (HC, wgs) -> (gcd, inverse)
+    if (perm_for[0] != HC || perm_for[1] != wgs) {
+        perm[0] = perm[1] = 0;
+        if (wgs % 8 == 0) {                           // whole rounds over the XCDs
+            const int P = wgs * kWaves;
+            int g = HC, t = P;
+            while (t) { const int m = g % t; g = t; t = m; }
+            const int period = P / g, step = HC / g % period;
+            int inv = 0;                              // step * inv = 1 (mod period); period is small
+            while (period > 1 && (long long)step * inv % period != 1) ++inv;
+            perm[0] = g;
+            perm[1] = inv;
+        }
+        perm_for[0] = HC;
+        perm_for[1] = wgs;
+    }
+    DecodeArgs b = a;
+    b.share_gcd = perm[0];
+    b.share_inv = perm[1];
+    hipLaunchKernelGGL(decode_balanced<R>, dim3(wgs), dim3(kThreads), lds, s, b);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int slices = (a.heads_per_pass * a.head_dim + 255) / 256;

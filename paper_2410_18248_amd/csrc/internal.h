@@ -22,6 +22,9 @@ struct DecodeArgs {
     int32_t bf16;             // 0: fp32 storage, 1: bf16 storage
     int32_t heads_per_pass;   // query heads of a kv group that share one pass over K/V
     float scale_log2e;        // softmax scale * log2(e)
+    // balanced: which share a wavefront takes (filled in by launch_decode): 0 = in launch
+    // order, else gcd(head passes, shares) and the inverse of passes / gcd modulo shares / gcd
+    int32_t share_gcd, share_inv;
 };
 
 // Query heads of one kv group that share a pass over K/V for this geometry
