@@ -28,7 +28,7 @@ __device__ __forceinline__ int ctx_len(const DecodeArgs &a, int r)
 }
 
 constexpr int kShareOwner = 1, kShareSlot1 = 2, kShareEmpty = 4;   // flags in share_info[].w
-constexpr int kMergeList = 64;          // pieces whose slots are resolved per pass of the balanced merge
+constexpr int kWideShares = 16;         // shares one block of the piece-parallel merge looks at
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;

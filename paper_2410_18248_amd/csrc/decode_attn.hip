@@ -268,64 +268,164 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
 }
 
 // Merges the pieces of every (request, kv head / pass) that was split over
-// several shares, in share order (= token order).  One block per share and slice
-// of 256 (head, dim) outputs: the share that holds the start of a split range
-// merges it (most blocks find nothing to do and leave after one load).
+// several shares, in share order (= token order).  One wavefront per share and
+// slice of 128 (head, dim) outputs, two outputs per lane: the share that holds the
+// start of a split range merges it, eight pieces' loads in flight at a time (most
+// waves find nothing to do and leave after one load).  A wave works alone: the
+// piece list lives in a register, one piece per lane, and is read with readlane.
+// The grid is small on purpose: launching a workgroup that leaves at once costs
+// about a nanosecond, and a block per share and 256 outputs spent most of this
+// kernel's time on that.
 template <bool BF16>
 __global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a)
 {
-    const int4 owned = a.share_info[blockIdx.x];
+    const int lane = threadIdx.x & 63;
+    const int w_first = __builtin_amdgcn_readfirstlane(blockIdx.x * kWaves + (threadIdx.x >> 6));
+    const int4 owned = a.share_info[w_first];
     if (!(owned.w & kShareOwner)) return;
-    const int r = owned.x, hc = owned.y;
+    const int r = __builtin_amdgcn_readfirstlane(owned.x), hc = __builtin_amdgcn_readfirstlane(owned.y);
+    const int w_last = __builtin_amdgcn_readfirstlane(owned.z);
+    const int first_flags = __builtin_amdgcn_readfirstlane(owned.w);
     const int D = a.head_dim;
     const int G = a.num_q_heads / a.num_kv_heads;
     const int GH = a.heads_per_pass;
     const int passes = G / GH;
-    const int w_first = blockIdx.x, w_last = owned.z;
-    const int g = hc / passes;
-    const size_t rh0 = (size_t)r * a.num_q_heads + g * G + (hc % passes) * GH;
-    const int idx = blockIdx.y * 256 + threadIdx.x;
+    const size_t rh0 = (size_t)r * a.num_q_heads + (hc / passes) * G + (hc % passes) * GH;
+    const int idx = blockIdx.y * 128 + 2 * lane;       // the lane's two outputs: same head, d even
     const bool live = idx < GH * D;
     const int h = live ? idx / D : 0, d = live ? idx % D : 0;
-    // The pieces' slots are looked up once per block, kMergeList at a time; each list
-    // is then reduced eight pieces at a time.
-    __shared__ int piece[kMergeList];
-    float M = kLowest, L = 0.0f, A = 0.0f;
-    for (int w0 = w_first; w0 <= w_last; w0 += kMergeList) {
-        const int cnt = min(kMergeList, w_last - w0 + 1);
-        __syncthreads();
-        if ((int)threadIdx.x < cnt) {
-            const int w = w0 + threadIdx.x;        // the first share knows its slot; later ones start
-            const int f = w == w_first ? owned.w : a.share_info[w].w;   // inside the range: slot 0
-            piece[threadIdx.x] = (f & kShareEmpty) ? -1 : w * 2 + ((w == w_first && (f & kShareSlot1)) ? 1 : 0);
+    float M = kLowest, L = 0.0f, A0 = 0.0f, A1 = 0.0f;
+    for (int w0 = w_first; w0 <= w_last; w0 += 64) {
+        const int cnt = min(64, w_last - w0 + 1);
+        int slot = -1;                                 // lane i: where piece i of this pass lies
+        if (lane < cnt) {
+            const int w = w0 + lane;                   // the first share knows its slot; later ones
+            const int f = w == w_first ? first_flags : a.share_info[w].w;   // start inside the range: slot 0
+            slot = (f & kShareEmpty) ? -1 : w * 2 + ((w == w_first && (f & kShareSlot1)) ? 1 : 0);
         }
-        __syncthreads();
         for (int i0 = 0; i0 < cnt; i0 += 8) {          // share order = token order
-            float mo[8], lo[8], ao[8];                 // eight pieces' loads in flight together
+            float2 ml[8], ao[8];                       // rows of the partials are 8-byte aligned
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-                const int pc = i0 + k < cnt ? piece[i0 + k] : -1;
-                const float *x = a.partials + ((size_t)max(pc, 0) * GH + h) * (D + 2);
-                mo[k] = pc >= 0 ? x[D] : kLowest;
-                lo[k] = pc >= 0 ? x[D + 1] : 0.0f;
-                ao[k] = pc >= 0 ? x[d] : 0.0f;
+                const int pc = __builtin_amdgcn_readlane(slot, min(i0 + k, 63));
+                const bool have = i0 + k < cnt && pc >= 0;
+                const float2 *x = reinterpret_cast<const float2 *>(
+                    a.partials + ((size_t)max(pc, 0) * GH + h) * (D + 2));
+                ml[k] = have ? x[D / 2] : make_float2(kLowest, 0.0f);
+                ao[k] = have ? x[d / 2] : make_float2(0.0f, 0.0f);
             }
             float Mn = M;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, mo[k]);
+            for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, ml[k].x);
             const float f0 = fast_exp2(M - Mn);
             L *= f0;
-            A *= f0;
+            A0 *= f0;
+            A1 *= f0;
             M = Mn;
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-                const float f = fast_exp2(mo[k] - M);
-                L += lo[k] * f;
-                A += ao[k] * f;
+                const float f = fast_exp2(ml[k].x - M);
+                L += ml[k].y * f;
+                A0 += ao[k].x * f;
+                A1 += ao[k].y * f;
             }
         }
     }
-    if (live) store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A / L : 0.0f);
+    if (live) {
+        store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A0 / L : 0.0f);
+        store_out<BF16>(a.out, (rh0 + h) * D + d + 1, L > 0.0f ? A1 / L : 0.0f);
+    }
+}
+
+// The same merge for a small batch of long contexts.  A range then has hundreds of
+// pieces, and one lane per output pair walking them eight at a time is a long serial
+// chain.  Here a block looks at 16 shares and, for each owner among them (there are
+// few), takes 32 outputs of one query head of its range: 32 groups of 8 threads,
+// four outputs per thread; group j merges the pieces j, j + 32, ... eight in flight
+// per thread, so one pass covers the 256 pieces that the piece list resolves at a
+// time; the groups' states are merged in group order at the end.
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void decode_merge_wide(const DecodeArgs a)
+{
+    constexpr int QUADS = 8, GROUPS = 32, INFL = 8;
+    const int tid = threadIdx.x, j = tid / QUADS, q = tid % QUADS;
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int GH = a.heads_per_pass;
+    const int passes = G / GH;
+    const int h = blockIdx.y;                          // query head of the pass
+    const int d0 = blockIdx.z * 32 + 4 * q;            // first of this thread's four outputs
+    __shared__ int4 owners[kWideShares];
+    __shared__ int piece[256];
+    __shared__ float state[GROUPS][QUADS][6];
+    if (tid < kWideShares) owners[tid] = a.share_info[blockIdx.x * kWideShares + tid];
+    __syncthreads();
+    for (int s = 0; s < kWideShares; ++s) {
+        const int4 owned = owners[s];
+        if (!(owned.w & kShareOwner)) continue;        // the same for the whole block
+        const int r = owned.x, hc = owned.y;
+        const int w_first = blockIdx.x * kWideShares + s, w_last = owned.z;
+        const size_t row = (size_t)r * a.num_q_heads + (hc / passes) * G + (hc % passes) * GH + h;
+        float M = kLowest, L = 0.0f, A[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int w0 = w_first; w0 <= w_last; w0 += 256) {
+            const int cnt = min(256, w_last - w0 + 1);
+            __syncthreads();
+            if (tid < cnt) {
+                const int w = w0 + tid;
+                const int f = w == w_first ? owned.w : a.share_info[w].w;
+                piece[tid] = (f & kShareEmpty) ? -1 : w * 2 + ((w == w_first && (f & kShareSlot1)) ? 1 : 0);
+            }
+            __syncthreads();
+            float2 ml[INFL], ao[INFL][2];              // rows of the partials are 8-byte aligned
+#pragma unroll
+            for (int k = 0; k < INFL; ++k) {
+                const int i = j + k * GROUPS;
+                const int pc = i < cnt ? piece[i] : -1;
+                const float2 *x = reinterpret_cast<const float2 *>(
+                    a.partials + ((size_t)max(pc, 0) * GH + h) * (D + 2));
+                ml[k] = pc >= 0 ? x[D / 2] : make_float2(kLowest, 0.0f);
+                ao[k][0] = pc >= 0 ? x[d0 / 2] : make_float2(0.0f, 0.0f);
+                ao[k][1] = pc >= 0 ? x[d0 / 2 + 1] : make_float2(0.0f, 0.0f);
+            }
+            float Mn = M;
+#pragma unroll
+            for (int k = 0; k < INFL; ++k) Mn = fmaxf(Mn, ml[k].x);
+            const float f0 = fast_exp2(M - Mn);
+            L *= f0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) A[e] *= f0;
+            M = Mn;
+#pragma unroll
+            for (int k = 0; k < INFL; ++k) {
+                const float f = fast_exp2(ml[k].x - M);
+                L += ml[k].y * f;
+                A[0] += ao[k][0].x * f;
+                A[1] += ao[k][0].y * f;
+                A[2] += ao[k][1].x * f;
+                A[3] += ao[k][1].y * f;
+            }
+        }
+        __syncthreads();                               // the state of the owner before is read
+        float *mine = state[j][q];
+        mine[0] = M;
+        mine[1] = L;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mine[2 + e] = A[e];
+        __syncthreads();
+        if (j == 0) {
+            for (int jj = 1; jj < GROUPS; ++jj) {      // group order = a fixed order of the pieces
+                const float *t = state[jj][q];
+                const float Mn = fmaxf(M, t[0]);
+                const float f0 = fast_exp2(M - Mn), f1 = fast_exp2(t[0] - Mn);
+                L = L * f0 + t[1] * f1;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) A[e] = A[e] * f0 + t[2 + e] * f1;
+                M = Mn;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                store_out<BF16>(a.out, row * D + d0 + e, L > 0.0f ? A[e] / L : 0.0f);
+        }
+    }
 }
 
 // ---------------------------------------------------------------- launchers
@@ -383,8 +483,15 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
     hipLaunchKernelGGL(decode_balanced<R>, dim3(wgs), dim3(kThreads), lds, s, b);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int slices = (a.heads_per_pass * a.head_dim + 255) / 256;
-    hipLaunchKernelGGL(decode_merge_balanced<R::kBF16>, dim3(wgs * kWaves, slices), dim3(256), 0, s, a);
+    // a batch so small that its ranges average 16 pieces and more: pieces in parallel
+    const int P = wgs * kWaves;
+    if ((long long)a.batch * HC * 16 <= P && P % kWideShares == 0) {
+        hipLaunchKernelGGL((decode_merge_wide<R::kBF16, R::D>),
+                           dim3(P / kWideShares, a.heads_per_pass, R::D / 32), dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
+    const int slices = (a.heads_per_pass * a.head_dim + 127) / 128;
+    hipLaunchKernelGGL(decode_merge_balanced<R::kBF16>, dim3(wgs, slices), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

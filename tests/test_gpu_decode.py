@@ -301,3 +301,25 @@ def test_large_batch_of_short_requests(dtype, H, Hkv):
     assert (got[~live] == 2.5).all()
     assert (got[live & (ctx == 0)] == 0).all()
     rig.close()
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,D,ctx", [
+    ("bf16", 2, 2, 128, [40000]),                 # one request: 1 250 one-chunk pieces per head
+    ("bf16", 8, 2, 128, [20000, 9000, 0]),        # matrix-core path, four heads per pass
+    ("bf16", 4, 4, 64, [33000, 17]),
+    ("f32", 2, 1, 64, [30000]),                   # fp32 group of two
+])
+def test_small_batch_of_long_contexts(dtype, H, Hkv, D, ctx):
+    """A few long requests: every (request, head) range is cut into hundreds of pieces,
+    more than one pass of the merge's piece list, and the merge takes the pieces of a
+    range in parallel."""
+    seed = 1234 + H
+    per = [(c + 15) // 16 for c in ctx]
+    geom = W.Geometry(1, H, Hkv, D, 16, sum(per) + 5, max(per), dtype)
+    rig, table, q, K, V = _setup(seed, geom, ctx)
+    running = np.ones(len(ctx), dtype=np.uint8)
+    out = rig.decode(0, q, table, ctx, running, sentinel=2.5)
+    ref = oracle.decode_attn(q, K, V, ctx, running, threads=8)
+    got = to_f64(out)
+    assert np.abs(got - ref).max() <= tol(geom)
+    rig.close()
