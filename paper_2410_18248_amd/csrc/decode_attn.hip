@@ -343,7 +343,7 @@ __global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a)
 // few), takes 32 outputs of one query head of its range: 32 groups of 8 threads,
 // four outputs per thread; group j merges the pieces j, j + 32, ... eight in flight
 // per thread, so one pass covers the 256 pieces that the piece list resolves at a
-// time; the groups' states are merged in group order at the end.
+// time; the groups' states are merged by a fixed tree through LDS at the end.
 template <bool BF16, int D>
 __global__ __launch_bounds__(256) void decode_merge_wide(const DecodeArgs a)
 {
@@ -411,9 +411,9 @@ __global__ __launch_bounds__(256) void decode_merge_wide(const DecodeArgs a)
 #pragma unroll
         for (int e = 0; e < 4; ++e) mine[2 + e] = A[e];
         __syncthreads();
-        if (j == 0) {
-            for (int jj = 1; jj < GROUPS; ++jj) {      // group order = a fixed order of the pieces
-                const float *t = state[jj][q];
+        for (int half = GROUPS / 2; half >= 1; half /= 2) {   // a fixed tree over the groups
+            if (j < half) {
+                const float *t = state[j + half][q];
                 const float Mn = fmaxf(M, t[0]);
                 const float f0 = fast_exp2(M - Mn), f1 = fast_exp2(t[0] - Mn);
                 L = L * f0 + t[1] * f1;
@@ -421,6 +421,16 @@ __global__ __launch_bounds__(256) void decode_merge_wide(const DecodeArgs a)
                 for (int e = 0; e < 4; ++e) A[e] = A[e] * f0 + t[2 + e] * f1;
                 M = Mn;
             }
+            __syncthreads();
+            if (j >= half / 2 && j < half) {           // the upper half of the next level publishes
+                mine[0] = M;
+                mine[1] = L;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) mine[2 + e] = A[e];
+            }
+            __syncthreads();
+        }
+        if (j == 0) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 store_out<BF16>(a.out, row * D + d0 + e, L > 0.0f ? A[e] / L : 0.0f);
@@ -483,9 +493,9 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
     hipLaunchKernelGGL(decode_balanced<R>, dim3(wgs), dim3(kThreads), lds, s, b);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // a batch so small that its ranges average 16 pieces and more: pieces in parallel
+    // a batch so small that its ranges average 64 pieces and more: pieces in parallel
     const int P = wgs * kWaves;
-    if ((long long)a.batch * HC * 16 <= P && P % kWideShares == 0) {
+    if ((long long)a.batch * HC * 64 <= P && P % kWideShares == 0) {
         hipLaunchKernelGGL((decode_merge_wide<R::kBF16, R::D>),
                            dim3(P / kWideShares, a.heads_per_pass, R::D / 32), dim3(256), 0, s, a);
         return hipGetLastError();
