@@ -323,3 +323,24 @@ def test_small_batch_of_long_contexts(dtype, H, Hkv, D, ctx):
     got = to_f64(out)
     assert np.abs(got - ref).max() <= tol(geom)
     rig.close()
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,D", [("bf16", 2, 2, 128), ("bf16", 8, 2, 128), ("f32", 4, 4, 64)])
+def test_one_long_request_among_many_short_ones(dtype, H, Hkv, D):
+    """The batch is large enough for the one-wavefront-per-share merge, and one request is so
+    long that each of its ranges is cut into far more pieces than one pass of that merge's
+    piece list holds."""
+    seed = 4321 + H
+    ctx = [20 + (i % 7) for i in range(35)] + [40000] + [33 - (i % 5) for i in range(35)]
+    per = [(c + 15) // 16 for c in ctx]
+    geom = W.Geometry(1, H, Hkv, D, 16, sum(per) + 5, max(per), dtype)
+    rig, table, q, K, V = _setup(seed, geom, ctx)
+    running = np.ones(len(ctx), dtype=np.uint8)
+    running[3] = 0
+    out = rig.decode(0, q, table, ctx, running, sentinel=2.5)
+    ref = oracle.decode_attn(q, K, V, ctx, running, threads=8)
+    got = to_f64(out)
+    live = running == 1
+    assert np.abs(got[live] - ref[live]).max() <= tol(geom)
+    assert (got[~live] == 2.5).all()
+    rig.close()
