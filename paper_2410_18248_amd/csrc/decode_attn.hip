@@ -166,24 +166,35 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
 {
     constexpr int D = R::D, CT = R::CT;
     extern __shared__ int prefix[];
-    __shared__ int wave_total[kWaves];
+    __shared__ int wave_total[kWaves], wave_longest[kWaves];
 
     const int B = a.batch;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int per = (B + kThreads - 1) / kThreads;   // consecutive requests per thread
-    int mine = 0;
+    int mine = 0, longest = 0;
     for (int i = 0; i < per; ++i) {
         const int r = tid * per + i;
-        if (r < B) mine += chunks_of(a.running[r], ctx_len(a, r), CT);
+        if (r < B) {
+            const int n = chunks_of(a.running[r], ctx_len(a, r), CT);
+            mine += n;
+            longest = max(longest, n);
+        }
     }
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt *= 2) longest = max(longest, __shfl_xor(longest, dlt));
     int incl = mine;                                  // inclusive scan inside the wave
 #pragma unroll
     for (int dlt = 1; dlt < 64; dlt *= 2) {
         const int up = __shfl_up(incl, dlt);
         if (lane >= dlt) incl += up;
     }
-    if (lane == 63) wave_total[wv] = incl;
+    if (lane == 63) {
+        wave_total[wv] = incl;
+        wave_longest[wv] = longest;
+    }
     __syncthreads();
+#pragma unroll
+    for (int ww = 0; ww < kWaves; ++ww) longest = max(longest, wave_longest[ww]);
     int run = incl - mine;
     for (int ww = 0; ww < wv; ++ww) run += wave_total[ww];
     if (tid == 0) prefix[0] = 0;
@@ -200,12 +211,29 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     const int GH = a.heads_per_pass;
     const int passes = G / GH;
     const int HC = a.num_kv_heads * passes;
-    const int T = prefix[B];                          // chunks per head / pass
+    // (values that are the same in every lane are told so: the compiler cannot see it
+    // through LDS and the shuffles, and would keep the range arithmetic in vector registers)
+    const int T = __builtin_amdgcn_readfirstlane(prefix[B]);   // chunks per head / pass
     const long long total = (long long)HC * T;
+    longest = __builtin_amdgcn_readfirstlane(longest);
     // from here on every wave is on its own: no barrier below
-    const int P = gridDim.x * kWaves;
+    int P = gridDim.x * kWaves;
     int share = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(wv);
-    if (a.share_gcd > 0) {
+    // A launch with little work and a long range in it: equal shares over all wavefronts would
+    // cut that range into hundreds of pieces of a chunk each, and the merge of one range is a
+    // chain of dependent loads (a 40 000-token request among 70 short ones, 2 heads: 10 us of
+    // attention, 200 us of merge).  Then only as many shares are used as gives each 2, 4 or
+    // 8 chunks -- for a longest range of 256, 512, 1024 chunks and more -- and the rest stay
+    // empty.
+    const int log2_share_chunks = longest >= 1024 ? 3 : longest >= 512 ? 2 : longest >= 256 ? 1 : 0;
+    const long long wanted = (total + (1 << log2_share_chunks) - 1) >> log2_share_chunks;
+    if (wanted < P) {
+        P = __builtin_amdgcn_readfirstlane(max(1, (int)wanted));
+        if (share >= P) {
+            if (lane == 0) a.share_info[share] = make_int4(0, 0, 0, kShareEmpty);
+            return;
+        }
+    } else if (a.share_gcd > 0) {
         // rank = (share * HC mod P) + share / (P / gcd) orders the shares by where they
         // start inside a head's stretch; this wave takes the share of rank
         // (XCD, index inside the XCD), found by inverting that
@@ -267,6 +295,39 @@ __global__ __launch_bounds__(kThreads) void decode_balanced(const DecodeArgs a)
     if (lane == 0) a.share_info[share] = owned;
 }
 
+// N pieces of a split range, their loads in flight together, folded into the running
+// (M, L, A0, A1) of the lane's two outputs.  slot holds one piece per lane (-1: an empty
+// share); i0 and cnt are the same in every lane.
+template <int N>
+__device__ __forceinline__ void merge_pieces(const float *partials, int slot, int i0, int cnt, int GH, int h,
+                                             int D, int d, float &M, float &L, float &A0, float &A1)
+{
+    float2 ml[N], ao[N];                               // rows of the partials are 8-byte aligned
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const int pc = __builtin_amdgcn_readlane(slot, min(i0 + k, 63));
+        const bool have = i0 + k < cnt && pc >= 0;
+        const float2 *x = reinterpret_cast<const float2 *>(partials + ((size_t)max(pc, 0) * GH + h) * (D + 2));
+        ml[k] = have ? x[D / 2] : make_float2(kLowest, 0.0f);
+        ao[k] = have ? x[d / 2] : make_float2(0.0f, 0.0f);
+    }
+    float Mn = M;
+#pragma unroll
+    for (int k = 0; k < N; ++k) Mn = fmaxf(Mn, ml[k].x);
+    const float f0 = fast_exp2(M - Mn);
+    L *= f0;
+    A0 *= f0;
+    A1 *= f0;
+    M = Mn;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float f = fast_exp2(ml[k].x - M);
+        L += ml[k].y * f;
+        A0 += ao[k].x * f;
+        A1 += ao[k].y * f;
+    }
+}
+
 // Merges the pieces of every (request, kv head / pass) that was split over
 // several shares, in share order (= token order).  One wavefront per share and
 // slice of 128 (head, dim) outputs, two outputs per lane: the share that holds the
@@ -295,41 +356,21 @@ __global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a)
     const bool live = idx < GH * D;
     const int h = live ? idx / D : 0, d = live ? idx % D : 0;
     float M = kLowest, L = 0.0f, A0 = 0.0f, A1 = 0.0f;
+    // lane i: where piece i of a pass of 64 lies.  The first share knows its slot; later ones
+    // start inside the range: slot 0.
+    auto slots_of = [&](int w0) {
+        const int w = w0 + lane;
+        if (w > w_last) return -1;
+        const int f = w == w_first ? first_flags : a.share_info[w].w;
+        return (f & kShareEmpty) ? -1 : w * 2 + ((w == w_first && (f & kShareSlot1)) ? 1 : 0);
+    };
+    int slot_next = slots_of(w_first);
     for (int w0 = w_first; w0 <= w_last; w0 += 64) {
         const int cnt = min(64, w_last - w0 + 1);
-        int slot = -1;                                 // lane i: where piece i of this pass lies
-        if (lane < cnt) {
-            const int w = w0 + lane;                   // the first share knows its slot; later ones
-            const int f = w == w_first ? first_flags : a.share_info[w].w;   // start inside the range: slot 0
-            slot = (f & kShareEmpty) ? -1 : w * 2 + ((w == w_first && (f & kShareSlot1)) ? 1 : 0);
-        }
-        for (int i0 = 0; i0 < cnt; i0 += 8) {          // share order = token order
-            float2 ml[8], ao[8];                       // rows of the partials are 8-byte aligned
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int pc = __builtin_amdgcn_readlane(slot, min(i0 + k, 63));
-                const bool have = i0 + k < cnt && pc >= 0;
-                const float2 *x = reinterpret_cast<const float2 *>(
-                    a.partials + ((size_t)max(pc, 0) * GH + h) * (D + 2));
-                ml[k] = have ? x[D / 2] : make_float2(kLowest, 0.0f);
-                ao[k] = have ? x[d / 2] : make_float2(0.0f, 0.0f);
-            }
-            float Mn = M;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, ml[k].x);
-            const float f0 = fast_exp2(M - Mn);
-            L *= f0;
-            A0 *= f0;
-            A1 *= f0;
-            M = Mn;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const float f = fast_exp2(ml[k].x - M);
-                L += ml[k].y * f;
-                A0 += ao[k].x * f;
-                A1 += ao[k].y * f;
-            }
-        }
+        const int slot = slot_next;
+        slot_next = slots_of(w0 + 64);                 // asked for together with this pass's pieces
+        for (int i0 = 0; i0 < cnt; i0 += 8)            // share order = token order
+            merge_pieces<8>(a.partials, slot, i0, cnt, GH, h, D, d, M, L, A0, A1);
     }
     if (live) {
         store_out<BF16>(a.out, (rh0 + h) * D + d, L > 0.0f ? A0 / L : 0.0f);
