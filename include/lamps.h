@@ -100,7 +100,7 @@ typedef struct {
     int32_t max_batch;          /* largest `batch` passed to lamps_decode_attn       */
     int32_t dtype;              /* lamps_dtype of q, the pools and out               */
     float softmax_scale;        /* 0 => 1/sqrt(head_dim), the Section 2.2 equation   */
-    int32_t part_tokens;        /* 0 => balanced shares (default: every workgroup gets
+    int32_t part_tokens;        /* 0 => balanced shares (default: every wavefront gets
                                    an equal part of all cached tokens); > 0 => fixed
                                    partitions of this many tokens, multiple of
                                    block_size                                        */
