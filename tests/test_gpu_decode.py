@@ -308,6 +308,9 @@ def test_large_batch_of_short_requests(dtype, H, Hkv):
     ("bf16", 8, 2, 128, [20000, 9000, 0]),        # matrix-core path, four heads per pass
     ("bf16", 4, 4, 64, [33000, 17]),
     ("f32", 2, 1, 64, [30000]),                   # fp32 group of two
+    ("bf16", 2, 2, 128, [10000, 50]),             # longest range 313 chunks: two chunks per share
+    ("bf16", 4, 4, 128, [20000, 7, 300]),         # 625 chunks: four per share
+    ("bf16", 8, 2, 128, [5000, 4200]),            # matrix-core path, 313 chunks of 16 tokens
 ])
 def test_small_batch_of_long_contexts(dtype, H, Hkv, D, ctx):
     """A few long requests: every (request, head) range is cut into hundreds of pieces,
