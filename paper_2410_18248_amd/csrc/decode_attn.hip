@@ -43,6 +43,8 @@
 //     weights at the price of a second, nearly free, MFMA.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "attn_reducers.h"
 #include "internal.h"
 
@@ -498,7 +500,8 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
     }
     // balanced: as many workgroups as the chip holds at once for this kernel (fewer
     // if the partial slots of that many wave shares would not fit the workspace)
-    static int resident = 0;                          // per instantiation; one device per process
+    static std::atomic<int> resident_once{0};         // per instantiation; one device per process
+    int resident = resident_once.load(std::memory_order_relaxed);
     if (resident == 0) {
         int dev = 0, cus = 0, per_cu = 0;
         hipError_t e = hipGetDevice(&dev);
@@ -509,28 +512,26 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
         if (cus < 1 || per_cu < 1) return hipErrorInvalidValue;
         resident = cus * per_cu;
+        resident_once.store(resident, std::memory_order_relaxed);   // every thread computes the same
     }
     const int wgs = min(resident, decode_max_shares(a.heads_per_pass, a.head_dim) / kWaves);
     const size_t lds = (size_t)(a.batch + 1) * sizeof(int);
-    static int perm_for[2] = {0, 0}, perm[2] = {0, 0};   // (HC, wgs) -> (gcd, inverse)
-    if (perm_for[0] != HC || perm_for[1] != wgs) {
-        perm[0] = perm[1] = 0;
-        if (wgs % 8 == 0) {                           // whole rounds over the XCDs
-            const int P = wgs * kWaves;
-            int g = HC, t = P;
-            while (t) { const int m = g % t; g = t; t = m; }
-            const int period = P / g, step = HC / g % period;
-            int inv = 0;                              // step * inv = 1 (mod period); period is small
-            while (period > 1 && (long long)step * inv % period != 1) ++inv;
-            perm[0] = g;
-            perm[1] = inv;
-        }
-        perm_for[0] = HC;
-        perm_for[1] = wgs;
-    }
     DecodeArgs b = a;
-    b.share_gcd = perm[0];
-    b.share_inv = perm[1];
+    b.share_gcd = b.share_inv = 0;                    // shares in launch order
+    if (wgs % 8 == 0) {                               // whole rounds over the XCDs: ranked shares
+        const int P = wgs * kWaves;
+        int g = HC, t = P;
+        while (t) { const int m = g % t; g = t; t = m; }
+        // inverse of HC / g modulo P / g (the two are coprime), by the extended Euclidean algorithm
+        const int period = P / g;
+        long long r0 = period, r1 = HC / g % period, t0 = 0, t1 = 1;
+        while (r1 > 1) {
+            const long long q = r0 / r1, r2 = r0 - q * r1, t2 = t0 - q * t1;
+            r0 = r1; r1 = r2; t0 = t1; t1 = t2;
+        }
+        b.share_gcd = g;
+        b.share_inv = period > 1 ? (int)((t1 % period + period) % period) : 0;
+    }
     hipLaunchKernelGGL(decode_balanced<R>, dim3(wgs), dim3(kThreads), lds, s, b);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
