@@ -63,6 +63,9 @@ def parse():
                          "traffic, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--geom", default="",
                     help="diagnostic: override geometry, e.g. H=8,Hkv=8,bs=32,B=64,MB=128,NB=50000")
+    ap.add_argument("--ctx-long", type=int, default=0,
+                    help="diagnostic: after the overrides, request 0 runs with this many tokens "
+                         "(a skewed batch: one long context among the others)")
     ap.add_argument("--prefill", default="",
                     help="measure lamps_prefill_attn instead (Discard's recompute): "
                          "'H,Hkv,D,requests,tokens[,cached]', e.g. 40,40,128,4,4096")
@@ -75,7 +78,7 @@ class Job:
     """Device-resident state of one benchmark workload."""
 
     def __init__(self, cfg_id, rotations, part_tokens, table_kind="random", ctx_override=0,
-                 geom_override="", direct_copy_bytes=0, staging_mib=0, zero_copy=0):
+                 geom_override="", direct_copy_bytes=0, staging_mib=0, zero_copy=0, ctx_long=0):
         import torch
 
         import lamps_workloads as W
@@ -98,6 +101,10 @@ class Job:
         if ctx_override:
             wl.ctx_lens[:] = ctx_override
             wl.name += "-ctx%d" % ctx_override
+        if ctx_long:
+            wl.ctx_lens[0] = ctx_long
+            wl.state[0] = W.RUNNING
+            wl.name += "-long%d" % ctx_long
         g = wl.geom
         self.wl, self.g = wl, g
         dev = torch.device("cuda:0")
@@ -503,7 +510,7 @@ def main():
         prefill_bench(a)
         return
     job = Job(a.config, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom, a.direct_copy_bytes, a.staging_mib,
-              a.zero_copy)
+              a.zero_copy, a.ctx_long)
     with_swap = not a.no_swap
 
     # calibrate: one short train to size the run
