@@ -336,14 +336,15 @@ __device__ __forceinline__ void merge_pieces(const float *partials, int slot, in
 // start of a split range merges it, eight pieces' loads in flight at a time (most
 // waves find nothing to do and leave after one load).  A wave works alone: the
 // piece list lives in a register, one piece per lane, and is read with readlane.
-// The grid is small on purpose: launching a workgroup that leaves at once costs
+// The grid is small on purpose (the launcher also folds up to 16 wavefronts into a
+// workgroup): launching a workgroup that leaves at once costs
 // about a nanosecond, and a block per share and 256 outputs spent most of this
 // kernel's time on that.
 template <bool BF16>
-__global__ __launch_bounds__(256) void decode_merge_balanced(const DecodeArgs a)
+__global__ __launch_bounds__(1024) void decode_merge_balanced(const DecodeArgs a)
 {
     const int lane = threadIdx.x & 63;
-    const int w_first = __builtin_amdgcn_readfirstlane(blockIdx.x * kWaves + (threadIdx.x >> 6));
+    const int w_first = __builtin_amdgcn_readfirstlane(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
     const int4 owned = a.share_info[w_first];
     if (!(owned.w & kShareOwner)) return;
     const int r = __builtin_amdgcn_readfirstlane(owned.x), hc = __builtin_amdgcn_readfirstlane(owned.y);
@@ -543,7 +544,9 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
         return hipGetLastError();
     }
     const int slices = (a.heads_per_pass * a.head_dim + 127) / 128;
-    hipLaunchKernelGGL(decode_merge_balanced<R::kBF16>, dim3(wgs, slices), dim3(256), 0, s, a);
+    // (workgroups of 16 wavefronts where the share count allows: fewer, larger workgroups launch faster)
+    const int fold = wgs % 4 == 0 ? 4 : wgs % 2 == 0 ? 2 : 1;
+    hipLaunchKernelGGL(decode_merge_balanced<R::kBF16>, dim3(wgs / fold, slices), dim3(256 * fold), 0, s, a);
     return hipGetLastError();
 }
 
