@@ -70,7 +70,9 @@ typedef enum {
  *               + fwd_b * (tokens recomputed or first processed in it)
  *               + (sw_a + sw_b * tokens swapped in or out in it)   if swap_stalls
  *   T_fwd(C)  = fwd_a + fwd_b * C        T_swap(C) = sw_a + sw_b * C
- * unit != 0: every iteration takes exactly 1 and swaps cost nothing. */
+ * unit != 0 (the worked example of Section 3.1): every iteration takes exactly 1,
+ * recomputing a discarded context takes one iteration (T_fwd = 1) and swaps cost
+ * nothing (T_swap = 0). */
 typedef struct {
     double it_a, it_b, fwd_a, fwd_b, sw_a, sw_b;
     int32_t swap_stalls; /* the paper's substrate: a swap interrupts the forward pass (Section 4.3) */
@@ -81,8 +83,9 @@ typedef struct {
     int32_t policy;               /* lamps_policy                                            */
     int32_t max_batch;            /* requests per iteration                                  */
     int64_t memory_tokens;        /* KV budget, tokens                                       */
-    int32_t starvation_threshold; /* iterations in the queue before a request goes to the
-                                     head (Section 4.4; the paper uses 100)                  */
+    int32_t starvation_threshold; /* iterations left out of the batch before a request goes
+                                     to the head of the queue, in the iteration in which its
+                                     counter gets there (Section 4.4; the paper uses 100)    */
     int32_t score_refresh;        /* iterations a cached score stays valid (Section 5: 1, or
                                      10 on ToolBench)                                        */
     int64_t recompute_chunk;      /* most tokens one request recomputes per iteration        */
@@ -148,7 +151,8 @@ int lamps_sched_add(lamps_sched *s, int64_t id, double arrival, int32_t prompt_t
 
 /* Steps 1-6 of an iteration of Algorithm 1 at the current time: arrivals and
  * finished API calls enter the waiting queue, scores, sort, batch formation,
- * starvation counters.  If nothing can run, the worst-ranked waiting request
+ * starvation counters (a request that reaches the threshold is tagged and the
+ * batch formed once more with it at the head).  If nothing can run, the worst-ranked waiting request
  * that holds memory is discarded, or, if none does, time moves to the next
  * arrival or API return; then the steps repeat.
  * Writes the batch (<= cap entries; cap >= max_batch) and *n.  *n == 0 means

@@ -19,22 +19,31 @@ notes):
     memory the candidate needs is free.  A request at the start of a segment
     needs room for the whole segment (what it has to bring back -- swapped or
     discarded context, the API response -- plus the segment's tokens): the
-    worked example refuses R3 while R1 is in its API call because R3 "will not
-    release memory before the API response completes".  A request in the
-    middle of a segment needs one token.
+    worked example (Section 3.1, FCFS) refuses R3 while R1 is in its API call
+    because R3 would still hold its memory when R1 comes back.  A request in
+    the middle of a segment needs one token.
   * Every request that is not finished and not in an API call is in the
     waiting queue at the start of every iteration and the batch is formed
     anew (iteration-level scheduling), so a better-ranked request displaces a
     running one; the displaced one keeps its memory.
   * An iteration in which a request recomputes discarded context or processes
     an API response produces no new token for it (the worked example counts
-    R2's post-API part as 2 units "including recomputation").
+    R2's part after its call as 2 units, one of them the recomputation).
   * Ties in the rank go to the earlier arrival, then the lower id.
   * If nothing can run while waiting requests hold memory (each needs more
-    than is free), the worst-ranked of them is discarded and recomputes later,
-    as the substrate the paper builds on does when it runs out of blocks; if no
-    waiting request holds memory the engine idles until the next arrival or
-    API return (the idle unit of the worked example).
+    than is free), the worst-ranked of them is discarded and recomputes later
+    (Section 4.3 names discard-and-recompute as what happens when memory is
+    full); if no waiting request holds memory the engine idles until the next
+    arrival or API return (the idle unit of the worked example).
+  * A request whose starvation counter reaches the threshold while the batch
+    is formed goes to the head of the queue in that same iteration (Section
+    4.4 places it there for the current iteration): the batch is formed once
+    more with the tagged requests first.  Counters are not incremented a
+    second time.
+  * In the worked example's units (unit=True) recomputing a discarded context
+    takes one iteration, T_fwd = 1 (Section 3.1 counts R2's part after its
+    call as two units, one of them the recomputation), and a swap takes no
+    time (R3's part after its call is one unit).
 """
 PRESERVE, DISCARD, SWAP = 0, 1, 2
 FCFS, SJF, SJF_TOTAL, LAMPS, FIXED = 0, 1, 2, 3, 4
@@ -106,9 +115,13 @@ class CostModel:
         self.sw_a, self.sw_b, self.swap_stalls, self.unit = sw_a, sw_b, swap_stalls, unit
 
     def t_fwd(self, C):
+        if self.unit:
+            return 1.0
         return self.fwd_a + self.fwd_b * C
 
     def t_swap(self, C):
+        if self.unit:
+            return 0.0
         return self.sw_a + self.sw_b * C
 
     def iteration(self, ctx_tokens, recomputed, swapped):
@@ -225,27 +238,40 @@ class Simulator:
                 if r.score is None or self.iteration - r.score_iter >= self.score_refresh:
                     r.score = self._rank(r)
                     r.score_iter = self.iteration
-            waiting.sort(key=lambda r: (0 if r.prioritized else 1, r.score, r.arrival, r.id))
+            order = lambda r: (0 if r.prioritized else 1, r.score, r.arrival, r.id)
+            waiting.sort(key=order)
             # the running batch
-            free = self.budget - sum(r.held for r in reqs)
-            batch = []
+            held_now = sum(r.held for r in reqs)
+
+            def form(count):
+                free, chosen = self.budget - held_now, []
+                for r in waiting:
+                    need = self._need(r)
+                    if len(chosen) < self.max_batch and need <= free:
+                        chosen.append(r)
+                        free -= need
+                        if count:
+                            r.starv = 0
+                    elif count:
+                        r.starv += 1
+                return chosen
+            batch = form(True)
+            # Algorithm 1's second loop: a request left out often enough is tagged and goes
+            # to the head of the queue for this very iteration
+            tagged = False
             for r in waiting:
-                need = self._need(r)
-                if len(batch) < self.max_batch and need <= free:
-                    batch.append(r)
-                    free -= need
-                    r.starv = 0
-                else:
-                    r.starv += 1
-            for r in waiting:
-                if r not in batch and r.starv >= self.starvation_threshold:
+                if r not in batch and not r.prioritized and r.starv >= self.starvation_threshold:
                     r.prioritized = True
                     r.starv = 0
+                    tagged = True
+            if tagged:
+                waiting.sort(key=order)
+                batch = form(False)
             if not batch:
-                # Nothing fits.  If memory is held by waiting requests none of which can grow
-                # (Section 4.3: "when memory is full, jobs are either discarded and recomputed
-                # when memory becomes available, or ..."), the worst-ranked holder is discarded;
-                # otherwise the engine idles until the next arrival or API return.
+                # Nothing fits.  If memory is held by waiting requests none of which can grow,
+                # the worst-ranked holder is discarded and recomputes once memory is there
+                # (Section 4.3 on full memory); otherwise the engine idles until the next
+                # arrival or API return.
                 victims = [r for r in reversed(waiting) if r.held > 0]
                 if victims:
                     v = victims[0]

@@ -43,8 +43,9 @@ struct Req {
     double completion = -1.0, first_token = -1.0;
 };
 
-double cost_t_fwd(const lamps_cost_model &c, double C) { return c.fwd_a + c.fwd_b * C; }
-double cost_t_swap(const lamps_cost_model &c, double C) { return c.sw_a + c.sw_b * C; }
+// In the worked example's units (Section 3.1) a recomputation takes one iteration and a swap none.
+double cost_t_fwd(const lamps_cost_model &c, double C) { return c.unit ? 1.0 : c.fwd_a + c.fwd_b * C; }
+double cost_t_swap(const lamps_cost_model &c, double C) { return c.unit ? 0.0 : c.sw_a + c.sw_b * C; }
 double cost_iteration(const lamps_cost_model &c, int64_t ctx_tokens, int64_t recomputed, int64_t swapped)
 {
     if (c.unit) return 1.0;
@@ -298,40 +299,52 @@ int lamps_sched_next_batch(lamps_sched *s, lamps_batch_entry *out, int32_t cap, 
                 r.score_iter = s->iteration;
             }
         }
-        std::sort(s->waiting.begin(), s->waiting.end(), [&](size_t a, size_t b) {
+        auto by_rank = [&](size_t a, size_t b) {
             const Req &x = s->reqs[a], &y = s->reqs[b];
             if (x.prioritized != y.prioritized) return x.prioritized;
             if (x.score != y.score) return x.score < y.score;
             if (x.arrival != y.arrival) return x.arrival < y.arrival;
             return x.id < y.id;
-        });
-        // the running batch
-        int64_t free_tokens = cfg.memory_tokens - s->total_held;
-        s->batch.clear();
-        for (size_t w : s->waiting) {
-            Req &r = s->reqs[w];
-            const int64_t nd = s->need(r);
-            if ((int32_t)s->batch.size() < cfg.max_batch && nd <= free_tokens) {
-                s->batch.push_back(w);
-                s->in_batch[w] = 1;
-                free_tokens -= nd;
-                r.starv = 0;
-            } else {
-                ++r.starv;
+        };
+        std::sort(s->waiting.begin(), s->waiting.end(), by_rank);
+        // the running batch; `count` = this is the pass that moves the starvation counters
+        auto form = [&](bool count) {
+            int64_t free_tokens = cfg.memory_tokens - s->total_held;
+            for (size_t w : s->batch) s->in_batch[w] = 0;
+            s->batch.clear();
+            for (size_t w : s->waiting) {
+                Req &r = s->reqs[w];
+                const int64_t nd = s->need(r);
+                if ((int32_t)s->batch.size() < cfg.max_batch && nd <= free_tokens) {
+                    s->batch.push_back(w);
+                    s->in_batch[w] = 1;
+                    free_tokens -= nd;
+                    if (count) r.starv = 0;
+                } else if (count) {
+                    ++r.starv;
+                }
             }
-        }
+        };
+        form(true);
+        // Algorithm 1's second loop: a request left out often enough is tagged and goes to the
+        // head of the queue for this very iteration (Section 4.4): the batch is formed once more
+        bool tagged = false;
         for (size_t w : s->waiting) {
             Req &r = s->reqs[w];
-            if (!s->in_batch[w] && r.starv >= cfg.starvation_threshold) {
+            if (!s->in_batch[w] && !r.prioritized && r.starv >= cfg.starvation_threshold) {
                 r.prioritized = true;
                 r.starv = 0;
+                tagged = true;
             }
         }
+        if (tagged) {
+            std::sort(s->waiting.begin(), s->waiting.end(), by_rank);
+            form(false);
+        }
         if (!s->batch.empty()) break;
-        // Nothing fits.  If memory is held by waiting requests none of which can grow
-        // (Section 4.3: "when memory is full, jobs are either discarded and recomputed ..."),
-        // the worst-ranked holder is discarded; otherwise the engine idles until the next
-        // arrival or API return.
+        // Nothing fits.  If memory is held by waiting requests none of which can grow, the
+        // worst-ranked holder is discarded and recomputes once memory is there (Section 4.3 on
+        // full memory); otherwise the engine idles until the next arrival or API return.
         Req *victim = nullptr;
         for (size_t k = s->waiting.size(); k-- > 0;)
             if (s->reqs[s->waiting[k]].held > 0) {
