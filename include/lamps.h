@@ -175,6 +175,46 @@ int lamps_decode_attn(lamps_ctx *ctx, int32_t layer, int32_t batch, const void *
                       const int32_t *block_table, const int32_t *ctx_lens,
                       const uint8_t *running_mask, void *out);
 
+/* ---- decode attention for callers that cannot allocate ---- */
+
+/* Bytes of device memory the library's code object reserves on every GPU it is
+ * loaded on for lamps_decode_attn_static (a file-scope device array; it lives
+ * until the process ends). */
+#define LAMPS_STATIC_SCRATCH_BYTES (33u << 20)
+
+/* lamps_decode_attn without a context and without a workspace, for callers that
+ * cannot allocate device memory: code running under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same kernels, same result,
+ * bit for bit, as lamps_decode_attn on a context created from `cfg` with
+ * part_tokens == 0; the split ranges' partial results and the per-share records
+ * go to the library's own LAMPS_STATIC_SCRATCH_BYTES array on the current device
+ * instead of a caller-provided workspace.  The call allocates nothing (no
+ * hipMalloc / hipFree, no host heap) and enqueues the two kernels on
+ * compute_stream (hipStream_t as void*, NULL = the default stream) of the
+ * current device.
+ *   cfg           host; validated as by lamps_create (staging / copy fields are ignored);
+ *                 part_tokens must be 0
+ *   k_pool,v_pool device, the two pools in the layout above, 16-byte aligned
+ *   q, out, block_table, ctx_lens, running_mask: as for lamps_decode_attn
+ * Limit: the partial slots of one launch -- two records of (heads per pass) x
+ * (head_dim + 2) floats for each wavefront resident on the chip -- must fit
+ * 32 MiB of the array (on an MI355X: 4.3 MB for 32 heads on 32 kv heads of 128,
+ * 8.5 MB for 32 on 8, 34 MB -- too much -- for 64 on 4); a geometry beyond that
+ * is refused with LAMPS_ERR_RANGE and nothing is enqueued.
+ * All calls on one GPU share that GPU's array, which keeps the last call's
+ * contents (nothing in it has to be cleared: every launch writes what it later
+ * reads): calls that overlap on one GPU -- two streams, two threads -- race and
+ * must be serialised by the caller.  The first call on a device looks the
+ * array's address up and asks the occupancy of the kernel (both are kept per
+ * device); make one eager call before capturing the call into a graph.
+ * Errors: INVALID (null, bad cfg, part_tokens != 0, alignment), RANGE (layer,
+ * batch > cfg->max_batch, geometry beyond the scratch array), HIP.  The text is
+ * available from lamps_last_error(NULL) on the calling thread. */
+int lamps_decode_attn_static(const lamps_config *cfg, void *compute_stream, int32_t layer,
+                             int32_t batch, const void *q, const void *k_pool, const void *v_pool,
+                             const int32_t *block_table, const int32_t *ctx_lens,
+                             const uint8_t *running_mask, void *out);
+
 /* ---- KV append: the cache grows by one position per iteration (Section 2.2.1) ---- */
 
 /* One layer of one iteration, enqueued on the compute stream; returns at once.
@@ -322,7 +362,8 @@ int lamps_free_blocks(lamps_ctx *ctx, const int32_t *block_ids, int32_t n);
 int lamps_num_free(lamps_ctx *ctx);
 
 /* Text of the last error on this context ("" if none).  With ctx == NULL,
- * the last error of a failed lamps_create on this thread. */
+ * the last error of a failed lamps_create or lamps_decode_attn_static on this
+ * thread. */
 const char *lamps_last_error(lamps_ctx *ctx);
 
 #ifdef __cplusplus

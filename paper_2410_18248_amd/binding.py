@@ -68,6 +68,7 @@ def load_library():
         "lamps_create": [cfgp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)],
         "lamps_destroy": [vp],
         "lamps_decode_attn": [vp, i32, i32, vp, vp, vp, vp, vp],
+        "lamps_decode_attn_static": [cfgp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp],
         "lamps_kv_append": [vp, i32, i32, vp, vp, vp, vp, vp, i32],
         "lamps_kv_append_tokens": [vp, i32, i32, i32, vp, vp, vp, vp, vp],
         "lamps_prefill_attn": [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp],
@@ -263,6 +264,16 @@ def lamps_pool_bytes(cfg):
 
 def lamps_workspace_bytes(cfg):
     return load_library().lamps_workspace_bytes(ctypes.byref(cfg))
+
+
+def lamps_decode_attn_static(cfg, compute_stream, layer, batch, q, k_pool, v_pool, block_table, ctx_lens,
+                             running_mask, out):
+    lib = load_library()
+    rc = lib.lamps_decode_attn_static(ctypes.byref(cfg), compute_stream or None, layer, batch, _ptr(q),
+                                      _ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(ctx_lens),
+                                      _ptr(running_mask), _ptr(out))
+    if rc < 0:
+        raise LampsError(rc, lib.lamps_last_error(None).decode())
 
 
 class Lamps:

@@ -47,6 +47,7 @@
 
 #include "attn_reducers.h"
 #include "internal.h"
+#include "lamps.h"
 
 namespace lamps {
 namespace {
@@ -484,12 +485,41 @@ __global__ __launch_bounds__(256) void decode_merge_wide(const DecodeArgs a)
 
 // ---------------------------------------------------------------- launchers
 
+// Workgroups the chip holds at once for decode_balanced<R>, per device (asked once per device and
+// instantiation; every thread that asks computes the same).
 template <typename R>
-hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
+hipError_t resident_workgroups(const DecodeArgs &a, int *out)
+{
+    static std::atomic<int> resident_on[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    int resident = resident_on[dev].load(std::memory_order_relaxed);
+    if (resident == 0) {
+        int cus = 0, per_cu = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_balanced<R>, kThreads,
+                                                             (a.max_batch + 1) * sizeof(int));
+        if (e != hipSuccess) return e;
+        if (cus < 1 || per_cu < 1) return hipErrorInvalidValue;
+        resident = cus * per_cu;
+        resident_on[dev].store(resident, std::memory_order_relaxed);
+    }
+    *out = resident;
+    return hipSuccess;
+}
+
+// demand != nullptr: nothing is launched; *demand receives the bytes of partial slots the
+// balanced launch would use with every resident wavefront taking a share.
+template <typename R>
+hipError_t launch_one(const DecodeArgs &a, hipStream_t s, size_t *demand)
 {
     const int G = a.num_q_heads / a.num_kv_heads;
     const int HC = a.num_kv_heads * (G / a.heads_per_pass);
     if (a.part_tokens > 0) {
+        if (demand) return hipErrorInvalidValue;
         const long long items = (long long)a.max_parts * HC * a.batch;
         dim3 grid((unsigned)((items + kWaves - 1) / kWaves));
         hipLaunchKernelGGL(decode_partial<R>, grid, dim3(kThreads), 0, s, a);
@@ -500,22 +530,18 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
         return hipGetLastError();
     }
     // balanced: as many workgroups as the chip holds at once for this kernel (fewer
-    // if the partial slots of that many wave shares would not fit the workspace)
-    static std::atomic<int> resident_once{0};         // per instantiation; one device per process
-    int resident = resident_once.load(std::memory_order_relaxed);
-    if (resident == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess)
-            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_balanced<R>, kThreads,
-                                                             (a.max_batch + 1) * sizeof(int));
-        if (e != hipSuccess) return e;
-        if (cus < 1 || per_cu < 1) return hipErrorInvalidValue;
-        resident = cus * per_cu;
-        resident_once.store(resident, std::memory_order_relaxed);   // every thread computes the same
+    // if the partial slots of that many wave shares would not fit behind a.partials)
+    int resident = 0;
+    hipError_t e = resident_workgroups<R>(a, &resident);
+    if (e != hipSuccess) return e;
+    const size_t per_share = decode_share_bytes(a.heads_per_pass, a.head_dim);
+    if (demand) {
+        *demand = (size_t)min(resident, kMaxShares / kWaves) * kWaves * per_share;
+        return hipSuccess;
     }
-    const int wgs = min(resident, decode_max_shares(a.heads_per_pass, a.head_dim) / kWaves);
+    const size_t fit = min((size_t)kMaxShares, a.partial_capacity / per_share);
+    const int wgs = min(resident, (int)(fit / kWaves));
+    if (wgs < 1) return hipErrorInvalidValue;
     const size_t lds = (size_t)(a.batch + 1) * sizeof(int);
     DecodeArgs b = a;
     b.share_gcd = b.share_inv = 0;                    // shares in launch order
@@ -534,7 +560,7 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
         b.share_inv = period > 1 ? (int)((t1 % period + period) % period) : 0;
     }
     hipLaunchKernelGGL(decode_balanced<R>, dim3(wgs), dim3(kThreads), lds, s, b);
-    hipError_t e = hipGetLastError();
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     // a batch so small that its ranges average 64 pieces and more: pieces in parallel
     const int P = wgs * kWaves;
@@ -551,28 +577,53 @@ hipError_t launch_one(const DecodeArgs &a, hipStream_t s)
 }
 
 template <bool BF16, int LPT>
-hipError_t launch_valu(const DecodeArgs &a, hipStream_t s)
+hipError_t launch_valu(const DecodeArgs &a, hipStream_t s, size_t *demand)
 {
     switch (a.heads_per_pass) {
-    case 1: return launch_one<ValuReducer<BF16, LPT, 1, kHalves>>(a, s);
+    case 1: return launch_one<ValuReducer<BF16, LPT, 1, kHalves>>(a, s, demand);
     case 2:
-        if constexpr (!BF16) return launch_one<ValuReducer<BF16, LPT, 2, kHalves>>(a, s);
+        if constexpr (!BF16) return launch_one<ValuReducer<BF16, LPT, 2, kHalves>>(a, s, demand);
         break;                                 // grouped bf16 heads take the MFMA path
     case 4:
-        if constexpr (!BF16) return launch_one<ValuReducer<BF16, LPT, 4, 1>>(a, s);
+        if constexpr (!BF16) return launch_one<ValuReducer<BF16, LPT, 4, 1>>(a, s, demand);
         break;
     }
     return hipErrorInvalidValue;
 }
 
 template <int D>
-hipError_t launch_mfma(const DecodeArgs &a, hipStream_t s)
+hipError_t launch_mfma(const DecodeArgs &a, hipStream_t s, size_t *demand)
 {
     if (a.heads_per_pass > 16) return hipErrorInvalidValue;
-    return launch_one<MfmaReducer<D>>(a, s);
+    return launch_one<MfmaReducer<D>>(a, s, demand);
+}
+
+// Picks the instantiation for the geometry; launches, or (demand != nullptr) only asks.
+hipError_t dispatch_impl(const DecodeArgs &a, hipStream_t stream, size_t *demand)
+{
+    const int G = a.num_q_heads / a.num_kv_heads;
+    if (a.heads_per_pass != decode_heads_per_pass(a.bf16, a.head_dim, G) || a.heads_per_pass == 0)
+        return hipErrorInvalidValue;
+    const int lpt = a.head_dim * (a.bf16 ? 2 : 4) / 16;
+    if (decode_uses_tiled_layout(a.bf16, G)) {
+        if (a.head_dim == 64) return launch_mfma<64>(a, stream, demand);
+        if (a.head_dim == 128) return launch_mfma<128>(a, stream, demand);
+        if (a.head_dim == 256) return launch_mfma<256>(a, stream, demand);
+    } else if (a.bf16) {
+        if (lpt == 8) return launch_valu<true, 8>(a, stream, demand);
+        if (lpt == 16) return launch_valu<true, 16>(a, stream, demand);
+        if (lpt == 32) return launch_valu<true, 32>(a, stream, demand);
+    } else {
+        if (lpt == 8) return launch_valu<false, 8>(a, stream, demand);
+        if (lpt == 16) return launch_valu<false, 16>(a, stream, demand);
+        if (lpt == 32) return launch_valu<false, 32>(a, stream, demand);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
+
+hipError_t dispatch(const DecodeArgs &a, hipStream_t stream, size_t *demand) { return dispatch_impl(a, stream, demand); }
 
 int decode_uses_tiled_layout(int bf16, int group) { return bf16 && group >= 2; }
 
@@ -590,10 +641,14 @@ int decode_heads_per_pass(int bf16, int head_dim, int group)
     return 1;
 }
 
+size_t decode_share_bytes(int heads_per_pass, int head_dim)
+{
+    return (size_t)2 * heads_per_pass * (head_dim + 2) * sizeof(float);
+}
+
 int decode_max_shares(int heads_per_pass, int head_dim)
 {
-    const size_t per_share = (size_t)2 * heads_per_pass * (head_dim + 2) * sizeof(float);
-    size_t n = kPartialBudget / per_share;
+    size_t n = kPartialBudget / decode_share_bytes(heads_per_pass, head_dim);
     if (n > (size_t)kMaxShares) n = kMaxShares;
     return (int)(n / kWaves) * kWaves;
 }
@@ -601,24 +656,96 @@ int decode_max_shares(int heads_per_pass, int head_dim)
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
 {
     if (a.batch == 0) return hipSuccess;
-    const int G = a.num_q_heads / a.num_kv_heads;
-    if (a.heads_per_pass != decode_heads_per_pass(a.bf16, a.head_dim, G) || a.heads_per_pass == 0)
-        return hipErrorInvalidValue;
-    const int lpt = a.head_dim * (a.bf16 ? 2 : 4) / 16;
-    if (decode_uses_tiled_layout(a.bf16, G)) {
-        if (a.head_dim == 64) return launch_mfma<64>(a, stream);
-        if (a.head_dim == 128) return launch_mfma<128>(a, stream);
-        if (a.head_dim == 256) return launch_mfma<256>(a, stream);
-    } else if (a.bf16) {
-        if (lpt == 8) return launch_valu<true, 8>(a, stream);
-        if (lpt == 16) return launch_valu<true, 16>(a, stream);
-        if (lpt == 32) return launch_valu<true, 32>(a, stream);
-    } else {
-        if (lpt == 8) return launch_valu<false, 8>(a, stream);
-        if (lpt == 16) return launch_valu<false, 16>(a, stream);
-        if (lpt == 32) return launch_valu<false, 32>(a, stream);
-    }
-    return hipErrorInvalidValue;
+    return dispatch(a, stream, nullptr);
 }
 
 }  // namespace lamps
+
+// ---------------------------------------------------------------- decode without a workspace
+//
+// The balanced scheme's scratch memory -- the partial slots of split ranges and one int4 per
+// share -- in a file-scope device array instead of the caller's workspace.  Every device the
+// library runs on holds its own copy of the array, at its own address, until the process ends.
+namespace {
+
+constexpr size_t kStaticPartialBytes = (size_t)LAMPS_STATIC_SCRATCH_BYTES - ((size_t)1 << 20);
+constexpr size_t kStaticInfoBytes = (size_t)(lamps::kMaxShares + 1) * sizeof(int4);
+static_assert(kStaticInfoBytes <= ((size_t)1 << 20), "share records must fit the last MiB");
+static_assert(kStaticPartialBytes % 256 == 0, "the share records start 256-byte aligned");
+
+static __device__ __align__(256) unsigned char scratch[LAMPS_STATIC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device.  The array's name is only a handle in host
+// code: the address comes from hipGetSymbolAddress, once per device, with that device current.
+hipError_t static_scratch(unsigned char **base)
+{
+    static std::atomic<unsigned char *> scratch_on[lamps::kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= lamps::kMaxDevices) return hipErrorInvalidDevice;
+    unsigned char *ptr = scratch_on[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        scratch_on[dev].store(ptr, std::memory_order_release);   // every thread finds the same address
+    }
+    *base = ptr;
+    return hipSuccess;
+}
+
+int static_fail(int code, const char *text)
+{
+    lamps::set_thread_error(text);
+    return code;
+}
+
+}  // namespace
+
+extern "C" int lamps_decode_attn_static(const lamps_config *cfg, void *compute_stream, int32_t layer,
+                                        int32_t batch, const void *q, const void *k_pool, const void *v_pool,
+                                        const int32_t *block_table, const int32_t *ctx_lens,
+                                        const uint8_t *running_mask, void *out)
+{
+    lamps::DecodeArgs a;
+    if (const char *why = lamps::decode_geometry(cfg, &a)) return static_fail(LAMPS_ERR_INVALID, why);
+    if (cfg->part_tokens != 0)
+        return static_fail(LAMPS_ERR_INVALID, "lamps_decode_attn_static: part_tokens must be 0 (balanced shares only)");
+    if (!q || !k_pool || !v_pool || !block_table || !ctx_lens || !running_mask || !out)
+        return static_fail(LAMPS_ERR_INVALID, "lamps_decode_attn_static: null argument");
+    if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)q | (uintptr_t)out) & 15)
+        return static_fail(LAMPS_ERR_INVALID, "lamps_decode_attn_static: pools, q and out must be 16-byte aligned");
+    if (layer < 0 || layer >= cfg->num_layers)
+        return static_fail(LAMPS_ERR_RANGE, "lamps_decode_attn_static: layer out of range");
+    if (batch < 0 || batch > cfg->max_batch)
+        return static_fail(LAMPS_ERR_RANGE, "lamps_decode_attn_static: batch out of range");
+    if (batch == 0) return LAMPS_OK;
+    unsigned char *base = nullptr;
+    hipError_t e = static_scratch(&base);
+    if (e != hipSuccess) return static_fail(LAMPS_ERR_HIP, hipGetErrorString(e));
+    a.q = q;
+    a.k_pool = k_pool;
+    a.v_pool = v_pool;
+    a.block_table = block_table;
+    a.ctx_lens = ctx_lens;
+    a.running = running_mask;
+    a.out = out;
+    a.batch = batch;
+    a.layer = layer;
+    a.partials = reinterpret_cast<float *>(base);
+    a.partial_capacity = kStaticPartialBytes;
+    a.share_info = reinterpret_cast<int4 *>(base + kStaticPartialBytes);
+    size_t demand = 0;
+    if ((e = lamps::dispatch(a, nullptr, &demand)) != hipSuccess)
+        return static_fail(LAMPS_ERR_HIP, hipGetErrorString(e));
+    if (demand > kStaticPartialBytes)
+        return static_fail(LAMPS_ERR_RANGE,
+                           "lamps_decode_attn_static: this geometry's partial slots (two records of heads per "
+                           "pass x (head_dim + 2) floats per resident wavefront) exceed the static scratch buffer");
+    // every launch writes the share record of every wavefront it starts and reads only those,
+    // and reads only the partial slots those records name: nothing has to start at zero
+    if ((e = lamps::dispatch(a, static_cast<hipStream_t>(compute_stream), nullptr)) != hipSuccess)
+        return static_fail(LAMPS_ERR_HIP, hipGetErrorString(e));
+    return LAMPS_OK;
+}

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "lamps.h"
+
 namespace lamps {
 
 struct DecodeArgs {
@@ -15,6 +17,7 @@ struct DecodeArgs {
     const uint8_t *running;      // [batch]
     float *partials;          // fixed partitions: [batch][H][max_parts][D + 2];
                               // balanced: [wave share][2][heads per pass][D + 2]
+    size_t partial_capacity;  // bytes behind partials (balanced: bounds the number of shares)
     int4 *share_info;         // balanced: [shares + 1] what each share leaves to the merge kernel
     void *out;                // [batch][H][D]
     int32_t batch, max_batch, layer, num_layers, num_q_heads, num_kv_heads, head_dim;
@@ -34,13 +37,24 @@ int decode_heads_per_pass(int bf16, int head_dim, int group);
 int decode_uses_tiled_layout(int bf16, int group);
 
 // Most wavefront shares the balanced scheme uses for a geometry (a multiple of
-// 4); its partials are [shares][2][heads_per_pass][head_dim + 2] floats.
+// 4); its partials are [shares][2][heads_per_pass][head_dim + 2] floats,
+// decode_share_bytes per share.
 int decode_max_shares(int heads_per_pass, int head_dim);
+size_t decode_share_bytes(int heads_per_pass, int head_dim);
+constexpr int kMaxDevices = 64;   // devices of one process the per-device tables cover
 
 // Enqueues one layer of decode attention.  part_tokens == 0 selects the balanced
 // scheme (then max_parts is ignored), part_tokens > 0 fixed partitions; either
 // way a small merge kernel follows unless no request can be split.
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
+// The same dispatch; with demand != nullptr nothing is launched and *demand receives the bytes
+// of partial slots a balanced launch uses when every resident wavefront takes a share.
+hipError_t dispatch(const DecodeArgs &a, hipStream_t stream, size_t *demand);
+// Validates cfg as lamps_create does and fills the geometry fields of *a (everything but the
+// pointers, batch, layer and partial_capacity).  Returns nullptr or an error text; allocates nothing.
+const char *decode_geometry(const lamps_config *cfg, DecodeArgs *a);
+// Sets the text lamps_last_error(NULL) returns on this thread (fixed buffer, no allocation).
+void set_thread_error(const char *text);
 
 struct AppendArgs {
     const void *k_new, *v_new;   // [batch][H_kv][D]

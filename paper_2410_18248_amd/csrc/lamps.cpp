@@ -23,7 +23,9 @@
 
 namespace {
 
-thread_local std::string g_create_error;
+// Error text of calls that have no context to keep it in (a failed lamps_create, the
+// workspace-free decode call): a fixed per-thread buffer, so that setting it allocates nothing.
+thread_local char g_thread_error[256] = "";
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -96,6 +98,11 @@ const char *derive(const lamps_config *c, Derived *d)
     return nullptr;
 }
 
+void thread_error(const char *a, const char *b = "")
+{
+    std::snprintf(g_thread_error, sizeof g_thread_error, "%s%s", a, b);
+}
+
 struct Ticket {
     hipEvent_t ev;
     size_t ring_slots;
@@ -134,11 +141,31 @@ struct lamps_ctx {
 
 namespace {
 
+void fill_geometry(const lamps_config &cfg, const Derived &d, lamps::DecodeArgs *pa)
+{
+    lamps::DecodeArgs &a = *pa;
+    a.max_batch = cfg.max_batch;
+    a.num_layers = cfg.num_layers;
+    a.num_q_heads = cfg.num_q_heads;
+    a.num_kv_heads = cfg.num_kv_heads;
+    a.head_dim = cfg.head_dim;
+    a.block_size = cfg.block_size;
+    a.log2_block_size = d.log2_bs;
+    a.max_blocks = cfg.max_blocks_per_req;
+    a.part_tokens = d.part_tokens;
+    a.max_parts = d.max_parts;
+    a.bf16 = cfg.dtype == LAMPS_BF16;
+    a.heads_per_pass = lamps::decode_heads_per_pass(a.bf16, a.head_dim, a.num_q_heads / a.num_kv_heads);
+    a.scale_log2e = d.scale_log2e;
+    a.share_gcd = a.share_inv = 0;
+}
+
 void fill_decode_args(lamps_ctx *c, lamps::DecodeArgs *pa, int32_t layer, int32_t batch, const void *q,
                       const int32_t *block_table, const int32_t *ctx_lens, const uint8_t *running_mask,
                       void *out)
 {
     lamps::DecodeArgs &a = *pa;
+    fill_geometry(c->cfg, c->d, pa);
     a.q = q;
     a.k_pool = c->k_pool;
     a.v_pool = c->v_pool;
@@ -146,23 +173,11 @@ void fill_decode_args(lamps_ctx *c, lamps::DecodeArgs *pa, int32_t layer, int32_
     a.ctx_lens = ctx_lens;
     a.running = running_mask;
     a.partials = c->partials;
+    a.partial_capacity = c->d.partial_bytes;
     a.share_info = c->share_info;
-    a.max_batch = c->cfg.max_batch;
     a.out = out;
     a.batch = batch;
     a.layer = layer;
-    a.num_layers = c->cfg.num_layers;
-    a.num_q_heads = c->cfg.num_q_heads;
-    a.num_kv_heads = c->cfg.num_kv_heads;
-    a.head_dim = c->cfg.head_dim;
-    a.block_size = c->cfg.block_size;
-    a.log2_block_size = c->d.log2_bs;
-    a.max_blocks = c->cfg.max_blocks_per_req;
-    a.part_tokens = c->d.part_tokens;
-    a.max_parts = c->d.max_parts;
-    a.bf16 = c->cfg.dtype == LAMPS_BF16;
-    a.heads_per_pass = lamps::decode_heads_per_pass(a.bf16, a.head_dim, a.num_q_heads / a.num_kv_heads);
-    a.scale_log2e = c->d.scale_log2e;
 }
 
 int fail(lamps_ctx *c, int code, const std::string &msg)
@@ -434,6 +449,21 @@ int swap_layered(lamps_ctx *c, bool out, char *host, const int32_t *block_ids, i
 
 }  // namespace
 
+namespace lamps {
+
+const char *decode_geometry(const lamps_config *cfg, DecodeArgs *a)
+{
+    Derived d;
+    if (const char *why = derive(cfg, &d)) return why;
+    *a = DecodeArgs{};
+    fill_geometry(*cfg, d, a);
+    return nullptr;
+}
+
+void set_thread_error(const char *text) { thread_error(text); }
+
+}  // namespace lamps
+
 extern "C" {
 
 size_t lamps_kv_bytes_per_token(const lamps_config *cfg)
@@ -475,25 +505,25 @@ int lamps_create(const lamps_config *cfg, void *k_pool, void *v_pool, void *work
 {
     Derived d;
     if (!out) {
-        g_create_error = "lamps_create: out is null";
+        thread_error("lamps_create: out is null");
         return LAMPS_ERR_INVALID;
     }
     *out = nullptr;
     if (const char *why = derive(cfg, &d)) {
-        g_create_error = std::string("lamps_create: ") + why;
+        thread_error("lamps_create: ", why);
         return LAMPS_ERR_INVALID;
     }
     if (!k_pool || !v_pool || !workspace) {
-        g_create_error = "lamps_create: k_pool, v_pool and workspace must be non-null";
+        thread_error("lamps_create: k_pool, v_pool and workspace must be non-null");
         return LAMPS_ERR_INVALID;
     }
     if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)workspace) & 15) {
-        g_create_error = "lamps_create: pools and workspace must be 16-byte aligned";
+        thread_error("lamps_create: pools and workspace must be 16-byte aligned");
         return LAMPS_ERR_INVALID;
     }
     lamps_ctx *c = new (std::nothrow) lamps_ctx();
     if (!c) {
-        g_create_error = "lamps_create: out of host memory";
+        thread_error("lamps_create: out of host memory");
         return LAMPS_ERR_NOMEM;
     }
     c->cfg = *cfg;
@@ -516,7 +546,7 @@ int lamps_create(const lamps_config *cfg, void *k_pool, void *v_pool, void *work
     c->in_guard.assign(nb, 0);
     c->mark.assign(nb, 0);
     *out = c;
-    g_create_error.clear();
+    g_thread_error[0] = 0;
     return LAMPS_OK;
 }
 
@@ -883,6 +913,6 @@ int lamps_num_free(lamps_ctx *c)
     return (int)c->free_stack.size();
 }
 
-const char *lamps_last_error(lamps_ctx *c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+const char *lamps_last_error(lamps_ctx *c) { return c ? c->err.c_str() : g_thread_error; }
 
 }  // extern "C"

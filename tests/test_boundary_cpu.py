@@ -174,3 +174,27 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "one MI355X" in r.stderr and r.stdout.strip() == ""
+
+
+def test_static_scratch_decode_checks_its_arguments_before_any_gpu_call():
+    """lamps_decode_attn_static: everything the host can see is refused before the device is
+    touched (this runs without a GPU), and the text comes back through lamps_last_error(NULL)."""
+    buf = ctypes.create_string_buffer(4096)
+    a = (ctypes.addressof(buf) + 255) & ~255                      # never dereferenced
+    ok = _cfg()
+
+    def call(cfg=ok, layer=0, batch=2, q=a, kp=a, vp=a, table=a, lens=a, mask=a, out=a):
+        P.lamps_decode_attn_static(cfg, 0, layer, batch, q, kp, vp, table, lens, mask, out)
+    for bad, status, word in ((dict(cfg=_cfg(head_dim=48)), -1, "head_dim"),
+                              (dict(cfg=_cfg(part_tokens=64)), -1, "part_tokens"),
+                              (dict(q=None), -1, "null"), (dict(vp=None), -1, "null"),
+                              (dict(kp=a + 8), -1, "aligned"),
+                              (dict(layer=2), -2, "layer"), (dict(layer=-1), -2, "layer"),
+                              (dict(batch=5), -2, "batch"), (dict(batch=-1), -2, "batch")):
+        with pytest.raises(P.LampsError) as e:
+            call(**bad)
+        assert e.value.status == status and word in str(e.value), (bad, str(e.value))
+    call(batch=0)                                                 # an empty batch is no work and no error
+    header = open(os.path.join(ROOT, "include", "lamps.h")).read()
+    m = re.search(r"#define\s+LAMPS_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", header)
+    assert m and (int(m.group(1)) << int(m.group(2))) == 33 << 20   # the stated, modest size
