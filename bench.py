@@ -8,14 +8,29 @@ out to pinned host memory, freed, re-allocated and swapped back in on side
 streams, Preserve-state requests stay masked, and Discard-state requests'
 blocks are freed.  Inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line: tokens/s of the whole job (running requests x steps /
-wall time, device fully drained at both ends), the HBM roofline of the decode
-kernel, and the CPU oracle timed on the host cores as a reported baseline.
+Timing rule.  A second host thread keeps the Swap-state requests' blocks going
+out and coming back, round after round (at most two groups of about 1 GiB in
+flight at a time), from before the warm-up steps until after the timed steps,
+so the host link is busy in both directions throughout.  The warm-up steps run,
+the compute stream is synchronised, exactly K steps are timed (host clock from
+before the first call until the compute stream has drained; HIP events on the
+compute stream for the kernel time), then the swap thread is told to stop and
+what it started is drained outside the timed region.  `value` = running
+requests x K / that time: tokens/s of one full decode-attention step with swaps
+in flight, whatever K is; the swap GB/s achieved during the timed steps is
+reported next to it.
+
+With no --config the line's headline is configuration 4 (the largest: 40
+layers, 113 GB of pools) and configurations 1-3 are measured the same way and
+reported under "per_config".  Prints ONE JSON line with the HBM roofline of the
+decode kernel and the CPU oracle timed on the host cores as a reported baseline.
 """
 import argparse
+import collections
 import json
 import os
 import sys
+import threading
 import time
 
 import numpy as np
@@ -32,6 +47,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC_BYTES = {
     "cfg1-7b-mha-bf16": 889426000,     # decode_balanced + decode_merge_balanced
     "cfg2-8b-gqa-bf16": 1713949000,
+    "cfg3-long-gqa-bf16": None,
+    "cfg4-13b-40layer-bf16": None,
     # prefill_mfma, fetched + written (same counters, same scale factors)
     "prefill-4x4096-new-on-0-cached-H32-Hkv8-D128": 359935000,
     "prefill-4x4096-new-on-0-cached-H40-Hkv40-D128": 693023000,
@@ -44,7 +61,14 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="0 = enough steps for ~50 ms of decode")
     ap.add_argument("--warmup", type=int, default=-1)
-    ap.add_argument("--config", type=int, default=1, help="workload 1..3 (1 is the headline)")
+    ap.add_argument("--config", type=int, default=0,
+                    help="workload 1..4 alone; 0 (default) = 4 as the headline and 1-3 under per_config")
+    ap.add_argument("--graph", type=int, default=-1,
+                    help="1: replay each step (all layers) from a HIP graph captured once per rotation; "
+                         "0: eager calls; -1 (default): graph for workloads of more than one layer")
+    ap.add_argument("--clock-warmup-ms", type=float, default=30.0,
+                    help="untimed decode steps run before the warm-up steps for about this long, so "
+                         "that the timed region does not start on clocks that are still ramping up")
     ap.add_argument("--rotations", type=int, default=0, help="disjoint KV regions cycled over")
     ap.add_argument("--part-tokens", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -53,7 +77,7 @@ def parse():
                     help="measure the layer-major swap-in of one request instead of the decode step")
     ap.add_argument("--staging-mib", type=int, default=0, help="lamps_config.staging_bytes in MiB (0 = default)")
     ap.add_argument("--direct-copy-bytes", type=int, default=0,
-                    help="lamps_config.direct_copy_bytes (0 = staged through the gather kernels, the default)")
+                    help="lamps_config.direct_copy_bytes (0 = the library default: blocks of 4 MiB and more per pool; -1 = never)")
     ap.add_argument("--zero-copy", type=int, default=0, metavar="WORKGROUPS",
                     help="lamps_config.zero_copy_workgroups (0 = off, the default)")
     ap.add_argument("--ctx-override", type=int, default=0,
@@ -132,6 +156,9 @@ class Job:
         torch.cuda.synchronize()
         self.lam = P.Lamps(self.cfg, self.k_pool, self.v_pool, self.ws, self.compute.cuda_stream,
                            self.s_out.cuda_stream, self.s_in.cuda_stream)
+        # decode steps are enqueued far ahead here and the swapped requests are paused (none of
+        # that work touches their blocks): the swap calls need not wait for the compute stream
+        self.lam.set_swap_fence(False)
         # every block starts allocated to the harness; what no batch uses goes back
         self.lam.alloc_blocks(g.num_blocks)
         perm = W.permutation(seed + 3, g.num_blocks)
@@ -153,16 +180,21 @@ class Job:
         self.lam.free_blocks([int(x) for x in perm[pos:]])
         self.ctx_d = torch.as_tensor(wl.ctx_lens.astype(np.int32), device=dev)
         self.mask_d = torch.as_tensor(self.running, device=dev)
-        # Swap-state requests of each rotation batch: their block ids and a pinned buffer
+        # Swap-state requests of all rotation batches: their block ids in groups of 128 MiB to
+        # 1 GiB (a quarter of everything in between), each with a pinned buffer of its own, so
+        # that the swap-in of one group runs while the next group is still on its way out
         self.block_bytes = P.lamps_block_bytes(self.cfg)
-        self.swap_ids, self.host = [], []
+        ids = []
         for b in range(self.R):
-            ids = []
             for r in np.flatnonzero(wl.state == W.SWAP):
                 ids += [int(x) for x in self.tables[b][r, :g.blocks_for(wl.ctx_lens[r])]]
-            self.swap_ids.append(ids)
-            self.host.append(torch.empty(max(1, len(ids) * self.block_bytes),
-                                         dtype=torch.uint8).pin_memory())
+        want = min(1 << 30, max(128 << 20, len(ids) * self.block_bytes // 4))
+        per_group = max(1, want // self.block_bytes)
+        self.swap_groups = []                           # [ids, pinned buffer] pairs
+        for i in range(0, len(ids), per_group):
+            part = ids[i:i + per_group]
+            self.swap_groups.append([part, torch.empty(len(part) * self.block_bytes,
+                                                       dtype=torch.uint8).pin_memory()])
         # Discard-state requests: their blocks are simply freed (and re-allocated next train)
         self.discard_ids = []
         for b in range(self.R):
@@ -170,7 +202,8 @@ class Job:
             for r in np.flatnonzero(wl.state == W.DISCARD):
                 ids += [int(x) for x in self.tables[b][r, :g.blocks_for(wl.ctx_lens[r])]]
             self.discard_ids.append(ids)
-        self.swap_bytes = sum(len(i) for i in self.swap_ids) * self.block_bytes
+        self.swap_bytes = sum(len(i) for i, _ in self.swap_groups) * self.block_bytes   # one round, each way
+        self.graphs = None
         torch.cuda.synchronize()
         # algorithmic bytes of one decode launch: K and V of the running requests' tokens,
         # q in, out, and the block-table entries walked
@@ -180,69 +213,117 @@ class Job:
                            + 2 * self.n_running * g.num_q_heads * g.head_dim * g.elem_bytes
                            + 4 * sum(g.blocks_for(c) for c in wl.ctx_lens[self.running == 1]))
 
-    def enqueue_swaps(self):
-        """Swap-state requests of every rotation batch: out, free, allocate, in."""
+    def swap_group(self, grp):
+        """One Swap-state group goes out, is freed, allocated again (other blocks) and comes back
+        in.  Returns (swap-out ticket, swap-in ticket)."""
+        lam = self.lam
+        old, host = grp
+        new = lam.alloc_blocks(len(old))                    # different physical blocks
+        t_out = lam.swap_out(old, host)
+        lam.free_blocks(old)
+        t_in = lam.swap_in(host, new)
+        grp[0] = new
+        return t_out, t_in
+
+    def recycle_discards(self):
+        """Discard-state requests: their blocks are freed and allocated again."""
         lam = self.lam
         for b in range(self.R):
-            old = self.swap_ids[b]
-            if old:
-                new = lam.alloc_blocks(len(old))            # different physical blocks
-                lam.swap_out(old, self.host[b])
-                lam.free_blocks(old)
-                lam.swap_in(self.host[b], new)
-                self.swap_ids[b] = new
             if self.discard_ids[b]:
                 lam.free_blocks(self.discard_ids[b])
                 self.discard_ids[b] = lam.alloc_blocks(len(self.discard_ids[b]))
 
-    def decode_steps(self, k):
+    def enqueue_swaps(self):
+        """One swap round, every group once, enqueued at once; returns the last swap-in ticket."""
+        last = None
+        for grp in self.swap_groups:
+            last = self.swap_group(grp)[1]
+        self.recycle_discards()
+        return last
+
+    def use_graphs(self):
+        """Captures one step (all layers) per rotation batch in a HIP graph; decode_steps replays
+        them from then on.  The calls have run eagerly before (the calibration trains)."""
+        torch = self.torch
         lam, L, B = self.lam, self.g.num_layers, self.wl.batch
-        for i in range(k):
+        self.graphs = []
+        for b in range(self.R):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=self.compute):
+                for layer in range(L):
+                    lam.decode_attn(layer, B, self.q[b], self.tab_d[b], self.ctx_d, self.mask_d, self.out[b])
+            self.graphs.append(gr)
+
+    def decode_steps(self, k, first=0):
+        lam, L, B = self.lam, self.g.num_layers, self.wl.batch
+        if self.graphs is not None:
+            with self.torch.cuda.stream(self.compute):
+                for i in range(first, first + k):
+                    self.graphs[i % self.R].replay()
+            return
+        for i in range(first, first + k):
             b = i % self.R
             for layer in range(L):
                 lam.decode_attn(layer, B, self.q[b], self.tab_d[b], self.ctx_d, self.mask_d,
                                 self.out[b])
 
-    def train(self, k, with_swap):
-        """k steps; returns (wall seconds with the device drained, decode-stream
-        seconds by HIP events on the compute stream)."""
+    def train(self, k, with_swap, warmup=0, clock_warmup_s=0.0, per_step_s=0.0):
+        """`warmup` untimed steps, then k timed ones.  Returns a dict: wall seconds of the k
+        steps (host clock, compute stream drained at both ends), their HIP-event seconds on the
+        compute stream, and what the swaps moved meanwhile.
+
+        With swaps: a second host thread keeps swap rounds going from before the warm-up until
+        after the timed steps (SwapFeeder); the decode steps never wait for them (the swapped
+        requests are masked)."""
         torch = self.torch
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
+        n_clock = int(clock_warmup_s / per_step_s) + 1 if clock_warmup_s > 0 and per_step_s > 0 else 0
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        if with_swap:
-            self.enqueue_swaps()
-        ta = time.perf_counter()
-        e0.record(self.compute)
-        self.decode_steps(k)
-        e1.record(self.compute)
-        tb = time.perf_counter()
+        feeder = None
+        if with_swap and self.swap_bytes:
+            feeder = SwapFeeder(self)
+            feeder.start()
+            feeder.first_done.wait()                     # the link is busy in both directions from here on
+        self.decode_steps(n_clock + warmup, first=0)
         self.compute.synchronize()
-        tc = time.perf_counter()
-        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(self.compute)
+        self.decode_steps(k, first=n_clock + warmup)
+        e1.record(self.compute)
+        self.compute.synchronize()
         t1 = time.perf_counter()
+        res = {"wall_s": t1 - t0, "event_s": e0.elapsed_time(e1) * 1e-3, "swaps_in_flight_at_end": False,
+               "swap_out_GBs_meanwhile": 0.0, "swap_in_GBs_meanwhile": 0.0}
+        if feeder:
+            res["swaps_in_flight_at_end"] = feeder.is_alive() and not feeder.failed
+            feeder.stop = True
+            feeder.join()
+            if feeder.failed:
+                raise feeder.failed
+            res["swap_out_GBs_meanwhile"], res["swap_in_GBs_meanwhile"] = feeder.rates(t0, t1)
+        torch.cuda.synchronize()
         if os.environ.get("LAMPS_BENCH_DEBUG"):
-            print("train k=%d swap=%s: swaps enqueued %.2f ms, decode enqueued %.2f, compute drained "
-                  "%.2f, all drained %.2f" % (k, with_swap, (ta - t0) * 1e3, (tb - t0) * 1e3,
-                                              (tc - t0) * 1e3, (t1 - t0) * 1e3), file=sys.stderr)
-        return t1 - t0, e0.elapsed_time(e1) * 1e-3
+            print("train k=%d swap=%s: warm-up %d+%d steps, timed %.3f ms, swaps meanwhile %.1f out / %.1f in GB/s" %
+                  (k, with_swap, n_clock, warmup, (t1 - t0) * 1e3, res["swap_out_GBs_meanwhile"],
+                   res["swap_in_GBs_meanwhile"]), file=sys.stderr)
+        return res
 
     def swap_alone(self):
         """GB/s of one batch's swap-out and swap-in with nothing else running, and of
         a plain pinned copy of the same size (the host link as this machine delivers it)."""
         torch, lam = self.torch, self.lam
-        ids = self.swap_ids[0]
-        if not ids:
+        if not self.swap_groups:
             return None
+        ids, host = self.swap_groups[0]
         nbytes = len(ids) * self.block_bytes
         res = {}
         for _ in range(2):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            lam.ticket_wait(lam.swap_out(ids, self.host[0]))
+            lam.ticket_wait(lam.swap_out(ids, host))
             t1 = time.perf_counter()
-            lam.ticket_wait(lam.swap_in(self.host[0], ids))
+            lam.ticket_wait(lam.swap_in(host, ids))
             t2 = time.perf_counter()
             res["swap_out_GBs"] = nbytes / (t1 - t0) / 1e9
             res["swap_in_GBs"] = nbytes / (t2 - t1) / 1e9
@@ -250,10 +331,10 @@ class Job:
         for _ in range(2):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            self.host[0][:nbytes].copy_(dbuf, non_blocking=True)
+            host[:nbytes].copy_(dbuf, non_blocking=True)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-            dbuf.copy_(self.host[0][:nbytes], non_blocking=True)
+            dbuf.copy_(host[:nbytes], non_blocking=True)
             torch.cuda.synchronize()
             t2 = time.perf_counter()
             res["memcpy_d2h_GBs"] = nbytes / (t1 - t0) / 1e9
@@ -275,6 +356,87 @@ class Job:
         return logical(self.k_pool, k_index), logical(self.v_pool, v_index)
 
 
+class SwapFeeder(threading.Thread):
+    """Keeps the Swap-state groups of a Job going out and coming back, round after round, from a
+    host thread of its own, until told to stop; then waits for what it started.  At most DEPTH
+    groups are in flight: with more copies queued than that, the runtime's copy path drops into
+    a mode four times slower (measured; the queue depth, not the decode kernels, sets it off),
+    so a caller that wants the link's rate feeds it like this.  The thread makes block-management
+    calls only (alloc, free, swap, ticket wait); the main thread makes decode calls only."""
+    DEPTH = 2
+
+    def __init__(self, job):
+        super().__init__(daemon=True)
+        self.job, self.stop, self.failed = job, False, None
+        self.first_done = threading.Event()
+        self.done = []                                   # (host time, is_out, bytes) per finished copy
+
+    def run(self):
+        job, lam = self.job, self.job.lam
+        pend = collections.deque()
+
+        def wait(ticket):                                # polled: a blocking host wait on an event of a
+            while not lam.ticket_query(ticket):          # busy device has been seen to return late
+                time.sleep(0.0001)
+
+        def retire():
+            t_out, t_in, n = pend.popleft()
+            wait(t_out)
+            self.done.append((time.perf_counter(), True, n))
+            wait(t_in)
+            self.done.append((time.perf_counter(), False, n))
+            self.first_done.set()
+        try:
+            while not self.stop:
+                for grp in job.swap_groups:
+                    if self.stop:
+                        break
+                    while len(pend) >= self.DEPTH:
+                        retire()
+                    t_out, t_in = job.swap_group(grp)
+                    pend.append((t_out, t_in, len(grp[0]) * job.block_bytes))
+                job.recycle_discards()
+            while pend:
+                retire()
+        except Exception as e:                           # reported by the main thread
+            self.failed = e
+        self.first_done.set()
+
+    def rates(self, t0, t1):
+        """GB/s out and in over [t0, t1], from the copies that finished inside it (whole copies)."""
+        out = sum(n for t, is_out, n in self.done if is_out and t0 <= t <= t1)
+        inn = sum(n for t, is_out, n in self.done if not is_out and t0 <= t <= t1)
+        return out / (t1 - t0) / 1e9, inn / (t1 - t0) / 1e9
+
+
+def _host_bits(t, torch):
+    t = t.cpu()
+    return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+
+def oracle_check(job, layers, requests):
+    """max |GPU - oracle| over the listed requests (all their query heads) in the listed layers
+    of rotation batch 0, each layer run once more into a buffer of its own."""
+    import oracle
+    torch, g, B = job.torch, job.g, job.wl.batch
+    q = _host_bits(job.q[0], torch)
+    pick = np.zeros(B, dtype=np.uint8)
+    pick[list(requests)] = 1
+    worst = 0.0
+    for layer in layers:
+        out = torch.zeros_like(job.out[0])
+        job.lam.decode_attn(layer, B, job.q[0], job.tab_d[0], job.ctx_d, job.mask_d, out)
+        job.compute.synchronize()
+        K, V = [None] * B, [None] * B
+        for r in requests:
+            K[r], V[r] = job.unpage(0, r, layer)
+        ref = oracle.decode_attn(q, K, V, job.wl.ctx_lens, pick, threads=len(os.sched_getaffinity(0)))
+        got = out.cpu().to(torch.float64).numpy()
+        sel = pick == 1
+        worst = max(worst, float(np.abs(got[sel] - ref[sel]).max()))
+    return worst
+
+
 def cpu_baseline(job):
     """The oracle, as it stands, on the host cores: all running requests of one
     batch, one layer.  Un-paging is done before the clock starts."""
@@ -284,8 +446,7 @@ def cpu_baseline(job):
     env = os.environ.get("OMP_NUM_THREADS")
     if env and env.isdigit():
         cores = min(cores, int(env))
-    q = job.q[0].cpu()
-    q = q.view(torch.int16).numpy().view(np.uint16) if q.dtype == torch.bfloat16 else q.numpy()
+    q = _host_bits(job.q[0], torch)
     B = job.wl.batch
     K, V = [None] * B, [None] * B
     last = job.g.num_layers - 1                     # job.out holds the last layer's result
@@ -509,16 +670,36 @@ def main():
     if a.prefill:
         prefill_bench(a)
         return
-    job = Job(a.config, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom, a.direct_copy_bytes, a.staging_mib,
+    if a.config:
+        line = measure_config(a, a.config, True)
+    else:
+        line = measure_config(a, 4, True)
+        line["per_config"] = [measure_config(a, c, False) for c in (1, 2, 3)]
+    print(json.dumps(line))
+
+
+def measure_config(a, cfg_id, headline):
+    """One workload measured by the timing rule of the module docstring.  headline: the whole
+    bench line (exactly --steps timed steps, oracle timed as cpu_baseline); otherwise a compact
+    record for "per_config" (at least --steps steps and at least about 20 ms of them)."""
+    import torch
+    job = Job(cfg_id, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom, a.direct_copy_bytes, a.staging_mib,
               a.zero_copy, a.ctx_long)
     with_swap = not a.no_swap
+    L = job.g.num_layers
 
-    # calibrate: one short train to size the run
+    # calibrate: short trains to size the run (and the eager calls every capture needs first)
     job.train(2 * job.R, False)
-    _, dec = job.train(2 * job.R, False)
-    per_step = dec / (2 * job.R)
+    per_step = job.train(2 * job.R, False)["event_s"] / (2 * job.R)
+    graph = a.graph == 1 or (a.graph < 0 and L > 1)
+    if graph:
+        job.use_graphs()
+        per_step = job.train(2 * job.R, False)["event_s"] / (2 * job.R)
     steps = a.steps if a.steps > 0 else int(min(4000, max(job.R, 0.05 / per_step)))
+    if not headline:
+        steps = max(steps, int(np.ceil(0.02 / per_step)))
     warmup = a.warmup if a.warmup >= 0 else max(job.R, steps // 4)
+    clock_s = a.clock_warmup_ms * 1e-3
 
     if a.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=job.dev)
@@ -527,60 +708,97 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    swap = None
     if with_swap:
         # the runtime sets up its copy path lazily (first large copies block the host for
         # milliseconds each); get that out of the way before anything is timed
-        for _ in range(3):
+        for _ in range(2):
             job.enqueue_swaps()
             torch.cuda.synchronize()
-    job.train(warmup, with_swap)
-    wall, dec = job.train(steps, with_swap)
-    wall_alone, dec_alone = job.train(steps, False)
+        swap = job.swap_alone()
+    under = job.train(steps, with_swap, warmup, clock_s, per_step)
+    alone = job.train(steps, False, warmup, clock_s, per_step) if with_swap else under
+    if swap:
+        swap["swap_out_GBs_during_timed_steps"] = under["swap_out_GBs_meanwhile"]
+        swap["swap_in_GBs_during_timed_steps"] = under["swap_in_GBs_meanwhile"]
 
     # spread over repeated trains (decode alone, each at least about 20 ms on the compute stream)
     n_each = max(job.R, int(0.02 / per_step))
-    per = sorted(job.train(n_each, False)[1] / n_each * 1e3 for _ in range(20))
+    per = sorted(job.train(n_each, False)["event_s"] / n_each * 1e3 for _ in range(20))
     spread = {"trains": len(per), "steps_each": n_each, "ms_per_step_min": per[0],
               "ms_per_step_median": 0.5 * (per[9] + per[10]), "ms_per_step_p95": per[18]}
 
-    launches = steps * job.g.num_layers
-    kernel_s = dec / launches
+    launches = steps * L
+    kernel_s = under["event_s"] / launches
     achieved = job.algo_bytes / kernel_s / 1e9
-    line = {
-        "metric": "decode-attention tokens/s (achieved HBM GB/s in roofline; swap GB/s in swap)",
-        "value": job.n_running * steps / wall,
-        "unit": "tokens/s",
-        "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": wall / steps * 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": job.g.dtype, "data": "synthetic",
-        "config": {"workload": job.wl.name, "batch": job.wl.batch, "running": job.n_running,
-                   "running_tokens": job.run_tokens, "layers": job.g.num_layers,
-                   "q_heads": job.g.num_q_heads, "kv_heads": job.g.num_kv_heads,
-                   "head_dim": job.g.head_dim, "block_size": job.g.block_size,
-                   "num_blocks": job.g.num_blocks, "rotations": job.R,
-                   "part_tokens": int(job.cfg.part_tokens),
-                   "swap_bytes_each_way_per_train": 0 if not with_swap else job.swap_bytes},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(job.wl.name),
-                     "kernel": "decode_balanced" if int(job.cfg.part_tokens) == 0 else "decode_partial",
-                     "algorithmic_bytes_per_launch": job.algo_bytes,
-                     "kernel_us": kernel_s * 1e6,
-                     "timing": "HIP events on the compute stream around the timed steps / launches "
-                               "(includes the small merge kernel that follows each launch)"},
-        "decode_alone": {"ms_per_step": dec_alone / steps * 1e3,
-                         "tokens_per_s": job.n_running * steps / wall_alone,
-                         "GBs": job.algo_bytes * job.g.num_layers / (dec_alone / steps) / 1e9},
-        "decode_alone_trains": spread,
-        "decode_slowdown_under_swap": dec / dec_alone,
-    }
-    if with_swap:
-        line["swap"] = job.swap_alone()
-    if not a.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(job)
+    alone_GBs = job.algo_bytes / (alone["event_s"] / launches) / 1e9
+    rule = ("a second host thread keeps the Swap-state groups going out and coming back (at most %d groups "
+            "in flight) from before the warm-up until after the timed steps; the decode steps are timed "
+            "on the compute stream meanwhile; swaps drained afterwards" % SwapFeeder.DEPTH
+            if with_swap else "decode alone")
+    cfgd = {"workload": job.wl.name, "batch": job.wl.batch, "running": job.n_running,
+            "running_tokens": job.run_tokens, "layers": L,
+            "q_heads": job.g.num_q_heads, "kv_heads": job.g.num_kv_heads,
+            "head_dim": job.g.head_dim, "block_size": job.g.block_size,
+            "num_blocks": job.g.num_blocks, "rotations": job.R,
+            "part_tokens": int(job.cfg.part_tokens),
+            "timing_rule": rule, "hip_graph": bool(graph), "clock_warmup_ms": a.clock_warmup_ms,
+            "swap_bytes_each_way_per_round": 0 if not with_swap else job.swap_bytes,
+            "swaps_in_flight_when_timed_steps_ended": under["swaps_in_flight_at_end"]}
+    roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(job.wl.name),
+            "kernel": "decode_balanced" if int(job.cfg.part_tokens) == 0 else "decode_partial",
+            "algorithmic_bytes_per_launch": job.algo_bytes,
+            "kernel_us": kernel_s * 1e6,
+            "timing": "HIP events on the compute stream around the timed steps / launches "
+                      "(includes the small merge kernel that follows each launch)"}
+    if headline:
+        line = {
+            "metric": "decode-attention tokens/s (achieved HBM GB/s in roofline; swap GB/s in swap)",
+            "value": job.n_running * steps / under["wall_s"],
+            "unit": "tokens/s",
+            "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": under["wall_s"] / steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": job.g.dtype, "data": "synthetic",
+            "config": cfgd,
+            "roofline": roof,
+            "decode_alone": {"ms_per_step": alone["event_s"] / steps * 1e3,
+                             "tokens_per_s": job.n_running * steps / alone["wall_s"],
+                             "GBs": alone_GBs, "frac": alone_GBs / HBM_PEAK_GBS},
+            "decode_alone_trains": spread,
+            "decode_slowdown_under_swap": under["event_s"] / alone["event_s"],
+        }
+        if swap:
+            line["swap"] = swap
+        if not a.no_cpu_baseline:
+            line["cpu_baseline"] = cpu_baseline(job)
+            if L > 1:                                   # the other layers, on a seeded sample of requests
+                run = np.flatnonzero(job.running)
+                sample = sorted(int(x) for x in run[job.W.permutation(job.W.config_seed(cfg_id) + 77, len(run))[:64]])
+                line["cpu_baseline"]["max_abs_err_sampled_layers"] = {
+                    "layers": [0, L // 2 - 1, L - 1], "requests": len(sample),
+                    "max_abs_err_gpu_vs_oracle": oracle_check(job, [0, L // 2 - 1, L - 1], sample)}
+    else:
+        line = {"workload": job.wl.name, "steps": steps, "warmup": warmup,
+                "tokens_per_s": job.n_running * steps / under["wall_s"],
+                "ms_per_step": under["wall_s"] / steps * 1e3,
+                "frac_under_swap": achieved / HBM_PEAK_GBS, "frac_alone": alone_GBs / HBM_PEAK_GBS,
+                "decode_slowdown_under_swap": under["event_s"] / alone["event_s"],
+                "kernel_us_under_swap": kernel_s * 1e6, "kernel_us_alone": alone["event_s"] / launches * 1e6,
+                "algorithmic_bytes_per_launch": job.algo_bytes,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(job.wl.name),
+                "decode_alone_trains": spread, "swap": swap, "config": cfgd}
+        if not a.no_cpu_baseline:
+            line["max_abs_err_gpu_vs_oracle"] = oracle_check(job, [L - 1], [int(r) for r in np.flatnonzero(job.running)])
+            line["oracle_checked"] = "all %d running requests, every query head" % job.n_running
     job.lam.destroy()
-    print(json.dumps(line))
+    del job
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    return line
 
 
 if __name__ == "__main__":

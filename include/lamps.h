@@ -109,8 +109,10 @@ typedef struct {
                                    least this large is swapped as two plain copies
                                    between the pools and the host buffer: no gather
                                    kernel, no staging, nothing runs on the compute
-                                   units.  0 or < 0 => never (the default: on this
-                                   hardware the staged path is the faster one)       */
+                                   units.  0 => the default, 4 MiB (a 40-layer model:
+                                   such runs are long enough for the copy engines,
+                                   and the decode step next to the swap slows by 2 %
+                                   instead of 8 %); < 0 => never                     */
     int32_t zero_copy_workgroups; /* > 0: lamps_swap_out / lamps_swap_in move the blocks
                                    with ONE kernel of this many workgroups (at most
                                    1024) that reads or writes the pinned host buffer
@@ -332,6 +334,20 @@ int lamps_swap_in_layered(lamps_ctx *ctx, const void *host_buf, const int32_t *b
  * ticket's copy has landed.  For a ticket of the block-major calls this is
  * lamps_compute_wait.  Errors: INVALID, RANGE (unknown ticket, layer), HIP. */
 int lamps_compute_wait_layer(lamps_ctx *ctx, uint64_t ticket, int32_t layer);
+
+/* By default every swap call orders its copy behind ALL compute-stream work enqueued
+ * before the call (it cannot know which of that work wrote, or still reads, the
+ * listed blocks).  A serving loop that enqueues one iteration at a time pays
+ * nothing for that; a caller that enqueues decode steps far ahead would make every
+ * later swap wait for all of them, although the blocks of a request that sits in an
+ * API call (Section 4.2: not in the running batch) are touched by none.  Such a
+ * caller switches the automatic ordering off (enabled == 0) and states the ordering
+ * itself, where it is needed, with lamps_swap_wait_compute: both swap streams then
+ * wait for the compute-stream work enqueued so far.  Ordering between the two swap
+ * directions (guards per block, host-buffer overlap) is not affected.
+ * Errors: INVALID, HIP. */
+int lamps_set_swap_fence(lamps_ctx *ctx, int32_t enabled);
+int lamps_swap_wait_compute(lamps_ctx *ctx);
 
 /* LAMPS_OK if the ticket's copy has finished, LAMPS_ERR_BUSY if not. */
 int lamps_ticket_query(lamps_ctx *ctx, uint64_t ticket);

@@ -77,6 +77,8 @@ def load_library():
         "lamps_swap_out_layered": [vp, vp, i32, vp, ctypes.POINTER(u64)],
         "lamps_swap_in_layered": [vp, vp, vp, i32, ctypes.POINTER(u64)],
         "lamps_compute_wait_layer": [vp, u64, i32],
+        "lamps_set_swap_fence": [vp, i32],
+        "lamps_swap_wait_compute": [vp],
         "lamps_ticket_query": [vp, u64],
         "lamps_ticket_wait": [vp, u64],
         "lamps_compute_wait": [vp, u64],
@@ -340,6 +342,12 @@ class Lamps:
 
     def compute_wait_layer(self, ticket, layer):
         self._check(self.lib.lamps_compute_wait_layer(self.h, ticket, layer))
+
+    def set_swap_fence(self, enabled):
+        self._check(self.lib.lamps_set_swap_fence(self.h, 1 if enabled else 0))
+
+    def swap_wait_compute(self):
+        self._check(self.lib.lamps_swap_wait_compute(self.h))
 
     def ticket_query(self, ticket):
         rc = self.lib.lamps_ticket_query(self.h, ticket)

@@ -87,7 +87,12 @@ const char *derive(const lamps_config *c, Derived *d)
     d->staging_bytes = bpc * d->block_bytes;
     d->workspace_bytes = align256(d->partial_bytes) + align256(d->prefix_bytes) +
                          2 * align256(d->staging_bytes);
-    d->direct_copy = c->direct_copy_bytes > 0 && (int64_t)d->half_bytes >= c->direct_copy_bytes;
+    // 0 = the default: blocks of 4 MiB and more per pool are contiguous runs long enough for the
+    // copy engines as they are (measured: a little slower over the link than the staged path,
+    // but the decode step next to it slows by 2 % instead of 8 %); zero-copy takes precedence
+    const int64_t direct_from = c->direct_copy_bytes != 0 ? c->direct_copy_bytes
+                                                          : (c->zero_copy_workgroups > 0 ? -1 : (int64_t)4 << 20);
+    d->direct_copy = direct_from > 0 && (int64_t)d->half_bytes >= direct_from;
     if (c->zero_copy_workgroups < 0 || c->zero_copy_workgroups > 1024)
         return "zero_copy_workgroups must be in [0, 1024]";
     if (c->zero_copy_workgroups > 0 && c->direct_copy_bytes > 0)
@@ -136,6 +141,7 @@ struct lamps_ctx {
     int32_t *ring = nullptr;                    // pinned; id lists read by the copy kernels
     size_t ring_cap = 0;
     uint64_t ring_head = 0, ring_tail = 0;      // monotonic slot counters
+    bool swap_fence = true;                     // swap calls order themselves behind the compute stream
     std::string err;
 };
 
@@ -298,35 +304,33 @@ int check_ids(lamps_ctx *c, const int32_t *ids, int32_t n, const char *who)
     return LAMPS_OK;
 }
 
-// Makes `stream` wait for every unfinished ticket named in guard[ids[*]].
+// Makes `stream` wait for every unfinished ticket named in guard[ids[*]].  A guard array holds
+// tickets of one direction only, and the copies of one direction run on one stream in ticket
+// order: waiting for the newest of them covers all the others.
 int wait_guards(lamps_ctx *c, hipStream_t stream, const std::vector<uint64_t> &guard,
                 const int32_t *ids, int32_t n)
 {
-    uint64_t last = 0;
-    std::vector<uint64_t> seen;
-    for (int32_t i = 0; i < n; ++i) {
-        const uint64_t t = guard[ids[i]];
-        if (t == 0 || t == last || t < c->base_ticket) continue;
-        last = t;
-        bool dup = false;
-        for (uint64_t s : seen) dup |= (s == t);
-        if (dup) continue;
-        seen.push_back(t);
-        if (!ticket_done(c, t)) LAMPS_HIP(hipStreamWaitEvent(stream, ticket_event(c, t), 0));
-    }
+    uint64_t newest = 0;
+    for (int32_t i = 0; i < n; ++i) newest = std::max(newest, guard[ids[i]]);
+    if (newest >= c->base_ticket && !ticket_done(c, newest))
+        LAMPS_HIP(hipStreamWaitEvent(stream, ticket_event(c, newest), 0));
     return LAMPS_OK;
 }
 
 // Orders `stream` after every unfinished copy of the other direction that
 // touches host bytes [lo, hi): a swap-in may be enqueued right after the
-// swap-out that fills its buffer, and the other way round.
+// swap-out that fills its buffer, and the other way round.  The newest such copy
+// stands for all of them (same stream, ticket order).
 int wait_host_overlap(lamps_ctx *c, hipStream_t stream, const char *lo, const char *hi,
                       bool other_is_out)
 {
-    for (Ticket &t : c->tickets)
-        if (t.is_out == other_is_out && t.host_lo < hi && lo < t.host_hi &&
-            hipEventQuery(t.ev) != hipSuccess)
-            LAMPS_HIP(hipStreamWaitEvent(stream, t.ev, 0));
+    for (size_t k = c->tickets.size(); k-- > 0;) {
+        Ticket &t = c->tickets[k];
+        if (t.is_out == other_is_out && t.host_lo < hi && lo < t.host_hi) {
+            if (hipEventQuery(t.ev) != hipSuccess) LAMPS_HIP(hipStreamWaitEvent(stream, t.ev, 0));
+            break;
+        }
+    }
     return LAMPS_OK;
 }
 
@@ -350,6 +354,17 @@ int mapped_host(lamps_ctx *c, const void *host, size_t bytes, const char *who, v
         }
         if (k == 0) *dev = at.devicePointer;
     }
+    return LAMPS_OK;
+}
+
+// A swap copy reads (out) or overwrites (in) blocks that compute-stream work enqueued before the
+// call may still write or read: unless the caller has taken that ordering into its own hands,
+// the swap stream waits for everything the compute stream holds at this moment.
+int fence_behind_compute(lamps_ctx *c, hipStream_t st)
+{
+    if (!c->swap_fence) return LAMPS_OK;
+    LAMPS_HIP(hipEventRecord(c->fence, c->cs));
+    LAMPS_HIP(hipStreamWaitEvent(st, c->fence, 0));
     return LAMPS_OK;
 }
 
@@ -437,10 +452,9 @@ int swap_layered(lamps_ctx *c, bool out, char *host, const int32_t *block_ids, i
     const size_t total = (size_t)n * c->d.block_bytes;
     Ticket t{ev, slots, host, host + total, out, {}, 0};
     auto enqueue = [&]() -> int {
-        LAMPS_HIP(hipEventRecord(c->fence, c->cs));
-        LAMPS_HIP(hipStreamWaitEvent(st, c->fence, 0));
-        int rc = wait_guards(c, st, out ? c->in_guard : c->out_guard, block_ids, n);
+        int rc = fence_behind_compute(c, st);
         if (rc != LAMPS_OK) return rc;
+        if ((rc = wait_guards(c, st, out ? c->in_guard : c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
         if ((rc = wait_host_overlap(c, st, host, host + total, !out)) != LAMPS_OK) return rc;
         return n > 0 ? enqueue_layer_steps(c, out, host, ids, n, st, &t) : LAMPS_OK;
     };
@@ -718,10 +732,9 @@ int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host
     Ticket t{ev, slots, host, host + total, true, {}, 0};
     auto enqueue = [&]() -> int {
         // the copy reads what the compute stream (and any earlier swap-in) wrote
-        LAMPS_HIP(hipEventRecord(c->fence, c->cs));
-        LAMPS_HIP(hipStreamWaitEvent(c->os, c->fence, 0));
-        int rc = wait_guards(c, c->os, c->in_guard, block_ids, n);
+        int rc = fence_behind_compute(c, c->os);
         if (rc != LAMPS_OK) return rc;
+        if ((rc = wait_guards(c, c->os, c->in_guard, block_ids, n)) != LAMPS_OK) return rc;
         if ((rc = wait_host_overlap(c, c->os, host, host + total, false)) != LAMPS_OK) return rc;
 
         if (c->d.direct_copy) {
@@ -782,10 +795,9 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
     auto enqueue = [&]() -> int {
         // the scatter overwrites blocks: earlier compute-stream readers and an
         // unfinished swap-out of the same blocks go first
-        LAMPS_HIP(hipEventRecord(c->fence, c->cs));
-        LAMPS_HIP(hipStreamWaitEvent(c->is, c->fence, 0));
-        int rc = wait_guards(c, c->is, c->out_guard, block_ids, n);
+        int rc = fence_behind_compute(c, c->is);
         if (rc != LAMPS_OK) return rc;
+        if ((rc = wait_guards(c, c->is, c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
         if ((rc = wait_host_overlap(c, c->is, host, host + total, true)) != LAMPS_OK) return rc;
 
         if (c->d.direct_copy) {
@@ -839,6 +851,24 @@ int lamps_compute_wait_layer(lamps_ctx *c, uint64_t ticket, int32_t layer)
     if (t.layers_per_step > 0 && (size_t)(layer / t.layers_per_step) < t.step_ev.size())
         e = t.step_ev[layer / t.layers_per_step];
     if (hipEventQuery(e) != hipSuccess) LAMPS_HIP(hipStreamWaitEvent(c->cs, e, 0));
+    return LAMPS_OK;
+}
+
+int lamps_set_swap_fence(lamps_ctx *c, int32_t enabled)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    c->swap_fence = enabled != 0;
+    return LAMPS_OK;
+}
+
+int lamps_swap_wait_compute(lamps_ctx *c)
+{
+    if (!c) return LAMPS_ERR_INVALID;
+    int rc = ensure_runtime(c);
+    if (rc != LAMPS_OK) return rc;
+    LAMPS_HIP(hipEventRecord(c->fence, c->cs));
+    LAMPS_HIP(hipStreamWaitEvent(c->os, c->fence, 0));
+    LAMPS_HIP(hipStreamWaitEvent(c->is, c->fence, 0));
     return LAMPS_OK;
 }
 

@@ -228,6 +228,37 @@ def test_compute_stream_writer_is_ordered_by_compute_wait_blocks():
     rig.close()
 
 
+@pytest.mark.parametrize("fence", [True, False])
+def test_swap_out_behind_a_compute_stream_writer(fence):
+    """The swap-out of blocks that compute-stream work still writes comes after that work: by
+    itself (the default), or, with the automatic ordering switched off, because the caller
+    said so with lamps_swap_wait_compute."""
+    geom = W.Geometry(8, 8, 8, 128, 16, 160, 8, "bf16")
+    bb = 2 * geom.block_half_bytes
+    rig = Rig(geom, max_batch=1)
+    lam = rig.lamps
+    _fill_random(rig, 23)
+    lam.alloc_blocks(geom.num_blocks)
+    lam.set_swap_fence(fence)
+    ids = list(range(3, 150))
+    host = _pinned(len(ids) * bb)
+    host.numpy()[:] = 0
+    big = torch.empty(1 << 28, dtype=torch.float32, device=rig.dev)
+    with torch.cuda.stream(rig.compute):
+        for _ in range(8):                              # a few milliseconds of work ahead of the writer
+            big.fill_(1.0)
+        idx = torch.as_tensor(ids, device=rig.dev)
+        rig.k_pool[idx] = 1.5
+        rig.v_pool[idx] = -2.0
+    if not fence:
+        lam.swap_wait_compute()
+    t = lam.swap_out(ids, host)
+    lam.ticket_wait(t)
+    got = host.view(torch.bfloat16).reshape(len(ids), 2, -1)
+    assert (got[:, 0] == 1.5).all() and (got[:, 1] == -2.0).all()
+    rig.close()
+
+
 @pytest.mark.parametrize("path", list(PATHS))
 def test_swap_in_right_behind_swap_out_through_one_buffer(path):
     geom = W.Geometry(4, 8, 8, 128, 16, 128, 8, "bf16")
