@@ -45,10 +45,10 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # each scaled by the same counter's reading for a plain 1 GiB copy: x2.0 and x1.0), keyed by
 # workload name; summaries in profiles/.  None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1-7b-mha-bf16": 889426000,     # decode_balanced + decode_merge_balanced
-    "cfg2-8b-gqa-bf16": 1713949000,
-    "cfg3-long-gqa-bf16": None,
-    "cfg4-13b-40layer-bf16": None,
+    "cfg1-7b-mha-bf16": 889187000,     # decode_balanced + decode_merge_balanced
+    "cfg2-8b-gqa-bf16": 1713836000,
+    "cfg3-long-gqa-bf16": 1546508000,
+    "cfg4-13b-40layer-bf16": 2177279000,   # per layer
     # prefill_mfma, fetched + written (same counters, same scale factors)
     "prefill-4x4096-new-on-0-cached-H32-Hkv8-D128": 359935000,
     "prefill-4x4096-new-on-0-cached-H40-Hkv40-D128": 693023000,

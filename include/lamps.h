@@ -29,10 +29,13 @@
  *     pointers are ordinary process memory unless marked pinned.
  *   - Arguments that live in device memory (block_table, ctx_lens,
  *     running_mask) are NOT validated: no call synchronises with the device.
- *     The kernels keep two mistakes harmless: a context length beyond
+ *     The kernels keep these mistakes harmless (no access outside the pools;
+ *     the affected rows are meaningless): a context length beyond
  *     max_blocks_per_req * block_size is clamped to the row by the decode
  *     kernels, and ignored (nothing read, nothing written) by the append and
- *     many-token calls, as is a context shorter than its new tokens.
+ *     many-token calls, as is a context shorter than its new tokens; a block
+ *     table entry outside [0, num_blocks) is not followed.
+ *     lamps_validate_args checks all of this on request (it synchronises).
  *   - A context is not thread-safe; calls on it must be serialised.
  *   - lamps_decode_attn, lamps_kv_append, lamps_kv_append_tokens and
  *     lamps_prefill_attn enqueue kernels on the compute stream and nothing else
@@ -176,6 +179,23 @@ int lamps_destroy(lamps_ctx *ctx);
 int lamps_decode_attn(lamps_ctx *ctx, int32_t layer, int32_t batch, const void *q,
                       const int32_t *block_table, const int32_t *ctx_lens,
                       const uint8_t *running_mask, void *out);
+
+/* A debug aid.  The calls above and below do not validate what lives in device
+ * memory; this one does, at the price of a host synchronisation: it runs a small
+ * kernel on the compute stream that reads block_table, ctx_lens and running_mask
+ * (nothing else; the pools are not touched) and waits for it.  A request is bad if
+ * its ctx_lens is negative or beyond max_blocks_per_req * block_size, or if it is
+ * running and a block-table entry its context uses lies outside [0, num_blocks).
+ * report (host, 4 ints, may be NULL): number of bad requests, the lowest bad
+ * request (-1 if none), what is wrong with it (1 = length, 2 = table entry), the
+ * offending value.
+ * Returns LAMPS_OK if every request is good, LAMPS_ERR_RANGE if not (the text names
+ * the first); errors: INVALID (null), RANGE (batch), HIP.
+ * (The decode and prefill kernels do not follow a table entry outside the pool --
+ * they read zeros, or the pool's last block, instead -- and clamp a length to the
+ * row; the affected rows of out are then meaningless, which is what this call finds.) */
+int lamps_validate_args(lamps_ctx *ctx, int32_t batch, const int32_t *block_table,
+                        const int32_t *ctx_lens, const uint8_t *running_mask, int32_t *report);
 
 /* ---- decode attention for callers that cannot allocate ---- */
 

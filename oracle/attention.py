@@ -17,12 +17,25 @@ _lib = None
 F32, BF16 = 0, 1
 
 
+_SANITIZE = os.environ.get("LAMPS_SANITIZE", "") not in ("", "0")
+if _SANITIZE:                                   # the sanitizer build lives apart from the normal one
+    _LIB = os.path.join(os.path.dirname(_HERE), "_build", "sanitize", "liblamps_oracle.so")
+
+
 def build(force=False):
-    """Compile the C oracle with gcc (plain -O2, OpenMP for the (r,h) loop)."""
+    """Compile the C oracle with gcc (plain -O2, OpenMP for the (r,h) loop).  With
+    LAMPS_SANITIZE=1: with clang, AddressSanitizer and UndefinedBehaviorSanitizer, one thread."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-             "-o", _LIB, _SRC, "-lm"])
+        if _SANITIZE:
+            os.makedirs(os.path.dirname(_LIB), exist_ok=True)
+            subprocess.check_call(
+                ["/opt/rocm/lib/llvm/bin/clang", "-O1", "-g", "-std=c99", "-fPIC", "-shared", "-Wall", "-Wextra",
+                 "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined",
+                 "-shared-libasan", "-fno-omit-frame-pointer", "-o", _LIB, _SRC, "-lm"])
+        else:
+            subprocess.check_call(
+                ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                 "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 

@@ -37,8 +37,13 @@ class LampsConfig(ctypes.Structure):
 
 
 def lib_path():
-    """The built library; LAMPS_LIBRARY overrides the in-tree path (to compare builds)."""
-    return os.environ.get("LAMPS_LIBRARY") or os.path.join(_HERE, "liblamps.so")
+    """The built library; LAMPS_LIBRARY overrides the in-tree path (to compare builds), and
+    LAMPS_SANITIZE=1 selects the sanitizer build of the host code (CPU container only)."""
+    if os.environ.get("LAMPS_LIBRARY"):
+        return os.environ["LAMPS_LIBRARY"]
+    if os.environ.get("LAMPS_SANITIZE", "") not in ("", "0"):
+        return os.path.join(os.path.dirname(_HERE), "_build", "sanitize", "liblamps.so")
+    return os.path.join(_HERE, "liblamps.so")
 
 
 def load_library():
@@ -46,12 +51,13 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
-    try:
-        # torch bundles its own HIP runtime under the same soname as /opt/rocm's; whichever is
-        # loaded first serves the whole process, and it has to be the one torch was built with
-        import torch  # noqa: F401
-    except ImportError:
-        pass
+    if os.environ.get("LAMPS_SANITIZE", "") in ("", "0"):
+        try:
+            # torch bundles its own HIP runtime under the same soname as /opt/rocm's; whichever is
+            # loaded first serves the whole process, and it has to be the one torch was built with
+            import torch  # noqa: F401
+        except ImportError:
+            pass
     path = lib_path()
     if not os.path.exists(path):
         raise ImportError("liblamps.so is not built: run `python -m paper_2410_18248_amd.build`")
@@ -69,6 +75,7 @@ def load_library():
         "lamps_destroy": [vp],
         "lamps_decode_attn": [vp, i32, i32, vp, vp, vp, vp, vp],
         "lamps_decode_attn_static": [cfgp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp],
+        "lamps_validate_args": [vp, i32, vp, vp, vp, vp],
         "lamps_kv_append": [vp, i32, i32, vp, vp, vp, vp, vp, i32],
         "lamps_kv_append_tokens": [vp, i32, i32, i32, vp, vp, vp, vp, vp],
         "lamps_prefill_attn": [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp],
@@ -309,6 +316,16 @@ class Lamps:
     def decode_attn(self, layer, batch, q, block_table, ctx_lens, running_mask, out):
         self._check(self.lib.lamps_decode_attn(self.h, layer, batch, _ptr(q), _ptr(block_table),
                                                _ptr(ctx_lens), _ptr(running_mask), _ptr(out)))
+
+    def validate_args(self, batch, block_table, ctx_lens, running_mask):
+        """Returns (bad requests, lowest bad request, reason, value); raises nothing for bad arguments."""
+        rep = (ctypes.c_int32 * 4)()
+        rc = self.lib.lamps_validate_args(self.h, batch, _ptr(block_table), _ptr(ctx_lens), _ptr(running_mask), rep)
+        if rc < 0 and rc != -2:
+            self._check(rc)
+        if rc == -2 and rep[0] == 0:
+            self._check(rc)                              # batch out of range
+        return tuple(rep)
 
     def kv_append(self, layer, batch, k_new, v_new, block_table, ctx_lens, running_mask, advance):
         self._check(self.lib.lamps_kv_append(self.h, layer, batch, _ptr(k_new), _ptr(v_new),

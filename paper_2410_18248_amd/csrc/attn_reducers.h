@@ -218,7 +218,10 @@ struct ValuReducer {
             uint4 kx[NL], vx[NL];
 #pragma unroll
             for (int f = 0; f < NH; ++f) {
-                if (pb[f] >= 0) {              // wave-uniform: half-chunks past the context are skipped
+                // wave-uniform: half-chunks past the context are skipped, and so is a table entry
+                // that does not name a block of the pool (the caller's mistake must not become a
+                // wild read; the row it belongs to is then meaningless)
+                if ((unsigned)pb[f] < (unsigned)a.num_blocks) {
                     const size_t off = (size_t)pb[f] * block_stride +
                                        (size_t)((t0 + f * HT) & (a.block_size - 1)) * D * ES;
                     if (t0 + (f + 1) * HT <= t_end) {
@@ -387,10 +390,20 @@ struct MfmaReducer {
             const int t = t_begin + c * CT;
             const size_t off = (size_t)block * block_stride +
                                (size_t)((t & (a.block_size - 1)) >> 4) * (16 * D * 2);
+            // (wave-uniform) a table entry that does not name a block of the pool is the caller's
+            // mistake; it must not become a wild read: the sub-tile counts as zeros and the row it
+            // belongs to is meaningless
+            if ((unsigned)block < (unsigned)a.num_blocks) {
 #pragma unroll
-            for (int i = 0; i < NK; ++i) kx[i] = load_stream16(kp + off + i * 1024);
+                for (int i = 0; i < NK; ++i) kx[i] = load_stream16(kp + off + i * 1024);
 #pragma unroll
-            for (int i = 0; i < NS; ++i) vx[i] = load_stream16(vp + off + i * 1024);
+                for (int i = 0; i < NS; ++i) vx[i] = load_stream16(vp + off + i * 1024);
+            } else {
+#pragma unroll
+                for (int i = 0; i < NK; ++i) kx[i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < NS; ++i) vx[i] = make_uint4(0, 0, 0, 0);
+            }
         };
         uint4 kx[NK], vx[NS], kn[NK], vn[NS];
         int ch = 0;

@@ -21,7 +21,7 @@ struct DecodeArgs {
     int4 *share_info;         // balanced: [shares + 1] what each share leaves to the merge kernel
     void *out;                // [batch][H][D]
     int32_t batch, max_batch, layer, num_layers, num_q_heads, num_kv_heads, head_dim;
-    int32_t block_size, log2_block_size, max_blocks, part_tokens, max_parts;
+    int32_t block_size, log2_block_size, max_blocks, num_blocks, part_tokens, max_parts;
     int32_t bf16;             // 0: fp32 storage, 1: bf16 storage
     int32_t heads_per_pass;   // query heads of a kv group that share one pass over K/V
     float scale_log2e;        // softmax scale * log2(e)
@@ -83,6 +83,16 @@ struct PrefillArgs {
 // Enqueues attention for the new tokens of every request over its paged cache, each token over
 // the positions up to and including its own.
 hipError_t launch_prefill(const PrefillArgs &a, hipStream_t stream);
+
+// Checks the device-resident arguments of a decode call: for every request r < batch, whether
+// ctx_lens[r] is negative or beyond the block-table row, and, for running requests, whether any
+// block-table entry its context uses lies outside [0, num_blocks).  result (device, 4 + 2 * batch
+// ints): [0] = number of bad requests, [1] = the lowest bad request index (or -1), [2] = what was
+// wrong with it (1 = length, 2 = table entry), [3] = the offending value; the rest is scratch.
+// Reads nothing but the three arrays.
+hipError_t launch_validate(const int32_t *block_table, const int32_t *ctx_lens, const uint8_t *running,
+                           int32_t batch, int32_t max_blocks, int32_t block_size, int32_t num_blocks,
+                           int32_t *result, hipStream_t stream);
 
 // Gather: staging image i (key bytes then value bytes of block ids[i]) <- pools.
 // Scatter: the reverse.  `half_bytes` = bytes of one block in one pool, a

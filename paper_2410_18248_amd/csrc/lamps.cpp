@@ -15,6 +15,7 @@
 #include <cstdio>
 #include <cstring>
 #include <deque>
+#include <memory>
 #include <new>
 #include <string>
 #include <vector>
@@ -31,7 +32,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Derived {
     size_t elem = 0, half_bytes = 0, block_bytes = 0, pool_bytes = 0;
-    size_t partial_bytes = 0, prefix_bytes = 0, staging_bytes = 0, workspace_bytes = 0;
+    size_t partial_bytes = 0, prefix_bytes = 0, aux_bytes = 0, staging_bytes = 0, workspace_bytes = 0;
     int part_tokens = 0, max_parts = 0, log2_bs = 0, blocks_per_chunk = 0;
     bool direct_copy = false;           // blocks are large enough to be copied one by one, unstaged
     int zero_copy = 0;                  // > 0: workgroups of the kernel that copies to / from host memory
@@ -85,7 +86,8 @@ const char *derive(const lamps_config *c, Derived *d)
     if (bpc > (size_t)c->num_blocks) bpc = c->num_blocks;
     d->blocks_per_chunk = (int)bpc;
     d->staging_bytes = bpc * d->block_bytes;
-    d->workspace_bytes = align256(d->partial_bytes) + align256(d->prefix_bytes) +
+    d->aux_bytes = (size_t)(4 + 2 * c->max_batch) * sizeof(int32_t);          // lamps_validate_args
+    d->workspace_bytes = align256(d->partial_bytes) + align256(d->prefix_bytes) + align256(d->aux_bytes) +
                          2 * align256(d->staging_bytes);
     // 0 = the default: blocks of 4 MiB and more per pool are contiguous runs long enough for the
     // copy engines as they are (measured: a little slower over the link than the staged path,
@@ -125,6 +127,7 @@ struct lamps_ctx {
     char *k_pool, *v_pool;
     float *partials;
     int4 *share_info;
+    int32_t *aux;                               // scratch of the argument checker
     char *stage_out, *stage_in;
     hipStream_t cs, os, is;
 
@@ -158,6 +161,7 @@ void fill_geometry(const lamps_config &cfg, const Derived &d, lamps::DecodeArgs 
     a.block_size = cfg.block_size;
     a.log2_block_size = d.log2_bs;
     a.max_blocks = cfg.max_blocks_per_req;
+    a.num_blocks = cfg.num_blocks;
     a.part_tokens = d.part_tokens;
     a.max_parts = d.max_parts;
     a.bf16 = cfg.dtype == LAMPS_BF16;
@@ -196,6 +200,15 @@ int hip_fail(lamps_ctx *c, const char *what, hipError_t e)
 {
     return fail(c, LAMPS_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
+
+// No exception crosses the C ABI: host containers may throw std::bad_alloc.  The texts are
+// short enough for the string's in-place buffer, so reporting them allocates nothing.
+#define LAMPS_CATCH(ctx)                                                             \
+    catch (const std::bad_alloc &) { return fail(ctx, LAMPS_ERR_NOMEM, "out of memory"); } \
+    catch (...) { return fail(ctx, LAMPS_ERR_INVALID, "C++ exception"); }
+#define LAMPS_CATCH_NOCTX                                                \
+    catch (const std::bad_alloc &) { thread_error("out of host memory"); return LAMPS_ERR_NOMEM; } \
+    catch (...) { thread_error("C++ exception"); return LAMPS_ERR_INVALID; }
 
 #define LAMPS_HIP(call)                                        \
     do {                                                       \
@@ -489,11 +502,14 @@ size_t lamps_kv_bytes_per_token(const lamps_config *cfg)
 
 int lamps_kv_layout(const lamps_config *cfg)
 {
-    Derived d;
-    if (derive(cfg, &d)) return LAMPS_ERR_INVALID;
-    return lamps::decode_uses_tiled_layout(cfg->dtype == LAMPS_BF16, cfg->num_q_heads / cfg->num_kv_heads)
-               ? LAMPS_LAYOUT_TILED
-               : LAMPS_LAYOUT_PLAIN;
+    try {
+        Derived d;
+        if (derive(cfg, &d)) return LAMPS_ERR_INVALID;
+        return lamps::decode_uses_tiled_layout(cfg->dtype == LAMPS_BF16, cfg->num_q_heads / cfg->num_kv_heads)
+                   ? LAMPS_LAYOUT_TILED
+                   : LAMPS_LAYOUT_PLAIN;
+    }
+    LAMPS_CATCH_NOCTX
 }
 
 size_t lamps_block_bytes(const lamps_config *cfg)
@@ -517,430 +533,519 @@ size_t lamps_workspace_bytes(const lamps_config *cfg)
 int lamps_create(const lamps_config *cfg, void *k_pool, void *v_pool, void *workspace,
                  void *compute_stream, void *swap_out_stream, void *swap_in_stream, lamps_ctx **out)
 {
-    Derived d;
-    if (!out) {
-        thread_error("lamps_create: out is null");
-        return LAMPS_ERR_INVALID;
+    try {
+        Derived d;
+        if (!out) {
+            thread_error("lamps_create: out is null");
+            return LAMPS_ERR_INVALID;
+        }
+        *out = nullptr;
+        if (const char *why = derive(cfg, &d)) {
+            thread_error("lamps_create: ", why);
+            return LAMPS_ERR_INVALID;
+        }
+        if (!k_pool || !v_pool || !workspace) {
+            thread_error("lamps_create: k_pool, v_pool and workspace must be non-null");
+            return LAMPS_ERR_INVALID;
+        }
+        if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)workspace) & 15) {
+            thread_error("lamps_create: pools and workspace must be 16-byte aligned");
+            return LAMPS_ERR_INVALID;
+        }
+        std::unique_ptr<lamps_ctx> c(new (std::nothrow) lamps_ctx());   // freed if a container below throws
+        if (!c) {
+            thread_error("lamps_create: out of host memory");
+            return LAMPS_ERR_NOMEM;
+        }
+        c->cfg = *cfg;
+        c->d = d;
+        c->k_pool = static_cast<char *>(k_pool);
+        c->v_pool = static_cast<char *>(v_pool);
+        char *ws = static_cast<char *>(workspace);
+        c->partials = reinterpret_cast<float *>(ws);
+        c->share_info = reinterpret_cast<int4 *>(ws + align256(d.partial_bytes));
+        c->aux = reinterpret_cast<int32_t *>(ws + align256(d.partial_bytes) + align256(d.prefix_bytes));
+        c->stage_out = ws + align256(d.partial_bytes) + align256(d.prefix_bytes) + align256(d.aux_bytes);
+        c->stage_in = c->stage_out + align256(d.staging_bytes);
+        c->cs = static_cast<hipStream_t>(compute_stream);
+        c->os = static_cast<hipStream_t>(swap_out_stream);
+        c->is = static_cast<hipStream_t>(swap_in_stream);
+        const int nb = cfg->num_blocks;
+        c->free_stack.resize(nb);
+        for (int i = 0; i < nb; ++i) c->free_stack[i] = nb - 1 - i;   // top of stack = id 0
+        c->allocated.assign(nb, 0);
+        c->out_guard.assign(nb, 0);
+        c->in_guard.assign(nb, 0);
+        c->mark.assign(nb, 0);
+        *out = c.release();
+        g_thread_error[0] = 0;
+        return LAMPS_OK;
     }
-    *out = nullptr;
-    if (const char *why = derive(cfg, &d)) {
-        thread_error("lamps_create: ", why);
-        return LAMPS_ERR_INVALID;
-    }
-    if (!k_pool || !v_pool || !workspace) {
-        thread_error("lamps_create: k_pool, v_pool and workspace must be non-null");
-        return LAMPS_ERR_INVALID;
-    }
-    if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)workspace) & 15) {
-        thread_error("lamps_create: pools and workspace must be 16-byte aligned");
-        return LAMPS_ERR_INVALID;
-    }
-    lamps_ctx *c = new (std::nothrow) lamps_ctx();
-    if (!c) {
-        thread_error("lamps_create: out of host memory");
-        return LAMPS_ERR_NOMEM;
-    }
-    c->cfg = *cfg;
-    c->d = d;
-    c->k_pool = static_cast<char *>(k_pool);
-    c->v_pool = static_cast<char *>(v_pool);
-    char *ws = static_cast<char *>(workspace);
-    c->partials = reinterpret_cast<float *>(ws);
-    c->share_info = reinterpret_cast<int4 *>(ws + align256(d.partial_bytes));
-    c->stage_out = ws + align256(d.partial_bytes) + align256(d.prefix_bytes);
-    c->stage_in = c->stage_out + align256(d.staging_bytes);
-    c->cs = static_cast<hipStream_t>(compute_stream);
-    c->os = static_cast<hipStream_t>(swap_out_stream);
-    c->is = static_cast<hipStream_t>(swap_in_stream);
-    const int nb = cfg->num_blocks;
-    c->free_stack.resize(nb);
-    for (int i = 0; i < nb; ++i) c->free_stack[i] = nb - 1 - i;   // top of stack = id 0
-    c->allocated.assign(nb, 0);
-    c->out_guard.assign(nb, 0);
-    c->in_guard.assign(nb, 0);
-    c->mark.assign(nb, 0);
-    *out = c;
-    g_thread_error[0] = 0;
-    return LAMPS_OK;
+    LAMPS_CATCH_NOCTX
 }
 
 int lamps_destroy(lamps_ctx *c)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    int rc = LAMPS_OK;
-    while (!c->tickets.empty()) {
-        if (hipEventSynchronize(c->tickets.front().ev) != hipSuccess) rc = LAMPS_ERR_HIP;
-        (void)hipEventDestroy(c->tickets.front().ev);
-        for (hipEvent_t e : c->tickets.front().step_ev) (void)hipEventDestroy(e);
-        c->tickets.pop_front();
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        int rc = LAMPS_OK;
+        while (!c->tickets.empty()) {
+            if (hipEventSynchronize(c->tickets.front().ev) != hipSuccess) rc = LAMPS_ERR_HIP;
+            (void)hipEventDestroy(c->tickets.front().ev);
+            for (hipEvent_t e : c->tickets.front().step_ev) (void)hipEventDestroy(e);
+            c->tickets.pop_front();
+        }
+        for (hipEvent_t e : c->spare_events) (void)hipEventDestroy(e);
+        if (c->fence) (void)hipEventDestroy(c->fence);
+        if (c->ring) (void)hipHostFree(c->ring);
+        delete c;
+        return rc;
     }
-    for (hipEvent_t e : c->spare_events) (void)hipEventDestroy(e);
-    if (c->fence) (void)hipEventDestroy(c->fence);
-    if (c->ring) (void)hipHostFree(c->ring);
-    delete c;
-    return rc;
+    LAMPS_CATCH(c)
 }
 
 int lamps_decode_attn(lamps_ctx *c, int32_t layer, int32_t batch, const void *q,
                       const int32_t *block_table, const int32_t *ctx_lens,
                       const uint8_t *running_mask, void *out)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!q || !block_table || !ctx_lens || !running_mask || !out)
-        return fail(c, LAMPS_ERR_INVALID, "lamps_decode_attn: null argument");
-    if (layer < 0 || layer >= c->cfg.num_layers)
-        return fail(c, LAMPS_ERR_RANGE, "lamps_decode_attn: layer out of range");
-    if (batch < 0 || batch > c->cfg.max_batch)
-        return fail(c, LAMPS_ERR_RANGE, "lamps_decode_attn: batch out of range");
-    if (batch == 0) return LAMPS_OK;
-    lamps::DecodeArgs a;
-    fill_decode_args(c, &a, layer, batch, q, block_table, ctx_lens, running_mask, out);
-    LAMPS_HIP(lamps::launch_decode(a, c->cs));
-    return LAMPS_OK;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!q || !block_table || !ctx_lens || !running_mask || !out)
+            return fail(c, LAMPS_ERR_INVALID, "lamps_decode_attn: null argument");
+        if (layer < 0 || layer >= c->cfg.num_layers)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_decode_attn: layer out of range");
+        if (batch < 0 || batch > c->cfg.max_batch)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_decode_attn: batch out of range");
+        if (batch == 0) return LAMPS_OK;
+        lamps::DecodeArgs a;
+        fill_decode_args(c, &a, layer, batch, q, block_table, ctx_lens, running_mask, out);
+        LAMPS_HIP(lamps::launch_decode(a, c->cs));
+        return LAMPS_OK;
+    }
+    LAMPS_CATCH(c)
+}
+
+int lamps_validate_args(lamps_ctx *c, int32_t batch, const int32_t *block_table, const int32_t *ctx_lens,
+                        const uint8_t *running_mask, int32_t *report)
+{
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!block_table || !ctx_lens || !running_mask)
+            return fail(c, LAMPS_ERR_INVALID, "lamps_validate_args: null argument");
+        if (batch < 0 || batch > c->cfg.max_batch)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_validate_args: batch out of range");
+        int32_t res[4] = {0, -1, 0, 0};
+        if (batch > 0) {
+            LAMPS_HIP(lamps::launch_validate(block_table, ctx_lens, running_mask, batch, c->cfg.max_blocks_per_req,
+                                             c->cfg.block_size, c->cfg.num_blocks, c->aux, c->cs));
+            LAMPS_HIP(hipMemcpyAsync(res, c->aux, sizeof res, hipMemcpyDeviceToHost, c->cs));
+            LAMPS_HIP(hipStreamSynchronize(c->cs));
+        }
+        if (report) std::memcpy(report, res, sizeof res);
+        if (res[0] == 0) return LAMPS_OK;
+        char text[160];
+        std::snprintf(text, sizeof text,
+                      res[2] == 1 ? "lamps_validate_args: %d bad request(s); request %d has context length %d"
+                                  : "lamps_validate_args: %d bad request(s); request %d uses block id %d",
+                      res[0], res[1], res[3]);
+        return fail(c, LAMPS_ERR_RANGE, text);
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_kv_append(lamps_ctx *c, int32_t layer, int32_t batch, const void *k_new,
                     const void *v_new, const int32_t *block_table, int32_t *ctx_lens,
                     const uint8_t *running_mask, int32_t advance)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!k_new || !v_new || !block_table || !ctx_lens || !running_mask)
-        return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append: null argument");
-    if (((uintptr_t)k_new | (uintptr_t)v_new) & 15)
-        return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append: k_new and v_new must be 16-byte aligned");
-    if (layer < 0 || layer >= c->cfg.num_layers)
-        return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append: layer out of range");
-    if (batch < 0 || batch > c->cfg.max_batch)
-        return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append: batch out of range");
-    if (batch == 0) return LAMPS_OK;
-    lamps::AppendArgs a;
-    a.k_new = k_new;
-    a.v_new = v_new;
-    a.k_pool = c->k_pool;
-    a.v_pool = c->v_pool;
-    a.block_table = block_table;
-    a.ctx_lens = ctx_lens;
-    a.running = running_mask;
-    a.q_start = nullptr;
-    a.batch = batch;
-    a.layer = layer;
-    a.num_layers = c->cfg.num_layers;
-    a.num_kv_heads = c->cfg.num_kv_heads;
-    a.head_dim = c->cfg.head_dim;
-    a.block_size = c->cfg.block_size;
-    a.log2_block_size = c->d.log2_bs;
-    a.max_blocks = c->cfg.max_blocks_per_req;
-    a.num_blocks = c->cfg.num_blocks;
-    a.bf16 = c->cfg.dtype == LAMPS_BF16;
-    a.advance = advance != 0;
-    const int tiled = lamps::decode_uses_tiled_layout(a.bf16, c->cfg.num_q_heads / c->cfg.num_kv_heads);
-    LAMPS_HIP(lamps::launch_kv_append(a, tiled, c->cs));
-    return LAMPS_OK;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!k_new || !v_new || !block_table || !ctx_lens || !running_mask)
+            return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append: null argument");
+        if (((uintptr_t)k_new | (uintptr_t)v_new) & 15)
+            return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append: k_new and v_new must be 16-byte aligned");
+        if (layer < 0 || layer >= c->cfg.num_layers)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append: layer out of range");
+        if (batch < 0 || batch > c->cfg.max_batch)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append: batch out of range");
+        if (batch == 0) return LAMPS_OK;
+        lamps::AppendArgs a;
+        a.k_new = k_new;
+        a.v_new = v_new;
+        a.k_pool = c->k_pool;
+        a.v_pool = c->v_pool;
+        a.block_table = block_table;
+        a.ctx_lens = ctx_lens;
+        a.running = running_mask;
+        a.q_start = nullptr;
+        a.batch = batch;
+        a.layer = layer;
+        a.num_layers = c->cfg.num_layers;
+        a.num_kv_heads = c->cfg.num_kv_heads;
+        a.head_dim = c->cfg.head_dim;
+        a.block_size = c->cfg.block_size;
+        a.log2_block_size = c->d.log2_bs;
+        a.max_blocks = c->cfg.max_blocks_per_req;
+        a.num_blocks = c->cfg.num_blocks;
+        a.bf16 = c->cfg.dtype == LAMPS_BF16;
+        a.advance = advance != 0;
+        const int tiled = lamps::decode_uses_tiled_layout(a.bf16, c->cfg.num_q_heads / c->cfg.num_kv_heads);
+        LAMPS_HIP(lamps::launch_kv_append(a, tiled, c->cs));
+        return LAMPS_OK;
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_kv_append_tokens(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t total_tokens,
                            const void *k_new, const void *v_new, const int32_t *q_start,
                            const int32_t *block_table, const int32_t *ctx_lens)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!k_new || !v_new || !q_start || !block_table || !ctx_lens)
-        return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append_tokens: null argument");
-    if (((uintptr_t)k_new | (uintptr_t)v_new) & 15)
-        return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append_tokens: k_new and v_new must be 16-byte aligned");
-    if (layer < 0 || layer >= c->cfg.num_layers)
-        return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append_tokens: layer out of range");
-    if (n_req < 0 || n_req > c->cfg.max_batch || total_tokens < 0)
-        return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append_tokens: n_req / total_tokens out of range");
-    if (n_req == 0 || total_tokens == 0) return LAMPS_OK;
-    lamps::AppendArgs a;
-    a.k_new = k_new;
-    a.v_new = v_new;
-    a.k_pool = c->k_pool;
-    a.v_pool = c->v_pool;
-    a.block_table = block_table;
-    a.ctx_lens = const_cast<int32_t *>(ctx_lens);     // the token form only reads it
-    a.running = nullptr;
-    a.q_start = q_start;
-    a.batch = n_req;
-    a.layer = layer;
-    a.num_layers = c->cfg.num_layers;
-    a.num_kv_heads = c->cfg.num_kv_heads;
-    a.head_dim = c->cfg.head_dim;
-    a.block_size = c->cfg.block_size;
-    a.log2_block_size = c->d.log2_bs;
-    a.max_blocks = c->cfg.max_blocks_per_req;
-    a.num_blocks = c->cfg.num_blocks;
-    a.bf16 = c->cfg.dtype == LAMPS_BF16;
-    a.advance = 0;
-    const int tiled = lamps::decode_uses_tiled_layout(a.bf16, c->cfg.num_q_heads / c->cfg.num_kv_heads);
-    LAMPS_HIP(lamps::launch_kv_append_tokens(a, total_tokens, tiled, c->cs));
-    return LAMPS_OK;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!k_new || !v_new || !q_start || !block_table || !ctx_lens)
+            return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append_tokens: null argument");
+        if (((uintptr_t)k_new | (uintptr_t)v_new) & 15)
+            return fail(c, LAMPS_ERR_INVALID, "lamps_kv_append_tokens: k_new and v_new must be 16-byte aligned");
+        if (layer < 0 || layer >= c->cfg.num_layers)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append_tokens: layer out of range");
+        if (n_req < 0 || n_req > c->cfg.max_batch || total_tokens < 0)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_kv_append_tokens: n_req / total_tokens out of range");
+        if (n_req == 0 || total_tokens == 0) return LAMPS_OK;
+        lamps::AppendArgs a;
+        a.k_new = k_new;
+        a.v_new = v_new;
+        a.k_pool = c->k_pool;
+        a.v_pool = c->v_pool;
+        a.block_table = block_table;
+        a.ctx_lens = const_cast<int32_t *>(ctx_lens);     // the token form only reads it
+        a.running = nullptr;
+        a.q_start = q_start;
+        a.batch = n_req;
+        a.layer = layer;
+        a.num_layers = c->cfg.num_layers;
+        a.num_kv_heads = c->cfg.num_kv_heads;
+        a.head_dim = c->cfg.head_dim;
+        a.block_size = c->cfg.block_size;
+        a.log2_block_size = c->d.log2_bs;
+        a.max_blocks = c->cfg.max_blocks_per_req;
+        a.num_blocks = c->cfg.num_blocks;
+        a.bf16 = c->cfg.dtype == LAMPS_BF16;
+        a.advance = 0;
+        const int tiled = lamps::decode_uses_tiled_layout(a.bf16, c->cfg.num_q_heads / c->cfg.num_kv_heads);
+        LAMPS_HIP(lamps::launch_kv_append_tokens(a, total_tokens, tiled, c->cs));
+        return LAMPS_OK;
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_prefill_attn(lamps_ctx *c, int32_t layer, int32_t n_req, int32_t total_tokens,
                        int32_t max_new_tokens, const void *q, const int32_t *q_start,
                        const int32_t *block_table, const int32_t *ctx_lens, void *out)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!q || !q_start || !block_table || !ctx_lens || !out)
-        return fail(c, LAMPS_ERR_INVALID, "lamps_prefill_attn: null argument");
-    if (((uintptr_t)q | (uintptr_t)out) & 15)
-        return fail(c, LAMPS_ERR_INVALID, "lamps_prefill_attn: q and out must be 16-byte aligned");
-    if (layer < 0 || layer >= c->cfg.num_layers)
-        return fail(c, LAMPS_ERR_RANGE, "lamps_prefill_attn: layer out of range");
-    if (n_req < 0 || n_req > c->cfg.max_batch || total_tokens < 0)
-        return fail(c, LAMPS_ERR_RANGE, "lamps_prefill_attn: n_req / total_tokens out of range");
-    if (n_req == 0 || total_tokens == 0) return LAMPS_OK;
-    lamps::PrefillArgs p;
-    fill_decode_args(c, &p.d, layer, n_req, q, block_table, ctx_lens, nullptr, out);
-    p.q_start = q_start;
-    p.total_tokens = total_tokens;
-    p.max_new_tokens = max_new_tokens > 0 && max_new_tokens < total_tokens ? max_new_tokens : total_tokens;
-    p.force_rows = max_new_tokens < 0;
-    LAMPS_HIP(lamps::launch_prefill(p, c->cs));
-    return LAMPS_OK;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!q || !q_start || !block_table || !ctx_lens || !out)
+            return fail(c, LAMPS_ERR_INVALID, "lamps_prefill_attn: null argument");
+        if (((uintptr_t)q | (uintptr_t)out) & 15)
+            return fail(c, LAMPS_ERR_INVALID, "lamps_prefill_attn: q and out must be 16-byte aligned");
+        if (layer < 0 || layer >= c->cfg.num_layers)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_prefill_attn: layer out of range");
+        if (n_req < 0 || n_req > c->cfg.max_batch || total_tokens < 0)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_prefill_attn: n_req / total_tokens out of range");
+        if (n_req == 0 || total_tokens == 0) return LAMPS_OK;
+        lamps::PrefillArgs p;
+        fill_decode_args(c, &p.d, layer, n_req, q, block_table, ctx_lens, nullptr, out);
+        p.q_start = q_start;
+        p.total_tokens = total_tokens;
+        p.max_new_tokens = max_new_tokens > 0 && max_new_tokens < total_tokens ? max_new_tokens : total_tokens;
+        p.force_rows = max_new_tokens < 0;
+        LAMPS_HIP(lamps::launch_prefill(p, c->cs));
+        return LAMPS_OK;
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host_buf,
                    uint64_t *ticket)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!ticket || (n > 0 && !host_buf))
-        return fail(c, LAMPS_ERR_INVALID, "lamps_swap_out: null argument");
-    int rc = check_ids(c, block_ids, n, "lamps_swap_out");
-    if (rc != LAMPS_OK) return rc;
-    void *host_dev = nullptr;
-    if (c->d.zero_copy &&
-        (rc = mapped_host(c, host_buf, (size_t)n * c->d.block_bytes, "lamps_swap_out", &host_dev)) != LAMPS_OK)
-        return rc;
-    if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
-    retire_finished(c);
-    int32_t *ids = nullptr;
-    size_t slots = 0;
-    if (!c->d.direct_copy) {                        // the gather kernel reads the ids from the pinned ring
-        if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
-        if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
-    }
-    hipEvent_t ev;
-    if ((rc = new_event(c, &ev)) != LAMPS_OK) {
-        c->ring_head -= slots;                      // nothing reads the reserved slots yet
-        return rc;
-    }
-
-    char *host = static_cast<char *>(host_buf);
-    const size_t total = (size_t)n * c->d.block_bytes;
-    Ticket t{ev, slots, host, host + total, true, {}, 0};
-    auto enqueue = [&]() -> int {
-        // the copy reads what the compute stream (and any earlier swap-in) wrote
-        int rc = fence_behind_compute(c, c->os);
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!ticket || (n > 0 && !host_buf))
+            return fail(c, LAMPS_ERR_INVALID, "lamps_swap_out: null argument");
+        int rc = check_ids(c, block_ids, n, "lamps_swap_out");
         if (rc != LAMPS_OK) return rc;
-        if ((rc = wait_guards(c, c->os, c->in_guard, block_ids, n)) != LAMPS_OK) return rc;
-        if ((rc = wait_host_overlap(c, c->os, host, host + total, false)) != LAMPS_OK) return rc;
-
-        if (c->d.direct_copy) {
-            // each block is two long contiguous runs: the copy engines take them as they are
-            for (int32_t i = 0; i < n; ++i) {
-                const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
-                LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes, c->k_pool + at, c->d.half_bytes,
-                                         hipMemcpyDeviceToHost, c->os));
-                LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes + c->d.half_bytes, c->v_pool + at,
-                                         c->d.half_bytes, hipMemcpyDeviceToHost, c->os));
-            }
-        } else if (c->d.zero_copy) {
-            LAMPS_HIP(lamps::launch_gather_host(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, host_dev,
-                                                c->d.zero_copy, c->os));
-        } else {
-            for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
-                const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
-                LAMPS_HIP(lamps::launch_gather(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
-                                               c->stage_out, c->os));
-                LAMPS_HIP(hipMemcpyAsync(host + (size_t)done * c->d.block_bytes, c->stage_out,
-                                         (size_t)cnt * c->d.block_bytes, hipMemcpyDeviceToHost, c->os));
-            }
+        void *host_dev = nullptr;
+        if (c->d.zero_copy &&
+            (rc = mapped_host(c, host_buf, (size_t)n * c->d.block_bytes, "lamps_swap_out", &host_dev)) != LAMPS_OK)
+            return rc;
+        if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
+        retire_finished(c);
+        int32_t *ids = nullptr;
+        size_t slots = 0;
+        if (!c->d.direct_copy) {                        // the gather kernel reads the ids from the pinned ring
+            if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
+            if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
         }
-        return LAMPS_OK;
-    };
-    return file_ticket(c, enqueue(), c->os, t, c->out_guard, block_ids, n, ticket);
+        hipEvent_t ev;
+        if ((rc = new_event(c, &ev)) != LAMPS_OK) {
+            c->ring_head -= slots;                      // nothing reads the reserved slots yet
+            return rc;
+        }
+
+        char *host = static_cast<char *>(host_buf);
+        const size_t total = (size_t)n * c->d.block_bytes;
+        Ticket t{ev, slots, host, host + total, true, {}, 0};
+        auto enqueue = [&]() -> int {
+            // the copy reads what the compute stream (and any earlier swap-in) wrote
+            int rc = fence_behind_compute(c, c->os);
+            if (rc != LAMPS_OK) return rc;
+            if ((rc = wait_guards(c, c->os, c->in_guard, block_ids, n)) != LAMPS_OK) return rc;
+            if ((rc = wait_host_overlap(c, c->os, host, host + total, false)) != LAMPS_OK) return rc;
+
+            if (c->d.direct_copy) {
+                // each block is two long contiguous runs: the copy engines take them as they are
+                for (int32_t i = 0; i < n; ++i) {
+                    const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
+                    LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes, c->k_pool + at, c->d.half_bytes,
+                                             hipMemcpyDeviceToHost, c->os));
+                    LAMPS_HIP(hipMemcpyAsync(host + (size_t)i * c->d.block_bytes + c->d.half_bytes, c->v_pool + at,
+                                             c->d.half_bytes, hipMemcpyDeviceToHost, c->os));
+                }
+            } else if (c->d.zero_copy) {
+                LAMPS_HIP(lamps::launch_gather_host(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, host_dev,
+                                                    c->d.zero_copy, c->os));
+            } else {
+                for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
+                    const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
+                    LAMPS_HIP(lamps::launch_gather(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                                   c->stage_out, c->os));
+                    LAMPS_HIP(hipMemcpyAsync(host + (size_t)done * c->d.block_bytes, c->stage_out,
+                                             (size_t)cnt * c->d.block_bytes, hipMemcpyDeviceToHost, c->os));
+                }
+            }
+            return LAMPS_OK;
+        };
+        return file_ticket(c, enqueue(), c->os, t, c->out_guard, block_ids, n, ticket);
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, int32_t n,
                   uint64_t *ticket)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!ticket || (n > 0 && !host_buf))
-        return fail(c, LAMPS_ERR_INVALID, "lamps_swap_in: null argument");
-    int rc = check_ids(c, block_ids, n, "lamps_swap_in");
-    if (rc != LAMPS_OK) return rc;
-    void *host_dev = nullptr;
-    if (c->d.zero_copy &&
-        (rc = mapped_host(c, host_buf, (size_t)n * c->d.block_bytes, "lamps_swap_in", &host_dev)) != LAMPS_OK)
-        return rc;
-    if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
-    retire_finished(c);
-    int32_t *ids = nullptr;
-    size_t slots = 0;
-    if (!c->d.direct_copy) {
-        if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
-        if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
-    }
-    hipEvent_t ev;
-    if ((rc = new_event(c, &ev)) != LAMPS_OK) {
-        c->ring_head -= slots;                      // nothing reads the reserved slots yet
-        return rc;
-    }
-
-    const char *host = static_cast<const char *>(host_buf);
-    const size_t total = (size_t)n * c->d.block_bytes;
-    Ticket t{ev, slots, host, host + total, false, {}, 0};
-    auto enqueue = [&]() -> int {
-        // the scatter overwrites blocks: earlier compute-stream readers and an
-        // unfinished swap-out of the same blocks go first
-        int rc = fence_behind_compute(c, c->is);
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!ticket || (n > 0 && !host_buf))
+            return fail(c, LAMPS_ERR_INVALID, "lamps_swap_in: null argument");
+        int rc = check_ids(c, block_ids, n, "lamps_swap_in");
         if (rc != LAMPS_OK) return rc;
-        if ((rc = wait_guards(c, c->is, c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
-        if ((rc = wait_host_overlap(c, c->is, host, host + total, true)) != LAMPS_OK) return rc;
-
-        if (c->d.direct_copy) {
-            for (int32_t i = 0; i < n; ++i) {
-                const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
-                LAMPS_HIP(hipMemcpyAsync(c->k_pool + at, host + (size_t)i * c->d.block_bytes, c->d.half_bytes,
-                                         hipMemcpyHostToDevice, c->is));
-                LAMPS_HIP(hipMemcpyAsync(c->v_pool + at, host + (size_t)i * c->d.block_bytes + c->d.half_bytes,
-                                         c->d.half_bytes, hipMemcpyHostToDevice, c->is));
-            }
-        } else if (c->d.zero_copy) {
-            LAMPS_HIP(lamps::launch_scatter_host(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, host_dev,
-                                                 c->d.zero_copy, c->is));
-        } else {
-            for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
-                const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
-                LAMPS_HIP(hipMemcpyAsync(c->stage_in, host + (size_t)done * c->d.block_bytes,
-                                         (size_t)cnt * c->d.block_bytes, hipMemcpyHostToDevice, c->is));
-                LAMPS_HIP(lamps::launch_scatter(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
-                                                c->stage_in, c->is));
-            }
+        void *host_dev = nullptr;
+        if (c->d.zero_copy &&
+            (rc = mapped_host(c, host_buf, (size_t)n * c->d.block_bytes, "lamps_swap_in", &host_dev)) != LAMPS_OK)
+            return rc;
+        if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
+        retire_finished(c);
+        int32_t *ids = nullptr;
+        size_t slots = 0;
+        if (!c->d.direct_copy) {
+            if ((rc = ring_reserve(c, n, &ids, &slots)) != LAMPS_OK) return rc;
+            if (n > 0) std::memcpy(ids, block_ids, (size_t)n * sizeof(int32_t));
         }
-        return LAMPS_OK;
-    };
-    return file_ticket(c, enqueue(), c->is, t, c->in_guard, block_ids, n, ticket);
+        hipEvent_t ev;
+        if ((rc = new_event(c, &ev)) != LAMPS_OK) {
+            c->ring_head -= slots;                      // nothing reads the reserved slots yet
+            return rc;
+        }
+
+        const char *host = static_cast<const char *>(host_buf);
+        const size_t total = (size_t)n * c->d.block_bytes;
+        Ticket t{ev, slots, host, host + total, false, {}, 0};
+        auto enqueue = [&]() -> int {
+            // the scatter overwrites blocks: earlier compute-stream readers and an
+            // unfinished swap-out of the same blocks go first
+            int rc = fence_behind_compute(c, c->is);
+            if (rc != LAMPS_OK) return rc;
+            if ((rc = wait_guards(c, c->is, c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
+            if ((rc = wait_host_overlap(c, c->is, host, host + total, true)) != LAMPS_OK) return rc;
+
+            if (c->d.direct_copy) {
+                for (int32_t i = 0; i < n; ++i) {
+                    const size_t at = (size_t)block_ids[i] * c->d.half_bytes;
+                    LAMPS_HIP(hipMemcpyAsync(c->k_pool + at, host + (size_t)i * c->d.block_bytes, c->d.half_bytes,
+                                             hipMemcpyHostToDevice, c->is));
+                    LAMPS_HIP(hipMemcpyAsync(c->v_pool + at, host + (size_t)i * c->d.block_bytes + c->d.half_bytes,
+                                             c->d.half_bytes, hipMemcpyHostToDevice, c->is));
+                }
+            } else if (c->d.zero_copy) {
+                LAMPS_HIP(lamps::launch_scatter_host(c->k_pool, c->v_pool, ids, n, c->d.half_bytes, host_dev,
+                                                     c->d.zero_copy, c->is));
+            } else {
+                for (int32_t done = 0; done < n; done += c->d.blocks_per_chunk) {
+                    const int32_t cnt = std::min<int32_t>(c->d.blocks_per_chunk, n - done);
+                    LAMPS_HIP(hipMemcpyAsync(c->stage_in, host + (size_t)done * c->d.block_bytes,
+                                             (size_t)cnt * c->d.block_bytes, hipMemcpyHostToDevice, c->is));
+                    LAMPS_HIP(lamps::launch_scatter(c->k_pool, c->v_pool, ids + done, cnt, c->d.half_bytes,
+                                                    c->stage_in, c->is));
+                }
+            }
+            return LAMPS_OK;
+        };
+        return file_ticket(c, enqueue(), c->is, t, c->in_guard, block_ids, n, ticket);
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_swap_out_layered(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host_buf, uint64_t *ticket)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    return swap_layered(c, true, static_cast<char *>(host_buf), block_ids, n, ticket, "lamps_swap_out_layered");
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        return swap_layered(c, true, static_cast<char *>(host_buf), block_ids, n, ticket, "lamps_swap_out_layered");
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_swap_in_layered(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, int32_t n,
                           uint64_t *ticket)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    return swap_layered(c, false, const_cast<char *>(static_cast<const char *>(host_buf)), block_ids, n, ticket,
-                        "lamps_swap_in_layered");
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        return swap_layered(c, false, const_cast<char *>(static_cast<const char *>(host_buf)), block_ids, n, ticket,
+                            "lamps_swap_in_layered");
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_compute_wait_layer(lamps_ctx *c, uint64_t ticket, int32_t layer)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_compute_wait_layer: unknown ticket");
-    if (layer < 0 || layer >= c->cfg.num_layers)
-        return fail(c, LAMPS_ERR_RANGE, "lamps_compute_wait_layer: layer out of range");
-    if (ticket_done(c, ticket)) return LAMPS_OK;
-    const Ticket &t = c->tickets[ticket - c->base_ticket];
-    hipEvent_t e = t.ev;
-    if (t.layers_per_step > 0 && (size_t)(layer / t.layers_per_step) < t.step_ev.size())
-        e = t.step_ev[layer / t.layers_per_step];
-    if (hipEventQuery(e) != hipSuccess) LAMPS_HIP(hipStreamWaitEvent(c->cs, e, 0));
-    return LAMPS_OK;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_compute_wait_layer: unknown ticket");
+        if (layer < 0 || layer >= c->cfg.num_layers)
+            return fail(c, LAMPS_ERR_RANGE, "lamps_compute_wait_layer: layer out of range");
+        if (ticket_done(c, ticket)) return LAMPS_OK;
+        const Ticket &t = c->tickets[ticket - c->base_ticket];
+        hipEvent_t e = t.ev;
+        if (t.layers_per_step > 0 && (size_t)(layer / t.layers_per_step) < t.step_ev.size())
+            e = t.step_ev[layer / t.layers_per_step];
+        if (hipEventQuery(e) != hipSuccess) LAMPS_HIP(hipStreamWaitEvent(c->cs, e, 0));
+        return LAMPS_OK;
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_set_swap_fence(lamps_ctx *c, int32_t enabled)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    c->swap_fence = enabled != 0;
-    return LAMPS_OK;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        c->swap_fence = enabled != 0;
+        return LAMPS_OK;
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_swap_wait_compute(lamps_ctx *c)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    int rc = ensure_runtime(c);
-    if (rc != LAMPS_OK) return rc;
-    LAMPS_HIP(hipEventRecord(c->fence, c->cs));
-    LAMPS_HIP(hipStreamWaitEvent(c->os, c->fence, 0));
-    LAMPS_HIP(hipStreamWaitEvent(c->is, c->fence, 0));
-    return LAMPS_OK;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        int rc = ensure_runtime(c);
+        if (rc != LAMPS_OK) return rc;
+        LAMPS_HIP(hipEventRecord(c->fence, c->cs));
+        LAMPS_HIP(hipStreamWaitEvent(c->os, c->fence, 0));
+        LAMPS_HIP(hipStreamWaitEvent(c->is, c->fence, 0));
+        return LAMPS_OK;
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_ticket_query(lamps_ctx *c, uint64_t ticket)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_ticket_query: unknown ticket");
-    return ticket_done(c, ticket) ? LAMPS_OK : LAMPS_ERR_BUSY;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_ticket_query: unknown ticket");
+        return ticket_done(c, ticket) ? LAMPS_OK : LAMPS_ERR_BUSY;
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_ticket_wait(lamps_ctx *c, uint64_t ticket)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_ticket_wait: unknown ticket");
-    if (ticket >= c->base_ticket) LAMPS_HIP(hipEventSynchronize(ticket_event(c, ticket)));
-    retire_finished(c);
-    return LAMPS_OK;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_ticket_wait: unknown ticket");
+        if (ticket >= c->base_ticket) LAMPS_HIP(hipEventSynchronize(ticket_event(c, ticket)));
+        retire_finished(c);
+        return LAMPS_OK;
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_compute_wait(lamps_ctx *c, uint64_t ticket)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_compute_wait: unknown ticket");
-    if (!ticket_done(c, ticket)) LAMPS_HIP(hipStreamWaitEvent(c->cs, ticket_event(c, ticket), 0));
-    return LAMPS_OK;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (!ticket_known(c, ticket)) return fail(c, LAMPS_ERR_RANGE, "lamps_compute_wait: unknown ticket");
+        if (!ticket_done(c, ticket)) LAMPS_HIP(hipStreamWaitEvent(c->cs, ticket_event(c, ticket), 0));
+        return LAMPS_OK;
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_compute_wait_blocks(lamps_ctx *c, const int32_t *block_ids, int32_t n)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    int rc = check_ids(c, block_ids, n, "lamps_compute_wait_blocks");
-    if (rc != LAMPS_OK) return rc;
-    if ((rc = wait_guards(c, c->cs, c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
-    return wait_guards(c, c->cs, c->in_guard, block_ids, n);
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        int rc = check_ids(c, block_ids, n, "lamps_compute_wait_blocks");
+        if (rc != LAMPS_OK) return rc;
+        if ((rc = wait_guards(c, c->cs, c->out_guard, block_ids, n)) != LAMPS_OK) return rc;
+        return wait_guards(c, c->cs, c->in_guard, block_ids, n);
+    }
+    LAMPS_CATCH(c)
 }
 
 int lamps_alloc_blocks(lamps_ctx *c, int32_t n, int32_t *block_ids_out)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    if (n < 0 || (n > 0 && !block_ids_out))
-        return fail(c, LAMPS_ERR_INVALID, "lamps_alloc_blocks: bad argument");
-    if ((size_t)n > c->free_stack.size())
-        return fail(c, LAMPS_ERR_NOMEM, "lamps_alloc_blocks: not enough free blocks");
-    for (int32_t i = 0; i < n; ++i) {
-        block_ids_out[i] = c->free_stack.back();
-        c->free_stack.pop_back();
-        c->allocated[block_ids_out[i]] = 1;
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        if (n < 0 || (n > 0 && !block_ids_out))
+            return fail(c, LAMPS_ERR_INVALID, "lamps_alloc_blocks: bad argument");
+        if ((size_t)n > c->free_stack.size())
+            return fail(c, LAMPS_ERR_NOMEM, "lamps_alloc_blocks: not enough free blocks");
+        for (int32_t i = 0; i < n; ++i) {
+            block_ids_out[i] = c->free_stack.back();
+            c->free_stack.pop_back();
+            c->allocated[block_ids_out[i]] = 1;
+        }
+        // A popped block may still be the source of an unfinished swap-out.  Its
+        // guard stays in place: lamps_swap_in orders itself behind it, and a caller
+        // that writes the block from the compute stream asks for the same with
+        // lamps_compute_wait_blocks.  Nothing is made to wait here, so decode steps
+        // of other requests keep running while the copy drains.
+        return LAMPS_OK;
     }
-    // A popped block may still be the source of an unfinished swap-out.  Its
-    // guard stays in place: lamps_swap_in orders itself behind it, and a caller
-    // that writes the block from the compute stream asks for the same with
-    // lamps_compute_wait_blocks.  Nothing is made to wait here, so decode steps
-    // of other requests keep running while the copy drains.
-    return LAMPS_OK;
+    LAMPS_CATCH(c)
 }
 
 int lamps_free_blocks(lamps_ctx *c, const int32_t *block_ids, int32_t n)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    int rc = check_ids(c, block_ids, n, "lamps_free_blocks");
-    if (rc != LAMPS_OK) return rc;
-    for (int32_t i = 0; i < n; ++i) {
-        c->allocated[block_ids[i]] = 0;
-        c->free_stack.push_back(block_ids[i]);
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        int rc = check_ids(c, block_ids, n, "lamps_free_blocks");
+        if (rc != LAMPS_OK) return rc;
+        for (int32_t i = 0; i < n; ++i) {
+            c->allocated[block_ids[i]] = 0;
+            c->free_stack.push_back(block_ids[i]);
+        }
+        return LAMPS_OK;
     }
-    return LAMPS_OK;
+    LAMPS_CATCH(c)
 }
 
 int lamps_num_free(lamps_ctx *c)
 {
-    if (!c) return LAMPS_ERR_INVALID;
-    return (int)c->free_stack.size();
+    try {
+        if (!c) return LAMPS_ERR_INVALID;
+        return (int)c->free_stack.size();
+    }
+    LAMPS_CATCH(c)
 }
 
 const char *lamps_last_error(lamps_ctx *c) { return c ? c->err.c_str() : g_thread_error; }

@@ -219,10 +219,12 @@ __global__ __launch_bounds__(kThreads, (D >= 256 && kCols <= 16) ? 2 : 1) void p
     // looked up one iteration before the loads that use them so that nobody waits for them.
     uint32_t ent[2 * GRP];
     const uint32_t last_entry = (uint32_t)wg_maxpos >> a.log2_block_size;   // nothing past it is looked up
+    const uint32_t last_block = (uint32_t)a.num_blocks - 1;
     auto lookup = [&](int grp) {
         const uint32_t t0 = (uint32_t)(grp * GRP * kStage);
 #pragma unroll
-        for (int i = 0; i < 2 * GRP; ++i) ent[i] = (uint32_t)table[min((t0 + 16 * i) >> a.log2_block_size, last_entry)];
+        for (int i = 0; i < 2 * GRP; ++i)               // (an entry that names no block of the pool is the caller's
+            ent[i] = min((uint32_t)table[min((t0 + 16 * i) >> a.log2_block_size, last_entry)], last_block);   // mistake: it reads the last block instead of memory outside the pools)
     };
     // This lane's part of a load's address: unit x of a sub-tile as it lies in the pool goes to
     // LDS slot x (tiled layout), or, plain layout (rows of NU units, which cannot be padded on the

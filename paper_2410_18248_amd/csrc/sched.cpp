@@ -59,6 +59,12 @@ int64_t ramp(int64_t base, int64_t n) { return n * base + n * (n + 1) / 2; }
 
 }  // namespace
 
+// No exception crosses the C ABI: the request table, the queues and the maps may throw
+// std::bad_alloc.
+#define LAMPS_SCHED_CATCH                                   \
+    catch (const std::bad_alloc &) { return LAMPS_ERR_NOMEM; } \
+    catch (...) { return LAMPS_ERR_INVALID; }
+
 struct lamps_sched {
     lamps_sched_config cfg;
     std::vector<Req> reqs;              // sorted by (arrival, id) once the first batch is formed
@@ -185,313 +191,334 @@ double lamps_memory_over_time(int strategy, int64_t c0, int64_t n1, double t_int
 
 int lamps_sched_create(const lamps_sched_config *cfg, lamps_sched **out)
 {
-    if (!cfg || !out) return LAMPS_ERR_INVALID;
-    *out = nullptr;
-    if (cfg->policy < LAMPS_POLICY_FCFS || cfg->policy > LAMPS_POLICY_FIXED || cfg->max_batch < 1 ||
-        cfg->memory_tokens < 1 || cfg->starvation_threshold < 1 || cfg->score_refresh < 1 ||
-        cfg->recompute_chunk < 1 || !(cfg->c_other >= 0) || !(cfg->bytes_per_token > 0))
-        return LAMPS_ERR_INVALID;
-    if (!cfg->cost.unit && !(cfg->cost.it_a + cfg->cost.it_b > 0)) return LAMPS_ERR_INVALID;
-    lamps_sched *s = new (std::nothrow) lamps_sched();
-    if (!s) return LAMPS_ERR_NOMEM;
-    s->cfg = *cfg;
-    *out = s;
-    return LAMPS_OK;
+    try {
+        if (!cfg || !out) return LAMPS_ERR_INVALID;
+        *out = nullptr;
+        if (cfg->policy < LAMPS_POLICY_FCFS || cfg->policy > LAMPS_POLICY_FIXED || cfg->max_batch < 1 ||
+            cfg->memory_tokens < 1 || cfg->starvation_threshold < 1 || cfg->score_refresh < 1 ||
+            cfg->recompute_chunk < 1 || !(cfg->c_other >= 0) || !(cfg->bytes_per_token > 0))
+            return LAMPS_ERR_INVALID;
+        if (!cfg->cost.unit && !(cfg->cost.it_a + cfg->cost.it_b > 0)) return LAMPS_ERR_INVALID;
+        lamps_sched *s = new (std::nothrow) lamps_sched();
+        if (!s) return LAMPS_ERR_NOMEM;
+        s->cfg = *cfg;
+        *out = s;
+        return LAMPS_OK;
+    }
+    LAMPS_SCHED_CATCH
 }
 
 int lamps_sched_destroy(lamps_sched *s)
 {
-    if (!s) return LAMPS_ERR_INVALID;
-    delete s;
-    return LAMPS_OK;
+    try {
+        if (!s) return LAMPS_ERR_INVALID;
+        delete s;
+        return LAMPS_OK;
+    }
+    LAMPS_SCHED_CATCH
 }
 
 int lamps_sched_add(lamps_sched *s, int64_t id, double arrival, int32_t prompt_tokens,
                     const lamps_segment *segments, int32_t n_segments, double priority)
 {
-    if (!s || !segments || n_segments < 1 || prompt_tokens < 0 || s->batch_pending) return LAMPS_ERR_INVALID;
-    for (int32_t k = 0; k < n_segments; ++k) {
-        const bool last = k == n_segments - 1;
-        if (segments[k].n_out < 1 || segments[k].api_response < 0) return LAMPS_ERR_INVALID;
-        if (last != (segments[k].api_duration < 0)) return LAMPS_ERR_INVALID;
-        if (segments[k].handling < LAMPS_HANDLING_AUTO || segments[k].handling > LAMPS_SWAP)
-            return LAMPS_ERR_INVALID;
+    try {
+        if (!s || !segments || n_segments < 1 || prompt_tokens < 0 || s->batch_pending) return LAMPS_ERR_INVALID;
+        for (int32_t k = 0; k < n_segments; ++k) {
+            const bool last = k == n_segments - 1;
+            if (segments[k].n_out < 1 || segments[k].api_response < 0) return LAMPS_ERR_INVALID;
+            if (last != (segments[k].api_duration < 0)) return LAMPS_ERR_INVALID;
+            if (segments[k].handling < LAMPS_HANDLING_AUTO || segments[k].handling > LAMPS_SWAP)
+                return LAMPS_ERR_INVALID;
+        }
+        if (s->by_id.count(id)) return LAMPS_ERR_DUP;
+        if (s->sorted && arrival < s->now) return LAMPS_ERR_INVALID;    // no arrivals in the past
+        Req r;
+        r.id = id;
+        r.arrival = arrival;
+        r.priority = priority;
+        r.prompt = prompt_tokens;
+        r.seg.assign(segments, segments + n_segments);
+        r.pending_recompute = prompt_tokens;
+        s->reqs.push_back(std::move(r));
+        s->by_id[id] = s->reqs.size() - 1;
+        s->sorted = false;
+        return LAMPS_OK;
     }
-    if (s->by_id.count(id)) return LAMPS_ERR_DUP;
-    if (s->sorted && arrival < s->now) return LAMPS_ERR_INVALID;    // no arrivals in the past
-    Req r;
-    r.id = id;
-    r.arrival = arrival;
-    r.priority = priority;
-    r.prompt = prompt_tokens;
-    r.seg.assign(segments, segments + n_segments);
-    r.pending_recompute = prompt_tokens;
-    s->reqs.push_back(std::move(r));
-    s->by_id[id] = s->reqs.size() - 1;
-    s->sorted = false;
-    return LAMPS_OK;
+    LAMPS_SCHED_CATCH
 }
 
 int lamps_sched_next_batch(lamps_sched *s, lamps_batch_entry *out, int32_t cap, int32_t *n)
 {
-    if (!s || !out || !n || s->batch_pending) return LAMPS_ERR_INVALID;
-    if (cap < s->cfg.max_batch) return LAMPS_ERR_RANGE;
-    if (!s->sorted) {
-        // (re)establish the (arrival, id) order; indices held in the lists are remapped
-        std::vector<size_t> order(s->reqs.size());
-        for (size_t i = 0; i < order.size(); ++i) order[i] = i;
-        std::sort(order.begin(), order.end(), [&](size_t a, size_t b) {
-            const Req &x = s->reqs[a], &y = s->reqs[b];
-            return x.arrival != y.arrival ? x.arrival < y.arrival : x.id < y.id;
-        });
-        std::vector<size_t> where(order.size());
-        std::vector<Req> sorted;
-        sorted.reserve(order.size());
-        for (size_t i = 0; i < order.size(); ++i) {
-            where[order[i]] = i;
-            sorted.push_back(std::move(s->reqs[order[i]]));
-        }
-        s->reqs.swap(sorted);
-        for (size_t &w : s->waiting) w = where[w];
-        for (size_t &w : s->in_api) w = where[w];
-        for (auto &kv : s->by_id) kv.second = where[kv.second];
-        s->next_new = 0;
-        s->in_batch.assign(s->reqs.size(), 0);
-        s->sorted = true;
-    }
-    const lamps_sched_config &cfg = s->cfg;
-    for (;;) {
-        if (s->done == s->reqs.size()) {
-            *n = 0;
-            return LAMPS_OK;
-        }
-        // new requests get their handling strategy and enter the waiting queue
-        // (requests added later with an arrival equal to the current time may sort in
-        // front of ones that are already past this stage; those are skipped)
-        while (s->next_new < s->reqs.size() &&
-               (s->reqs[s->next_new].state != kNew || s->reqs[s->next_new].arrival <= s->now)) {
-            Req &r = s->reqs[s->next_new];
-            if (r.state == kNew) {
-                s->decide(r);
-                r.state = kWaiting;
-                s->waiting.push_back(s->next_new);
+    try {
+        if (!s || !out || !n || s->batch_pending) return LAMPS_ERR_INVALID;
+        if (cap < s->cfg.max_batch) return LAMPS_ERR_RANGE;
+        if (!s->sorted) {
+            // (re)establish the (arrival, id) order; indices held in the lists are remapped
+            std::vector<size_t> order(s->reqs.size());
+            for (size_t i = 0; i < order.size(); ++i) order[i] = i;
+            std::sort(order.begin(), order.end(), [&](size_t a, size_t b) {
+                const Req &x = s->reqs[a], &y = s->reqs[b];
+                return x.arrival != y.arrival ? x.arrival < y.arrival : x.id < y.id;
+            });
+            std::vector<size_t> where(order.size());
+            std::vector<Req> sorted;
+            sorted.reserve(order.size());
+            for (size_t i = 0; i < order.size(); ++i) {
+                where[order[i]] = i;
+                sorted.push_back(std::move(s->reqs[order[i]]));
             }
-            ++s->next_new;
+            s->reqs.swap(sorted);
+            for (size_t &w : s->waiting) w = where[w];
+            for (size_t &w : s->in_api) w = where[w];
+            for (auto &kv : s->by_id) kv.second = where[kv.second];
+            s->next_new = 0;
+            s->in_batch.assign(s->reqs.size(), 0);
+            s->sorted = true;
         }
-        // requests whose API call has finished re-enter it
-        for (size_t k = 0; k < s->in_api.size();) {
-            Req &r = s->reqs[s->in_api[k]];
-            if (r.api_end <= s->now) {
-                s->return_from_api(r);
-                s->waiting.push_back(s->in_api[k]);
-                s->in_api[k] = s->in_api.back();
-                s->in_api.pop_back();
-            } else {
-                ++k;
+        const lamps_sched_config &cfg = s->cfg;
+        for (;;) {
+            if (s->done == s->reqs.size()) {
+                *n = 0;
+                return LAMPS_OK;
             }
-        }
-        // scores (cached, refreshed every score_refresh iterations), then the sort
-        for (size_t w : s->waiting) {
-            Req &r = s->reqs[w];
-            if (!r.has_score || s->iteration - r.score_iter >= cfg.score_refresh) {
-                r.score = s->rank(r);
-                r.has_score = true;
-                r.score_iter = s->iteration;
+            // new requests get their handling strategy and enter the waiting queue
+            // (requests added later with an arrival equal to the current time may sort in
+            // front of ones that are already past this stage; those are skipped)
+            while (s->next_new < s->reqs.size() &&
+                   (s->reqs[s->next_new].state != kNew || s->reqs[s->next_new].arrival <= s->now)) {
+                Req &r = s->reqs[s->next_new];
+                if (r.state == kNew) {
+                    s->decide(r);
+                    r.state = kWaiting;
+                    s->waiting.push_back(s->next_new);
+                }
+                ++s->next_new;
             }
-        }
-        auto by_rank = [&](size_t a, size_t b) {
-            const Req &x = s->reqs[a], &y = s->reqs[b];
-            if (x.prioritized != y.prioritized) return x.prioritized;
-            if (x.score != y.score) return x.score < y.score;
-            if (x.arrival != y.arrival) return x.arrival < y.arrival;
-            return x.id < y.id;
-        };
-        std::sort(s->waiting.begin(), s->waiting.end(), by_rank);
-        // the running batch; `count` = this is the pass that moves the starvation counters
-        auto form = [&](bool count) {
-            int64_t free_tokens = cfg.memory_tokens - s->total_held;
-            for (size_t w : s->batch) s->in_batch[w] = 0;
-            s->batch.clear();
-            for (size_t w : s->waiting) {
-                Req &r = s->reqs[w];
-                const int64_t nd = s->need(r);
-                if ((int32_t)s->batch.size() < cfg.max_batch && nd <= free_tokens) {
-                    s->batch.push_back(w);
-                    s->in_batch[w] = 1;
-                    free_tokens -= nd;
-                    if (count) r.starv = 0;
-                } else if (count) {
-                    ++r.starv;
+            // requests whose API call has finished re-enter it
+            for (size_t k = 0; k < s->in_api.size();) {
+                Req &r = s->reqs[s->in_api[k]];
+                if (r.api_end <= s->now) {
+                    s->return_from_api(r);
+                    s->waiting.push_back(s->in_api[k]);
+                    s->in_api[k] = s->in_api.back();
+                    s->in_api.pop_back();
+                } else {
+                    ++k;
                 }
             }
-        };
-        form(true);
-        // Algorithm 1's second loop: a request left out often enough is tagged and goes to the
-        // head of the queue for this very iteration (Section 4.4): the batch is formed once more
-        bool tagged = false;
-        for (size_t w : s->waiting) {
-            Req &r = s->reqs[w];
-            if (!s->in_batch[w] && !r.prioritized && r.starv >= cfg.starvation_threshold) {
-                r.prioritized = true;
-                r.starv = 0;
-                tagged = true;
+            // scores (cached, refreshed every score_refresh iterations), then the sort
+            for (size_t w : s->waiting) {
+                Req &r = s->reqs[w];
+                if (!r.has_score || s->iteration - r.score_iter >= cfg.score_refresh) {
+                    r.score = s->rank(r);
+                    r.has_score = true;
+                    r.score_iter = s->iteration;
+                }
             }
-        }
-        if (tagged) {
+            auto by_rank = [&](size_t a, size_t b) {
+                const Req &x = s->reqs[a], &y = s->reqs[b];
+                if (x.prioritized != y.prioritized) return x.prioritized;
+                if (x.score != y.score) return x.score < y.score;
+                if (x.arrival != y.arrival) return x.arrival < y.arrival;
+                return x.id < y.id;
+            };
             std::sort(s->waiting.begin(), s->waiting.end(), by_rank);
-            form(false);
-        }
-        if (!s->batch.empty()) break;
-        // Nothing fits.  If memory is held by waiting requests none of which can grow, the
-        // worst-ranked holder is discarded and recomputes once memory is there (Section 4.3 on
-        // full memory); otherwise the engine idles until the next arrival or API return.
-        Req *victim = nullptr;
-        for (size_t k = s->waiting.size(); k-- > 0;)
-            if (s->reqs[s->waiting[k]].held > 0) {
-                victim = &s->reqs[s->waiting[k]];
-                break;
+            // the running batch; `count` = this is the pass that moves the starvation counters
+            auto form = [&](bool count) {
+                int64_t free_tokens = cfg.memory_tokens - s->total_held;
+                for (size_t w : s->batch) s->in_batch[w] = 0;
+                s->batch.clear();
+                for (size_t w : s->waiting) {
+                    Req &r = s->reqs[w];
+                    const int64_t nd = s->need(r);
+                    if ((int32_t)s->batch.size() < cfg.max_batch && nd <= free_tokens) {
+                        s->batch.push_back(w);
+                        s->in_batch[w] = 1;
+                        free_tokens -= nd;
+                        if (count) r.starv = 0;
+                    } else if (count) {
+                        ++r.starv;
+                    }
+                }
+            };
+            form(true);
+            // Algorithm 1's second loop: a request left out often enough is tagged and goes to the
+            // head of the queue for this very iteration (Section 4.4): the batch is formed once more
+            bool tagged = false;
+            for (size_t w : s->waiting) {
+                Req &r = s->reqs[w];
+                if (!s->in_batch[w] && !r.prioritized && r.starv >= cfg.starvation_threshold) {
+                    r.prioritized = true;
+                    r.starv = 0;
+                    tagged = true;
+                }
             }
-        if (victim) {
-            s->total_held -= victim->held;
-            victim->held = 0;
-            victim->pending_swapin = 0;
-            victim->pending_recompute = victim->ctx;
-            victim->started = false;
-            victim->has_score = false;
-            ++s->preemptions;
-            s->discarded.push_back(victim->id);
-            continue;
+            if (tagged) {
+                std::sort(s->waiting.begin(), s->waiting.end(), by_rank);
+                form(false);
+            }
+            if (!s->batch.empty()) break;
+            // Nothing fits.  If memory is held by waiting requests none of which can grow, the
+            // worst-ranked holder is discarded and recomputes once memory is there (Section 4.3 on
+            // full memory); otherwise the engine idles until the next arrival or API return.
+            Req *victim = nullptr;
+            for (size_t k = s->waiting.size(); k-- > 0;)
+                if (s->reqs[s->waiting[k]].held > 0) {
+                    victim = &s->reqs[s->waiting[k]];
+                    break;
+                }
+            if (victim) {
+                s->total_held -= victim->held;
+                victim->held = 0;
+                victim->pending_swapin = 0;
+                victim->pending_recompute = victim->ctx;
+                victim->started = false;
+                victim->has_score = false;
+                ++s->preemptions;
+                s->discarded.push_back(victim->id);
+                continue;
+            }
+            bool have = false;
+            double nxt = 0.0;
+            for (size_t k : s->in_api)
+                if (!have || s->reqs[k].api_end < nxt) nxt = s->reqs[k].api_end, have = true;
+            if (s->next_new < s->reqs.size() && (!have || s->reqs[s->next_new].arrival < nxt))
+                nxt = s->reqs[s->next_new].arrival, have = true;
+            if (!have) return LAMPS_ERR_NOMEM;
+            s->now = std::max(s->now, nxt);
         }
-        bool have = false;
-        double nxt = 0.0;
-        for (size_t k : s->in_api)
-            if (!have || s->reqs[k].api_end < nxt) nxt = s->reqs[k].api_end, have = true;
-        if (s->next_new < s->reqs.size() && (!have || s->reqs[s->next_new].arrival < nxt))
-            nxt = s->reqs[s->next_new].arrival, have = true;
-        if (!have) return LAMPS_ERR_NOMEM;
-        s->now = std::max(s->now, nxt);
+        *n = (int32_t)s->batch.size();
+        for (int32_t i = 0; i < *n; ++i) {
+            const Req &r = s->reqs[s->batch[i]];
+            out[i].id = r.id;
+            out[i].swap_in = r.pending_swapin;
+            out[i].recompute = r.pending_recompute > 0 ? std::min<int64_t>(cfg.recompute_chunk, r.pending_recompute) : 0;
+            const int64_t held_after = r.held + r.pending_swapin + (out[i].recompute ? out[i].recompute : 1);
+            out[i].context = out[i].recompute ? std::max(r.ctx, held_after) : r.ctx + 1;
+        }
+        s->batch_pending = true;
+        return LAMPS_OK;
     }
-    *n = (int32_t)s->batch.size();
-    for (int32_t i = 0; i < *n; ++i) {
-        const Req &r = s->reqs[s->batch[i]];
-        out[i].id = r.id;
-        out[i].swap_in = r.pending_swapin;
-        out[i].recompute = r.pending_recompute > 0 ? std::min<int64_t>(cfg.recompute_chunk, r.pending_recompute) : 0;
-        const int64_t held_after = r.held + r.pending_swapin + (out[i].recompute ? out[i].recompute : 1);
-        out[i].context = out[i].recompute ? std::max(r.ctx, held_after) : r.ctx + 1;
-    }
-    s->batch_pending = true;
-    return LAMPS_OK;
+    LAMPS_SCHED_CATCH
 }
 
 int lamps_sched_commit(lamps_sched *s, double iteration_time, lamps_sched_event *events, int32_t cap,
                        int32_t *n)
 {
-    if (!s || !events || !n || !s->batch_pending) return LAMPS_ERR_INVALID;
-    if (cap < s->cfg.max_batch) return LAMPS_ERR_RANGE;
-    const lamps_sched_config &cfg = s->cfg;
-    int64_t recomputed = 0, swapped = 0, ctx_tokens = 0;
-    std::vector<size_t> generated;
-    for (size_t w : s->batch) {
-        Req &r = s->reqs[w];
-        r.started = true;
-        if (r.pending_swapin) {
-            r.held += r.pending_swapin;
-            s->total_held += r.pending_swapin;
-            swapped += r.pending_swapin;
-            r.pending_swapin = 0;
-        }
-        if (r.pending_recompute > 0) {
-            const int64_t k = std::min<int64_t>(cfg.recompute_chunk, r.pending_recompute);
-            r.held += k;
-            s->total_held += k;
-            if (r.ctx < r.held) r.ctx = r.held;
-            r.pending_recompute -= k;
-            recomputed += k;
-        } else {
-            ++r.held;
-            ++s->total_held;
-            ++r.ctx;
-            ++r.done_in_seg;
-            generated.push_back(w);
-        }
-        ctx_tokens += r.held;
-    }
-    s->peak = std::max(s->peak, s->total_held);
-    if (s->total_held > cfg.memory_tokens) return LAMPS_ERR_INVALID;      // cannot happen: need() was free
-    // requests that reach their API call leave by their handling strategy
-    for (size_t w : generated) {
-        const Req &r = s->reqs[w];
-        const lamps_segment &sg = r.seg[r.cur];
-        if (r.done_in_seg == sg.n_out && sg.api_duration >= 0 && sg.handling == LAMPS_SWAP) swapped += r.held;
-    }
-    s->now += iteration_time >= 0 ? iteration_time : cost_iteration(cfg.cost, ctx_tokens, recomputed, swapped);
-    ++s->iteration;
-    int32_t ne = 0;
-    for (size_t w : generated) {
-        Req &r = s->reqs[w];
-        if (r.first_token < 0) r.first_token = s->now;
-        const lamps_segment &sg = r.seg[r.cur];
-        if (r.done_in_seg < sg.n_out) continue;
-        events[ne].id = r.id;
-        events[ne].context = r.ctx;
-        if (sg.api_duration < 0) {                  // finished
-            r.state = kDone;
-            r.completion = s->now;
-            s->total_held -= r.held;
-            r.held = 0;
-            ++s->done;
-            events[ne].what = 1;
-            events[ne].handling = LAMPS_PRESERVE;
-        } else {
-            r.state = kInApi;
-            r.api_end = s->now + sg.api_duration;
-            r.starv = 0;
-            if (sg.handling == LAMPS_DISCARD || sg.handling == LAMPS_SWAP) {
-                s->total_held -= r.held;            // Preserve keeps it
-                r.held = 0;
+    try {
+        if (!s || !events || !n || !s->batch_pending) return LAMPS_ERR_INVALID;
+        if (cap < s->cfg.max_batch) return LAMPS_ERR_RANGE;
+        const lamps_sched_config &cfg = s->cfg;
+        int64_t recomputed = 0, swapped = 0, ctx_tokens = 0;
+        std::vector<size_t> generated;
+        for (size_t w : s->batch) {
+            Req &r = s->reqs[w];
+            r.started = true;
+            if (r.pending_swapin) {
+                r.held += r.pending_swapin;
+                s->total_held += r.pending_swapin;
+                swapped += r.pending_swapin;
+                r.pending_swapin = 0;
             }
-            s->in_api.push_back(w);
-            events[ne].what = 0;
-            events[ne].handling = sg.handling;
+            if (r.pending_recompute > 0) {
+                const int64_t k = std::min<int64_t>(cfg.recompute_chunk, r.pending_recompute);
+                r.held += k;
+                s->total_held += k;
+                if (r.ctx < r.held) r.ctx = r.held;
+                r.pending_recompute -= k;
+                recomputed += k;
+            } else {
+                ++r.held;
+                ++s->total_held;
+                ++r.ctx;
+                ++r.done_in_seg;
+                generated.push_back(w);
+            }
+            ctx_tokens += r.held;
         }
-        ++ne;
+        s->peak = std::max(s->peak, s->total_held);
+        if (s->total_held > cfg.memory_tokens) return LAMPS_ERR_INVALID;      // cannot happen: need() was free
+        // requests that reach their API call leave by their handling strategy
+        for (size_t w : generated) {
+            const Req &r = s->reqs[w];
+            const lamps_segment &sg = r.seg[r.cur];
+            if (r.done_in_seg == sg.n_out && sg.api_duration >= 0 && sg.handling == LAMPS_SWAP) swapped += r.held;
+        }
+        s->now += iteration_time >= 0 ? iteration_time : cost_iteration(cfg.cost, ctx_tokens, recomputed, swapped);
+        ++s->iteration;
+        int32_t ne = 0;
+        for (size_t w : generated) {
+            Req &r = s->reqs[w];
+            if (r.first_token < 0) r.first_token = s->now;
+            const lamps_segment &sg = r.seg[r.cur];
+            if (r.done_in_seg < sg.n_out) continue;
+            events[ne].id = r.id;
+            events[ne].context = r.ctx;
+            if (sg.api_duration < 0) {                  // finished
+                r.state = kDone;
+                r.completion = s->now;
+                s->total_held -= r.held;
+                r.held = 0;
+                ++s->done;
+                events[ne].what = 1;
+                events[ne].handling = LAMPS_PRESERVE;
+            } else {
+                r.state = kInApi;
+                r.api_end = s->now + sg.api_duration;
+                r.starv = 0;
+                if (sg.handling == LAMPS_DISCARD || sg.handling == LAMPS_SWAP) {
+                    s->total_held -= r.held;            // Preserve keeps it
+                    r.held = 0;
+                }
+                s->in_api.push_back(w);
+                events[ne].what = 0;
+                events[ne].handling = sg.handling;
+            }
+            ++ne;
+        }
+        // what left the waiting queue (API call or finished) is dropped from it
+        size_t keep = 0;
+        for (size_t w : s->waiting)
+            if (s->reqs[w].state == kWaiting) s->waiting[keep++] = w;
+        s->waiting.resize(keep);
+        for (size_t w : s->batch) s->in_batch[w] = 0;
+        s->batch.clear();
+        s->batch_pending = false;
+        *n = ne;
+        return LAMPS_OK;
     }
-    // what left the waiting queue (API call or finished) is dropped from it
-    size_t keep = 0;
-    for (size_t w : s->waiting)
-        if (s->reqs[w].state == kWaiting) s->waiting[keep++] = w;
-    s->waiting.resize(keep);
-    for (size_t w : s->batch) s->in_batch[w] = 0;
-    s->batch.clear();
-    s->batch_pending = false;
-    *n = ne;
-    return LAMPS_OK;
+    LAMPS_SCHED_CATCH
 }
 
 int lamps_sched_run(lamps_sched *s)
 {
-    if (!s) return LAMPS_ERR_INVALID;
-    std::vector<lamps_batch_entry> b(s->cfg.max_batch);
-    std::vector<lamps_sched_event> e(s->cfg.max_batch);
-    for (;;) {
-        int32_t n = 0, ne = 0;
-        int rc = lamps_sched_next_batch(s, b.data(), (int32_t)b.size(), &n);
-        if (rc != LAMPS_OK) return rc;
-        if (n == 0) return LAMPS_OK;
-        rc = lamps_sched_commit(s, -1.0, e.data(), (int32_t)e.size(), &ne);
-        if (rc != LAMPS_OK) return rc;
+    try {
+        if (!s) return LAMPS_ERR_INVALID;
+        std::vector<lamps_batch_entry> b(s->cfg.max_batch);
+        std::vector<lamps_sched_event> e(s->cfg.max_batch);
+        for (;;) {
+            int32_t n = 0, ne = 0;
+            int rc = lamps_sched_next_batch(s, b.data(), (int32_t)b.size(), &n);
+            if (rc != LAMPS_OK) return rc;
+            if (n == 0) return LAMPS_OK;
+            rc = lamps_sched_commit(s, -1.0, e.data(), (int32_t)e.size(), &ne);
+            if (rc != LAMPS_OK) return rc;
+        }
     }
+    LAMPS_SCHED_CATCH
 }
 
 int lamps_sched_take_discards(lamps_sched *s, int64_t *ids, int32_t cap, int32_t *n)
 {
-    if (!s || !n || cap < 0 || (cap > 0 && !ids)) return LAMPS_ERR_INVALID;
-    const size_t take = std::min<size_t>(s->discarded.size(), (size_t)cap);
-    for (size_t i = 0; i < take; ++i) ids[i] = s->discarded[i];
-    s->discarded.erase(s->discarded.begin(), s->discarded.begin() + take);
-    *n = (int32_t)take;
-    return LAMPS_OK;
+    try {
+        if (!s || !n || cap < 0 || (cap > 0 && !ids)) return LAMPS_ERR_INVALID;
+        const size_t take = std::min<size_t>(s->discarded.size(), (size_t)cap);
+        for (size_t i = 0; i < take; ++i) ids[i] = s->discarded[i];
+        s->discarded.erase(s->discarded.begin(), s->discarded.begin() + take);
+        *n = (int32_t)take;
+        return LAMPS_OK;
+    }
+    LAMPS_SCHED_CATCH
 }
 
 double lamps_sched_now(const lamps_sched *s) { return s ? s->now : -1.0; }
@@ -499,23 +526,29 @@ double lamps_sched_now(const lamps_sched *s) { return s ? s->now : -1.0; }
 int lamps_sched_result(const lamps_sched *s, int64_t id, double *completion, double *first_token,
                        int32_t *handling, int32_t n_handling)
 {
-    if (!s || n_handling < 0 || (n_handling > 0 && !handling)) return LAMPS_ERR_INVALID;
-    auto it = s->by_id.find(id);
-    if (it == s->by_id.end()) return LAMPS_ERR_RANGE;
-    const Req &r = s->reqs[it->second];
-    if (completion) *completion = r.completion;
-    if (first_token) *first_token = r.first_token;
-    for (int32_t k = 0; k < n_handling && k < (int32_t)r.seg.size(); ++k) handling[k] = r.seg[k].handling;
-    return LAMPS_OK;
+    try {
+        if (!s || n_handling < 0 || (n_handling > 0 && !handling)) return LAMPS_ERR_INVALID;
+        auto it = s->by_id.find(id);
+        if (it == s->by_id.end()) return LAMPS_ERR_RANGE;
+        const Req &r = s->reqs[it->second];
+        if (completion) *completion = r.completion;
+        if (first_token) *first_token = r.first_token;
+        for (int32_t k = 0; k < n_handling && k < (int32_t)r.seg.size(); ++k) handling[k] = r.seg[k].handling;
+        return LAMPS_OK;
+    }
+    LAMPS_SCHED_CATCH
 }
 
 int lamps_sched_stats(const lamps_sched *s, int64_t *iterations, int64_t *peak_memory, int64_t *preemptions)
 {
-    if (!s) return LAMPS_ERR_INVALID;
-    if (iterations) *iterations = s->iteration;
-    if (peak_memory) *peak_memory = s->peak;
-    if (preemptions) *preemptions = s->preemptions;
-    return LAMPS_OK;
+    try {
+        if (!s) return LAMPS_ERR_INVALID;
+        if (iterations) *iterations = s->iteration;
+        if (peak_memory) *peak_memory = s->peak;
+        if (preemptions) *preemptions = s->preemptions;
+        return LAMPS_OK;
+    }
+    LAMPS_SCHED_CATCH
 }
 
 }  // extern "C"

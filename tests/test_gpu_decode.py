@@ -216,14 +216,16 @@ def _full_size(cfg, sample_requests, rep=0, part_tokens=None):
     q = torch.empty((wl.batch, geom.num_q_heads, geom.head_dim), dtype=rig.tdtype,
                     device=rig.dev).normal_(generator=gen)
     running = (wl.state == W.RUNNING).astype(np.uint8)
+    run_idx = np.flatnonzero(running)
+    ragged, boundary = _edge_requests(wl, run_idx)
     out = rig.decode(0, q, table, wl.ctx_lens, running, sentinel=3.0)
     got = to_f64(out)
     qn = t2n(q)
-    run_idx = np.flatnonzero(running)
     pick = run_idx[W.permutation(seed + 4, len(run_idx))[:sample_requests]]
-    # always include the shortest and the longest running request
+    # always include the shortest and the longest running request, one whose length is not a
+    # multiple of the kernels' chunk and one that ends exactly at a block boundary
     pick = set(pick.tolist()) | {int(run_idx[np.argmin(wl.ctx_lens[run_idx])]),
-                                 int(run_idx[np.argmax(wl.ctx_lens[run_idx])])}
+                                 int(run_idx[np.argmax(wl.ctx_lens[run_idx])]), ragged, boundary}
     worst = 0.0
     for r in sorted(pick):
         C = int(wl.ctx_lens[r])
@@ -235,6 +237,21 @@ def _full_size(cfg, sample_requests, rep=0, part_tokens=None):
     assert not np.isnan(got[run_idx]).any()
     rig.close()
     return worst
+
+
+def _edge_requests(wl, run_idx):
+    """A running request whose length is no multiple of 32 (the largest chunk of the kernels), and
+    one whose length is a multiple of the block size -- if the draw holds none of the latter, the
+    first running request is cut back to its last block boundary (in wl, before the launch)."""
+    bs = wl.geom.block_size
+    ragged = next(int(r) for r in run_idx if wl.ctx_lens[r] % 32 != 0)
+    at = [int(r) for r in run_idx if wl.ctx_lens[r] % bs == 0 and int(r) != ragged]
+    if not at:
+        r = next(int(r) for r in run_idx if int(r) != ragged and wl.ctx_lens[r] >= 2 * bs)
+        wl.ctx_lens[r] -= wl.ctx_lens[r] % bs
+        at = [r]
+    assert wl.ctx_lens[ragged] % 32 != 0 and wl.ctx_lens[at[0]] % bs == 0
+    return ragged, at[0]
 
 
 @pytest.mark.parametrize("cfg,sample,part", [(1, 6, None), (2, 8, None), (3, 2, None), (3, 2, 512),
@@ -267,10 +284,11 @@ def test_cfg4_full_size_layers_sampled():
     qn = t2n(q)
     running = (wl.state == W.RUNNING).astype(np.uint8)
     run_idx = np.flatnonzero(running)
+    ragged, boundary = _edge_requests(wl, run_idx)
     for layer in (0, 19, 39):
         out = rig.decode(layer, q, table, wl.ctx_lens, running, sentinel=3.0)
         got = to_f64(out)
-        pick = run_idx[W.permutation(seed + 10 + layer, len(run_idx))[:6]]
+        pick = run_idx[W.permutation(seed + 10 + layer, len(run_idx))[:6]].tolist() + [ragged, boundary]
         for r in pick:
             C = int(wl.ctx_lens[r])
             k, v = rig.unpage_request(layer, table[r], C)
@@ -346,4 +364,32 @@ def test_one_long_request_among_many_short_ones(dtype, H, Hkv, D):
     live = running == 1
     assert np.abs(got[live] - ref[live]).max() <= tol(geom)
     assert (got[~live] == 2.5).all()
+    rig.close()
+
+
+def test_validator_finds_bad_device_arguments():
+    """lamps_validate_args reads the table, the lengths and the mask only.  The bad tables go to
+    the validator alone, never to the attention call."""
+    geom = W.Geometry(2, 8, 2, 128, 16, 40, 6, "bf16")
+    ctx = [40, 96, 17, 0, 5]
+    rig, table, q, K, V = _setup(77, geom, ctx)
+    lam, dev = rig.lamps, rig.dev
+    B = len(ctx)
+
+    def check(tab, lens, mask):
+        return lam.validate_args(B, torch.as_tensor(np.ascontiguousarray(tab, dtype=np.int32), device=dev),
+                                 torch.as_tensor(np.asarray(lens, dtype=np.int32), device=dev),
+                                 torch.as_tensor(np.asarray(mask, dtype=np.uint8), device=dev))
+    ones = [1] * B
+    assert check(table, ctx, ones) == (0, -1, 0, 0)             # unused entries are -1: never looked at
+    bad = table.copy()
+    bad[1, 5] = geom.num_blocks                                  # last used entry of request 1 (96 tokens = 6 blocks)
+    assert check(bad, ctx, ones) == (1, 1, 2, geom.num_blocks)
+    assert check(bad, ctx, [1, 0, 1, 1, 1]) == (0, -1, 0, 0)     # a paused request's table is not read
+    bad[4, 0] = -7
+    bad[2, 1] = 12345
+    assert check(bad, ctx, ones) == (3, 1, 2, geom.num_blocks)   # three bad requests, the lowest is reported
+    assert check(table, [40, 97, 17, 0, 5], ones) == (1, 1, 1, 97)     # longer than the row of 6 blocks
+    assert check(table, [40, 96, -1, 0, 5], [0] * B) == (1, 2, 1, -1)  # a length is checked paused or not
+    assert "request 2" in lam.last_error()
     rig.close()
