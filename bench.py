@@ -681,7 +681,7 @@ def main():
 def measure_config(a, cfg_id, headline):
     """One workload measured by the timing rule of the module docstring.  headline: the whole
     bench line (exactly --steps timed steps, oracle timed as cpu_baseline); otherwise a compact
-    record for "per_config" (at least --steps steps and at least about 20 ms of them)."""
+    record for "per_config" (at least --steps steps and at least about 60 ms of them)."""
     import torch
     job = Job(cfg_id, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom, a.direct_copy_bytes, a.staging_mib,
               a.zero_copy, a.ctx_long)
@@ -696,8 +696,8 @@ def measure_config(a, cfg_id, headline):
         job.use_graphs()
         per_step = job.train(2 * job.R, False)["event_s"] / (2 * job.R)
     steps = a.steps if a.steps > 0 else int(min(4000, max(job.R, 0.05 / per_step)))
-    if not headline:
-        steps = max(steps, int(np.ceil(0.02 / per_step)))
+    if not headline:                                    # long enough for a dozen swap copies to finish inside
+        steps = max(steps, int(np.ceil(0.06 / per_step)))
     warmup = a.warmup if a.warmup >= 0 else max(job.R, steps // 4)
     clock_s = a.clock_warmup_ms * 1e-3
 
