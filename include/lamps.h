@@ -126,6 +126,15 @@ typedef struct {
                                    0 => off (the default); not together with
                                    direct_copy_bytes.  The layer-major calls always
                                    stage.                                            */
+    int32_t max_swaps_in_flight;  /* > 0: a swap call first waits (on the host, polling)
+                                   until fewer than this many swaps of its direction
+                                   are unfinished.  With more than about two copies
+                                   per direction queued ahead while both directions are
+                                   busy, the runtime's copy path has been measured to
+                                   drop to a quarter of the link rate for tens of
+                                   milliseconds at a time; 2 keeps it at full rate.
+                                   0 => no limit (the default: the calls never block;
+                                   the caller paces them)                            */
 } lamps_config;
 
 /* ---- sizes (pure functions of the config; return 0 on an invalid config) ---- */

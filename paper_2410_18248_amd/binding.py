@@ -33,7 +33,8 @@ class LampsConfig(ctypes.Structure):
                 ("max_blocks_per_req", ctypes.c_int32), ("max_batch", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("part_tokens", ctypes.c_int32), ("staging_bytes", ctypes.c_int64),
-                ("direct_copy_bytes", ctypes.c_int64), ("zero_copy_workgroups", ctypes.c_int32)]
+                ("direct_copy_bytes", ctypes.c_int64), ("zero_copy_workgroups", ctypes.c_int32),
+                ("max_swaps_in_flight", ctypes.c_int32)]
 
 
 def lib_path():

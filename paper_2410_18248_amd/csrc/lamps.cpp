@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -18,6 +19,7 @@
 #include <memory>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "internal.h"
@@ -97,6 +99,7 @@ const char *derive(const lamps_config *c, Derived *d)
     d->direct_copy = direct_from > 0 && (int64_t)d->half_bytes >= direct_from;
     if (c->zero_copy_workgroups < 0 || c->zero_copy_workgroups > 1024)
         return "zero_copy_workgroups must be in [0, 1024]";
+    if (c->max_swaps_in_flight < 0) return "max_swaps_in_flight is negative";
     if (c->zero_copy_workgroups > 0 && c->direct_copy_bytes > 0)
         return "zero_copy_workgroups and direct_copy_bytes exclude each other";
     d->zero_copy = c->zero_copy_workgroups;
@@ -275,6 +278,29 @@ int new_event(lamps_ctx *c, hipEvent_t *ev)
     return LAMPS_OK;
 }
 
+// Backpressure (lamps_config.max_swaps_in_flight): waits, polling, until fewer than the limit
+// of this direction's copies are unfinished.  Copies of one direction finish in ticket order, so
+// the oldest unfinished one is the one to watch.
+int wait_for_room(lamps_ctx *c, bool out)
+{
+    const int limit = c->cfg.max_swaps_in_flight;
+    if (limit <= 0) return LAMPS_OK;
+    for (;;) {
+        retire_finished(c);
+        int busy = 0;
+        hipEvent_t oldest = nullptr;
+        for (const Ticket &t : c->tickets)
+            if (t.is_out == out && hipEventQuery(t.ev) != hipSuccess) {
+                if (!oldest) oldest = t.ev;
+                ++busy;
+            }
+        if (busy < limit) return LAMPS_OK;
+        while (hipEventQuery(oldest) == hipErrorNotReady) std::this_thread::sleep_for(std::chrono::microseconds(50));
+        const hipError_t e = hipEventQuery(oldest);
+        if (e != hipSuccess) return hip_fail(c, "hipEventQuery", e);
+    }
+}
+
 // Reserves n contiguous ring slots; *slots is what the ticket must give back.
 int ring_reserve(lamps_ctx *c, int32_t n, int32_t **where, size_t *slots)
 {
@@ -450,6 +476,7 @@ int swap_layered(lamps_ctx *c, bool out, char *host, const int32_t *block_ids, i
     int rc = check_ids(c, block_ids, n, who);
     if (rc != LAMPS_OK) return rc;
     if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
+    if ((rc = wait_for_room(c, out)) != LAMPS_OK) return rc;
     retire_finished(c);
     int32_t *ids = nullptr;
     size_t slots = 0;
@@ -778,6 +805,7 @@ int lamps_swap_out(lamps_ctx *c, const int32_t *block_ids, int32_t n, void *host
             (rc = mapped_host(c, host_buf, (size_t)n * c->d.block_bytes, "lamps_swap_out", &host_dev)) != LAMPS_OK)
             return rc;
         if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
+        if ((rc = wait_for_room(c, true)) != LAMPS_OK) return rc;
         retire_finished(c);
         int32_t *ids = nullptr;
         size_t slots = 0;
@@ -843,6 +871,7 @@ int lamps_swap_in(lamps_ctx *c, const void *host_buf, const int32_t *block_ids, 
             (rc = mapped_host(c, host_buf, (size_t)n * c->d.block_bytes, "lamps_swap_in", &host_dev)) != LAMPS_OK)
             return rc;
         if ((rc = ensure_runtime(c)) != LAMPS_OK) return rc;
+        if ((rc = wait_for_room(c, false)) != LAMPS_OK) return rc;
         retire_finished(c);
         int32_t *ids = nullptr;
         size_t slots = 0;

@@ -8,11 +8,11 @@ import paper_2410_18248_amd as P
 
 
 def make_config(geom, max_batch, part_tokens=0, staging_bytes=0, scale=0.0, direct_copy_bytes=0,
-                zero_copy_workgroups=0):
+                zero_copy_workgroups=0, max_swaps_in_flight=0):
     return P.LampsConfig(geom.num_layers, geom.num_q_heads, geom.num_kv_heads, geom.head_dim,
                          geom.block_size, geom.num_blocks, geom.max_blocks_per_req, max_batch,
                          P.LAMPS_BF16 if geom.dtype == "bf16" else P.LAMPS_F32, scale,
-                         part_tokens, staging_bytes, direct_copy_bytes, zero_copy_workgroups)
+                         part_tokens, staging_bytes, direct_copy_bytes, zero_copy_workgroups, max_swaps_in_flight)
 
 
 def t2n(t):
@@ -35,12 +35,13 @@ class Rig:
     """Pools, workspace, streams and a Lamps context for one geometry."""
 
     def __init__(self, geom, max_batch, part_tokens=0, staging_bytes=0, poison=True,
-                 side_streams=True, scale=0.0, direct_copy_bytes=0, zero_copy_workgroups=0):
+                 side_streams=True, scale=0.0, direct_copy_bytes=0, zero_copy_workgroups=0,
+                 max_swaps_in_flight=0):
         self.geom = geom
         self.dev = torch.device("cuda:0")
         self.tdtype = torch.bfloat16 if geom.dtype == "bf16" else torch.float32
         self.cfg = make_config(geom, max_batch, part_tokens, staging_bytes, scale, direct_copy_bytes,
-                               zero_copy_workgroups)
+                               zero_copy_workgroups, max_swaps_in_flight)
         assert P.lamps_pool_bytes(self.cfg) == int(np.prod(geom.pool_shape)) * geom.elem_bytes
         assert P.lamps_kv_layout(self.cfg) == (P.LAMPS_LAYOUT_TILED if geom.kv_layout == "tiled"
                                                else P.LAMPS_LAYOUT_PLAIN)

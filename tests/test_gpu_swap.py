@@ -228,6 +228,37 @@ def test_compute_stream_writer_is_ordered_by_compute_wait_blocks():
     rig.close()
 
 
+def test_backpressure_keeps_the_swap_queue_shallow():
+    """max_swaps_in_flight = 2: a swap call returns only when fewer than two copies of its
+    direction are unfinished, so right after call k the copies before k - 1 are done; the
+    images are what they are without the limit."""
+    geom = W.Geometry(8, 8, 8, 128, 16, 400, 8, "bf16")
+    bb = 2 * geom.block_half_bytes
+    rig = Rig(geom, max_batch=1, max_swaps_in_flight=2)
+    lam = rig.lamps
+    _fill_random(rig, 29)
+    model = _model(rig)
+    lam.alloc_blocks(geom.num_blocks)
+    groups = [list(range(40 * g, 40 * g + 40)) for g in range(10)]      # 20 MiB each
+    hosts = [_pinned(40 * bb) for _ in groups]
+    tickets = []
+    for ids, host in zip(groups, hosts):
+        tickets.append(lam.swap_out(ids, host))
+        assert all(lam.ticket_query(t) for t in tickets[:-2])           # at most two still on their way
+    for g, (ids, host) in enumerate(zip(groups, hosts)):                # and back in, into the next group's blocks
+        t = lam.swap_in(host, groups[(g + 1) % len(groups)])
+        tickets.append(t)
+        assert all(lam.ticket_query(x) for x in tickets[len(groups):-2])
+    lam.ticket_wait(tickets[-1])
+    for ids, host in zip(groups, hosts):                                # every swap-out read the blocks before any swap-in wrote them
+        np.testing.assert_array_equal(host.numpy().reshape(len(ids), bb), model.swap_out(ids))
+    for g, ids in enumerate(groups):                                    # group g + 1 now holds what group g held
+        model_after = model.swap_out(ids)
+        got = _model(rig).swap_out(groups[(g + 1) % len(groups)])
+        np.testing.assert_array_equal(got, model_after)
+    rig.close()
+
+
 @pytest.mark.parametrize("fence", [True, False])
 def test_swap_out_behind_a_compute_stream_writer(fence):
     """The swap-out of blocks that compute-stream work still writes comes after that work: by
