@@ -486,7 +486,8 @@ def swap_layered_bench(a):
     L, Hkv, D, blocks = [int(x) for x in a.swap_layered.split(",")]
     nb = blocks + 8
     dev = torch.device("cuda:0")
-    cfg = P.LampsConfig(L, Hkv, Hkv, D, 16, nb, blocks, 1, P.LAMPS_BF16, 0.0, 0, a.staging_mib << 20, 0)
+    cfg = P.LampsConfig(L, Hkv, Hkv, D, 16, nb, blocks, 1, P.LAMPS_BF16, 0.0, 0, a.staging_mib << 20,
+                        a.direct_copy_bytes or -1)      # the block-major side of the comparison is the staged path
     elems = P.lamps_pool_bytes(cfg) // 2
     k_pool = torch.empty(elems, dtype=torch.bfloat16, device=dev).normal_()
     v_pool = torch.empty(elems, dtype=torch.bfloat16, device=dev).normal_()
