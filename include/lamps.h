@@ -36,7 +36,13 @@
  *     many-token calls, as is a context shorter than its new tokens; a block
  *     table entry outside [0, num_blocks) is not followed.
  *     lamps_validate_args checks all of this on request (it synchronises).
- *   - A context is not thread-safe; calls on it must be serialised.
+ *   - A context is not thread-safe; calls on it must be serialised -- with one
+ *     exception: the compute-stream calls (lamps_decode_attn, lamps_kv_append,
+ *     lamps_kv_append_tokens, lamps_prefill_attn) read nothing of the context that
+ *     ever changes, so ONE thread may make them while ONE other thread makes
+ *     all the block-management and swap calls (alloc, free, swap, ticket, wait
+ *     calls).  lamps_last_error then reports the most recent failure of either;
+ *     read it from the thread whose call failed, before its next call.
  *   - lamps_decode_attn, lamps_kv_append, lamps_kv_append_tokens and
  *     lamps_prefill_attn enqueue kernels on the compute stream and nothing else
  *     (no memset, no copy, no allocation, no host wait): once each has run

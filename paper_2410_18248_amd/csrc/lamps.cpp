@@ -17,6 +17,7 @@
 #include <cstring>
 #include <deque>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -148,6 +149,7 @@ struct lamps_ctx {
     size_t ring_cap = 0;
     uint64_t ring_head = 0, ring_tail = 0;      // monotonic slot counters
     bool swap_fence = true;                     // swap calls order themselves behind the compute stream
+    std::mutex err_lock;                        // the compute-stream calls may fail next to a swap call
     std::string err;
 };
 
@@ -195,7 +197,10 @@ void fill_decode_args(lamps_ctx *c, lamps::DecodeArgs *pa, int32_t layer, int32_
 
 int fail(lamps_ctx *c, int code, const std::string &msg)
 {
-    if (c) c->err = msg;
+    if (c) {
+        std::lock_guard<std::mutex> hold(c->err_lock);
+        c->err = msg;
+    }
     return code;
 }
 
