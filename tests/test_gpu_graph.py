@@ -93,3 +93,58 @@ def test_decode_iteration_replayed_from_a_graph(dtype, H, Hkv, D, bs, L, ctx, pa
             assert (got[l][~live] == 2.5).all(), (it, l)
         assert cd.cpu().tolist() == model.ctx, it
     rig.close()
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_full_size_step_replayed_from_a_graph(cfg):
+    """The launch configuration the benchmark times for its 40-layer headline -- every layer's
+    decode call of a step replayed from one HIP graph -- at full size: configuration 1 (vector
+    path) and 2 (grouped heads) with the layer call captured four times over four query / output
+    buffers.  Each replay is bit-identical to the eager calls, and a seeded sample of requests is
+    checked against the oracle."""
+    wl = W.workload(cfg)
+    geom, seed = wl.geom, W.config_seed(cfg)
+    rig = Rig(geom, max_batch=wl.batch, poison=False)
+    lam, dev = rig.lamps, rig.dev
+    gen = torch.Generator(device=dev).manual_seed(seed)
+    rig.k_pool.normal_(generator=gen)
+    rig.v_pool.normal_(generator=gen)
+    perm = W.permutation(seed + 3, geom.num_blocks)
+    table, _ = W.deal_block_table(perm, wl.ctx_lens, geom)
+    running = (wl.state == W.RUNNING).astype(np.uint8)
+    td = torch.as_tensor(table, device=dev)
+    cd = torch.as_tensor(wl.ctx_lens.astype(np.int32), device=dev)
+    md = torch.as_tensor(running, device=dev)
+    n = 4
+    qs = [torch.empty((wl.batch, geom.num_q_heads, geom.head_dim), dtype=rig.tdtype, device=dev).normal_(generator=gen)
+          for _ in range(n)]
+    eager = [torch.full_like(q, 3.0) for q in qs]
+    outs = [torch.full_like(q, 3.0) for q in qs]
+    with torch.cuda.stream(rig.compute):
+        for i in range(n):
+            lam.decode_attn(0, wl.batch, qs[i], td, cd, md, eager[i])
+    rig.compute.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=rig.compute):
+        for i in range(n):
+            lam.decode_attn(0, wl.batch, qs[i], td, cd, md, outs[i])
+    for rep in range(3):
+        for o in outs:
+            o.fill_(3.0)
+        torch.cuda.synchronize()                        # the program's own work and waits between replays
+        with torch.cuda.stream(rig.compute):
+            graph.replay()
+        rig.compute.synchronize()
+        for i in range(n):
+            assert torch.equal(outs[i].view(torch.int16), eager[i].view(torch.int16)), (rep, i)
+    run_idx = np.flatnonzero(running)
+    pick = run_idx[W.permutation(seed + 21, len(run_idx))[:4]]
+    got = to_f64(outs[n - 1])
+    qn = qs[n - 1].cpu().view(torch.int16).numpy().view(np.uint16)
+    for r in pick:
+        C = int(wl.ctx_lens[r])
+        k, v = rig.unpage_request(0, table[r], C)
+        ref = oracle.decode_attn(qn[r:r + 1], [k], [v], [C], [1], threads=8)
+        assert np.abs(got[r] - ref[0]).max() <= tol(geom), r
+    assert (got[running == 0] == 3.0).all()
+    rig.close()
