@@ -69,6 +69,40 @@ def test_static_scratch_decode_equals_the_workspace_decode_twice_in_a_row(dtype,
     rig.close()
 
 
+def test_static_scratch_decode_captured_in_a_graph():
+    """The callers the entry point is for: one eager call first (it looks the scratch array up),
+    then the call is captured into a HIP graph -- nothing in it allocates or synchronises -- and
+    replayed with other work in between; every replay equals lamps_decode_attn bit for bit."""
+    ctx = [900, 30, 1500, 77, 2100, 260]
+    H, Hkv, D, bs = 16, 4, 128, 16
+    mb = max((c + bs - 1) // bs for c in ctx)
+    geom = W.Geometry(1, H, Hkv, D, bs, sum((c + bs - 1) // bs for c in ctx) + 3, mb, "bf16")
+    rig = Rig(geom, max_batch=len(ctx))
+    B = len(ctx)
+    running = np.ones(B, dtype=np.uint8)
+    (q, table, lens, mask), ref = _case(rig, geom, 9300, ctx, running)
+    want = torch.zeros((B, H, D), dtype=rig.tdtype, device=rig.dev)
+    got = torch.zeros_like(want)
+    with torch.cuda.stream(rig.compute):
+        rig.lamps.decode_attn(0, B, q, table, lens, mask, want)
+        P.lamps_decode_attn_static(rig.cfg, rig.compute.cuda_stream, 0, B, q, rig.k_pool, rig.v_pool, table, lens,
+                                   mask, got)                          # eager once
+    rig.compute.synchronize()
+    assert np.abs(to_f64(want) - ref).max() <= tol(geom)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=rig.compute):
+        P.lamps_decode_attn_static(rig.cfg, rig.compute.cuda_stream, 0, B, q, rig.k_pool, rig.v_pool, table, lens,
+                                   mask, got)
+    for rep in range(3):
+        got.fill_(5.0)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(rig.compute):
+            graph.replay()
+        rig.compute.synchronize()
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16)), rep
+    rig.close()
+
+
 def test_static_scratch_decode_refuses_what_it_cannot_hold():
     geom = W.Geometry(1, 64, 4, 128, 16, 8, 4, "bf16")                # 16 heads per pass: 34 MB of partial slots
     rig = Rig(geom, max_batch=2)
