@@ -393,3 +393,43 @@ def test_validator_finds_bad_device_arguments():
     assert check(table, [40, 96, -1, 0, 5], [0] * B) == (1, 2, 1, -1)  # a length is checked paused or not
     assert "request 2" in lam.last_error()
     rig.close()
+
+
+def _random_case(k):
+    """Seeded draw of a geometry and a batch: every supported head size, group size, block size,
+    both decompositions, contexts from empty to several blocks, some requests paused."""
+    u = W.uniform01(5150 + k, 64)
+    dtype = "bf16" if u[0] < 0.7 else "f32"
+    D = (64, 128, 256)[int(u[1] * 3)] if dtype == "bf16" else (32, 64, 128)[int(u[1] * 3)]
+    Hkv = (1, 2, 3, 4)[int(u[2] * 4)]
+    G = (1, 1, 2, 4, 5, 8, 16)[int(u[3] * 7)]
+    bs = (16, 32, 64, 128)[int(u[4] * 4)]
+    L = 1 + int(u[5] * 3)
+    B = 1 + int(u[6] * 9)
+    ctx = [int(u[10 + r] ** 2 * 700) for r in range(B)]                # skewed towards short, some 0
+    running = [0 if u[30 + r] < 0.2 else 1 for r in range(B)]
+    part = 0 if u[7] < 0.5 else bs * (1 + int(u[8] * 4))
+    return dtype, Hkv * G, Hkv, D, bs, L, ctx, running, part
+
+
+@pytest.mark.parametrize("k", range(24))
+def test_randomized_geometries(k):
+    dtype, H, Hkv, D, bs, L, ctx, running, part = _random_case(k)
+    mb = max(1, max((c + bs - 1) // bs for c in ctx))
+    geom = W.Geometry(L, H, Hkv, D, bs, sum((c + bs - 1) // bs for c in ctx) + 4, mb, dtype)
+    rig, table, q, K, V = _setup(6000 + k, geom, ctx, part)
+    layer = L - 1
+    out = rig.decode(layer, q, table, ctx, running, sentinel=7.0)
+    ref = oracle.decode_attn(q, K, V, ctx, running)
+    got = to_f64(out)
+    for r in range(len(ctx)):
+        if running[r]:
+            assert np.abs(got[r] - ref[r]).max() <= tol(geom), (k, r, ctx[r], geom)
+            if ctx[r] == 0:
+                assert (got[r] == 0).all()
+        else:
+            assert (got[r] == 7.0).all()
+    assert rig.lamps.validate_args(len(ctx), torch.as_tensor(table, device=rig.dev),
+                                   torch.as_tensor(np.asarray(ctx, dtype=np.int32), device=rig.dev),
+                                   torch.as_tensor(np.asarray(running, dtype=np.uint8), device=rig.dev))[0] == 0
+    rig.close()
