@@ -8,17 +8,19 @@ out to pinned host memory, freed, re-allocated and swapped back in on side
 streams, Preserve-state requests stay masked, and Discard-state requests'
 blocks are freed.  Inputs are resident in HBM before the timed region.
 
-Timing rule.  A second host thread keeps the Swap-state requests' blocks going
-out and coming back, round after round (at most two groups of about 1 GiB in
-flight at a time), from before the warm-up steps until after the timed steps,
-so the host link is busy in both directions throughout.  The warm-up steps run,
-the compute stream is synchronised, exactly K steps are timed (host clock from
-before the first call until the compute stream has drained; HIP events on the
-compute stream for the kernel time), then the swap thread is told to stop and
-what it started is drained outside the timed region.  `value` = running
-requests x K / that time: tokens/s of one full decode-attention step with swaps
-in flight, whatever K is; the swap GB/s achieved during the timed steps is
-reported next to it.
+Timing rule.  A second host thread keeps the Swap-state requests' blocks moving
+the way the configuration states it -- configuration 1: out to pinned host
+memory; 2: back in from it, into freshly allocated blocks; 3 and 4: out, freed,
+re-allocated and back in -- round after round (at most two groups of 128 MiB to
+1 GiB in flight at a time), from before the warm-up steps until after the timed
+steps, so the host link is busy in those directions throughout.  The warm-up
+steps run, the compute stream is synchronised, exactly K steps are timed (host
+clock from before the first call until the compute stream has drained; HIP
+events on the compute stream for the kernel time), then the swap thread is told
+to stop and what it started is drained outside the timed region.  `value` =
+running requests x K / that time: tokens/s of one full decode-attention step
+with swaps in flight, whatever K is; the swap GB/s achieved during the timed
+steps is reported next to it.
 
 With no --config the line's headline is configuration 4 (the largest: 40
 layers, 113 GB of pools) and configurations 1-3 are measured the same way and
@@ -93,6 +95,9 @@ def parse():
     ap.add_argument("--prefill", default="",
                     help="measure lamps_prefill_attn instead (Discard's recompute): "
                          "'H,Hkv,D,requests,tokens[,cached]', e.g. 40,40,128,4,4096")
+    ap.add_argument("--swap-directions", choices=["", "out", "in", "both"], default="",
+                    help="which way the Swap-state blocks move during the timed steps (default: as the "
+                         "configuration states it: 1 out, 2 in, 3 and 4 both)")
     ap.add_argument("--table", choices=["random", "sequential"], default="random",
                     help="physical placement of the blocks (sequential is a diagnostic)")
     return ap.parse_args()
@@ -102,7 +107,7 @@ class Job:
     """Device-resident state of one benchmark workload."""
 
     def __init__(self, cfg_id, rotations, part_tokens, table_kind="random", ctx_override=0,
-                 geom_override="", direct_copy_bytes=0, staging_mib=0, zero_copy=0, ctx_long=0):
+                 geom_override="", direct_copy_bytes=0, staging_mib=0, zero_copy=0, ctx_long=0, swap_mode=""):
         import torch
 
         import lamps_workloads as W
@@ -203,6 +208,11 @@ class Job:
                 ids += [int(x) for x in self.tables[b][r, :g.blocks_for(wl.ctx_lens[r])]]
             self.discard_ids.append(ids)
         self.swap_bytes = sum(len(i) for i, _ in self.swap_groups) * self.block_bytes   # one round, each way
+        # which way the Swap-state blocks move while the steps are timed, as the configurations
+        # state it: 1 swaps out, 2 swaps in, 3 and 4 do both (anything else: both)
+        self.swap_mode = swap_mode or {1: "out", 2: "in"}.get(cfg_id, "both")
+        for ids, host in self.swap_groups:                  # the host images exist before anything comes back in
+            self.lam.ticket_wait(self.lam.swap_out(ids, host))
         self.graphs = None
         torch.cuda.synchronize()
         # algorithmic bytes of one decode launch: K and V of the running requests' tokens,
@@ -214,12 +224,18 @@ class Job:
                            + 4 * sum(g.blocks_for(c) for c in wl.ctx_lens[self.running == 1]))
 
     def swap_group(self, grp):
-        """One Swap-state group goes out, is freed, allocated again (other blocks) and comes back
-        in.  Returns (swap-out ticket, swap-in ticket)."""
+        """One turn of one Swap-state group, by the workload's swap directions:
+        "both": out, freed, allocated again (other blocks) and back in;
+        "out":  out (the requests entered their API call; the blocks stay listed for the next turn);
+        "in":   back in from the host image into freshly allocated blocks, the old ones freed
+                (the requests return from their API call).
+        Returns (swap-out ticket or None, swap-in ticket or None)."""
         lam = self.lam
         old, host = grp
+        if self.swap_mode == "out":
+            return lam.swap_out(old, host), None
         new = lam.alloc_blocks(len(old))                    # different physical blocks
-        t_out = lam.swap_out(old, host)
+        t_out = lam.swap_out(old, host) if self.swap_mode == "both" else None
         lam.free_blocks(old)
         t_in = lam.swap_in(host, new)
         grp[0] = new
@@ -234,10 +250,11 @@ class Job:
                 self.discard_ids[b] = lam.alloc_blocks(len(self.discard_ids[b]))
 
     def enqueue_swaps(self):
-        """One swap round, every group once, enqueued at once; returns the last swap-in ticket."""
+        """One swap round, every group once, enqueued at once; returns the last ticket."""
         last = None
         for grp in self.swap_groups:
-            last = self.swap_group(grp)[1]
+            t_out, t_in = self.swap_group(grp)
+            last = t_in if t_in is not None else t_out
         self.recycle_discards()
         return last
 
@@ -381,10 +398,12 @@ class SwapFeeder(threading.Thread):
 
         def retire():
             t_out, t_in, n = pend.popleft()
-            wait(t_out)
-            self.done.append((time.perf_counter(), True, n))
-            wait(t_in)
-            self.done.append((time.perf_counter(), False, n))
+            if t_out is not None:
+                wait(t_out)
+                self.done.append((time.perf_counter(), True, n))
+            if t_in is not None:
+                wait(t_in)
+                self.done.append((time.perf_counter(), False, n))
             self.first_done.set()
         try:
             while not self.stop:
@@ -685,7 +704,7 @@ def measure_config(a, cfg_id, headline):
     record for "per_config" (at least --steps steps and at least about 60 ms of them)."""
     import torch
     job = Job(cfg_id, a.rotations, a.part_tokens, a.table, a.ctx_override, a.geom, a.direct_copy_bytes, a.staging_mib,
-              a.zero_copy, a.ctx_long)
+              a.zero_copy, a.ctx_long, a.swap_directions)
     with_swap = not a.no_swap
     L = job.g.num_layers
 
@@ -744,6 +763,7 @@ def measure_config(a, cfg_id, headline):
             "num_blocks": job.g.num_blocks, "rotations": job.R,
             "part_tokens": int(job.cfg.part_tokens),
             "timing_rule": rule, "hip_graph": bool(graph), "clock_warmup_ms": a.clock_warmup_ms,
+            "swap_directions": job.swap_mode if with_swap else "none",
             "swap_bytes_each_way_per_round": 0 if not with_swap else job.swap_bytes,
             "swaps_in_flight_when_timed_steps_ended": under["swaps_in_flight_at_end"]}
     roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
